@@ -1,0 +1,106 @@
+"""Oracle of the stitched inference loop (test infrastructure; see package docstring).
+
+Algorithm 1 ("Inference procedure"): decoding starts on the small model; the
+active model first brings its own KV cache up to date with whatever part of
+prompt + output it has not processed (a prefill over that suffix; a plain
+decode step when the suffix is one token), which yields a next-token
+distribution and a token; the entropy of the distribution is compared with tau
+(Eq. 2); a small-model token with entropy above tau is thrown away and the same
+position is redone by the large model; a large-model token is always kept and
+control returns to the small model as soon as the large model's entropy is at
+or below tau.
+
+Position-explicit form used here: ``n_kv[m]`` is the number of tokens of
+prompt + output whose K/V rows model m holds.  The paper's cache-size counter
+L also counts the token just sampled, so L = n_kv + 1 after an accepted step,
+and its "rollback" of the small model's cache on a discard only drops that
+sampled token: the K/V rows written during the discarded step belong to
+tokens that were already accepted and stay valid.
+"""
+
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, List, Optional, Sequence, Tuple
+
+SLM, LLM = 0, 1
+
+
+@dataclass
+class Invocation:
+    model: int            # which model ran
+    pos0: int             # position of the first token of the span
+    span: List[int]       # tokens fed in (the suffix the model had not seen)
+    token: int            # token it produced
+    h_norm: float         # normalised entropy of its distribution
+    hi: bool              # h_norm > tau
+    accept: bool          # token appended to the output
+
+
+@dataclass
+class StitchResult:
+    output: List[int] = field(default_factory=list)
+    trace: List[Invocation] = field(default_factory=list)
+
+    @property
+    def n_llm_tokens(self) -> int:
+        return sum(1 for r in self.trace if r.accept and r.model == LLM)
+
+    @property
+    def n_rejected(self) -> int:
+        return sum(1 for r in self.trace if not r.accept)
+
+
+Forward = Callable[[int, List[int], int], Tuple[int, float]]
+
+
+def generate(prompt: Sequence[int], forward: Forward, tau: float, n_tokens: int,
+             eos: Optional[int] = None, max_invocations: Optional[int] = None) -> StitchResult:
+    """Run Algorithm 1 until ``n_tokens`` tokens have been accepted.
+
+    ``forward(model, span, pos0)`` runs model ``model`` over ``span`` placed at
+    positions pos0.., updating that model's cache, and returns the token it
+    proposes for position pos0+len(span) and the normalised entropy (Eq. 1) of
+    the distribution it was drawn from.
+    """
+    seq = list(prompt)
+    n_kv = [0, 0]
+    active = SLM
+    res = StitchResult()
+    while len(res.output) < n_tokens:
+        if max_invocations is not None and len(res.trace) >= max_invocations:
+            break
+        pos0 = n_kv[active]
+        span = seq[pos0:]
+        token, h = forward(active, span, pos0)
+        n_kv[active] = len(seq)
+        hi = h > tau
+        if active == SLM and hi:
+            res.trace.append(Invocation(active, pos0, span, token, h, True, False))
+            active = LLM                      # token discarded; the large model redoes this position
+            continue
+        res.trace.append(Invocation(active, pos0, span, token, h, hi, True))
+        if active == LLM and not hi:
+            active = SLM                      # token kept; hand back
+        seq.append(token)
+        res.output.append(token)
+        if eos is not None and token == eos:
+            break
+    return res
+
+
+def decoder_forward(models, scale_of_pos: Callable[[int], float], log: Optional[list] = None) -> Forward:
+    """Bind two ``oracle.decoder.OracleModel`` objects (index SLM, LLM) into the
+    ``forward`` callable of :func:`generate`.  ``scale_of_pos(p)`` is the logit
+    scale used when predicting the token at absolute position p.  When ``log``
+    is a list, the scaled logits of every invocation are appended to it."""
+    from . import router
+
+    def forward(model: int, span: List[int], pos0: int) -> Tuple[int, float]:
+        out = models[model].forward(span, pos0, logit_scale=scale_of_pos(pos0 + len(span)))
+        logits = out["logits"]
+        if log is not None:
+            log.append(logits)
+        return router.greedy_token(logits), router.normalised_entropy(logits)
+
+    return forward
