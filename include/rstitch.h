@@ -1,0 +1,193 @@
+/*
+ * rstitch.h - C ABI of the MI355X (gfx950) hot path of entropy-routed stitched
+ * decoding between a small and a large autoregressive decoder.
+ *
+ * What the paper defines and this library computes:
+ *   - the active model maps the tokens it has not processed yet to a next-token
+ *     distribution and a token (Section "Preliminary"; Algorithm 1, the
+ *     "Prefill" and "Decode" branches);
+ *   - the uncertainty of a step is the normalised entropy of that distribution
+ *     (Eq. 1) and the switching rule compares it with a threshold tau (Eq. 2);
+ *   - each model keeps its own KV cache and, when switched to, prefills only
+ *     the tokens produced since it last ran (Section "KV Cache management").
+ * The decoder layer itself (RMSNorm, rotary embedding, grouped-query attention
+ * over a KV cache, SwiGLU MLP, LM head; bf16 weights, fp32 accumulation) is the
+ * public Qwen2-style block; the paper treats it as "a full forward pass".
+ *
+ * General rules of this ABI
+ *   - Every pointer argument says whether it is HOST or DEVICE memory.  The
+ *     library never allocates or frees device memory: weights, KV caches,
+ *     workspace and outputs are owned by the caller and are only borrowed, for
+ *     the life time of the rs_model handle (weights, KV, workspace) or of the
+ *     call (everything else; "of the call" includes the asynchronous execution
+ *     on the stream).
+ *   - Calls that take a stream only enqueue work on it and return; results are
+ *     valid once the caller has synchronised that stream.  `stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).  Two calls that
+ *     use the same rs_model must not run concurrently.
+ *   - No call throws.  Every call returns an rs_status; on failure
+ *     rs_last_error() describes the most recent failure on the calling thread.
+ *   - Arguments the host can see (sizes, counts, null pointers) are checked
+ *     before anything is launched.  Values that live in device memory
+ *     (positions, token ids, slots) are checked by the kernels themselves: a
+ *     row whose position, token or slot is out of range is skipped without any
+ *     out-of-bounds access and RS_FLAG_BADARG is set in the output record of
+ *     its sequence.
+ *   - Layouts: all matrices are row-major [out_features, in_features], bf16.
+ */
+#ifndef RSTITCH_H
+#define RSTITCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t rs_status;
+#define RS_OK          0
+#define RS_EINVAL     (-1)  /* malformed argument (null pointer, bad shape, bad count)      */
+#define RS_ECAPACITY  (-2)  /* request exceeds what the model was created for               */
+#define RS_EHIP       (-3)  /* the HIP runtime reported an error (see rs_last_error)        */
+#define RS_ENOTIMPL   (-4)  /* valid request that this build does not support               */
+
+/* Which model of the stitched pair a call is made for (Algorithm 1's "active"). */
+#define RS_SLM 0
+#define RS_LLM 1
+
+/* rs_route_out.flags */
+#define RS_FLAG_HI         1u  /* normalised entropy > tau (strictly; Eq. 2)                         */
+#define RS_FLAG_ACCEPT     2u  /* the token is kept: always for the LLM, for the SLM only if !HI      */
+#define RS_FLAG_NEXT_LLM   4u  /* the model to run next is the LLM (== HI)                            */
+#define RS_FLAG_NONFINITE  8u  /* a logit was NaN/Inf; HI is forced, entropy fields are NaN           */
+#define RS_FLAG_BADARG    16u  /* a device-side position/token/slot was out of range; record invalid */
+
+typedef struct rs_config {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;    /* divides n_q_heads                                              */
+    int32_t head_dim;      /* 32, 64 or 128                                                  */
+    int32_t d_ffn;         /* multiple of 8                                                  */
+    int32_t vocab;         /* >= 2                                                           */
+    int32_t tied_lm_head;  /* informational; lm_head may simply alias embed                  */
+    int32_t max_ctx;       /* positions per sequence slot in the KV cache                    */
+    int32_t max_seqs;      /* sequence slots in the KV cache (1..8)                          */
+    int32_t max_rows;      /* most token rows one call may carry (1..64)                     */
+    float   rms_eps;
+    float   rope_theta;
+} rs_config;
+
+typedef struct rs_weights {
+    const void *embed;        /* DEVICE bf16 [vocab, d_model]                                 */
+    const void *lm_head;      /* DEVICE bf16 [vocab, d_model]                                 */
+    const void *final_norm;   /* DEVICE bf16 [d_model]                                        */
+    /* HOST arrays of n_layers DEVICE pointers each: */
+    const void *const *attn_norm;   /* bf16 [d_model]                                          */
+    const void *const *w_qkv;       /* bf16 [(n_q+2 n_kv) head_dim, d_model]: q heads, k heads, v heads */
+    const void *const *w_o;         /* bf16 [d_model, n_q head_dim]                            */
+    const void *const *mlp_norm;    /* bf16 [d_model]                                          */
+    const void *const *w_gate_up;   /* bf16 [2 d_ffn, d_model]: gate rows then up rows         */
+    const void *const *w_down;      /* bf16 [d_model, d_ffn]                                   */
+} rs_weights;
+
+/* Router record of one sequence for one call (24 bytes). */
+typedef struct rs_route_out {
+    int32_t  token;      /* argmax of the logits, lowest index among equals                  */
+    uint32_t flags;      /* RS_FLAG_*                                                        */
+    float    h_nats;     /* entropy of softmax(scaled logits), natural log                   */
+    float    h_norm;     /* h_nats / ln(vocab)  (Eq. 1)                                      */
+    float    max_logit;  /* largest scaled logit                                             */
+    float    log_z;      /* ln sum exp(scaled logits)                                        */
+} rs_route_out;
+
+typedef struct rs_model rs_model;   /* opaque host-side handle */
+
+/* Human-readable description of the last failure on this thread ("" if none). */
+const char *rs_last_error(void);
+
+/* ABI version of the loaded library (bumped on incompatible change). */
+int32_t rs_abi_version(void);
+
+/* Bytes of DEVICE workspace rs_create_model needs for this configuration
+ * (rotary table, activations of max_rows rows, attention and router partials).
+ * Returns 0 if the configuration is invalid. */
+size_t rs_workspace_bytes(const rs_config *cfg);
+
+/* Bytes of one KV buffer (K or V): n_layers * max_seqs * n_kv_heads * max_ctx *
+ * head_dim * 2.  Layout [layer][slot][kv_head][position][head_dim], bf16. */
+size_t rs_kv_bytes(const rs_config *cfg);
+
+/* Bind weights, KV caches and workspace into a handle.  Builds the rotary
+ * cos/sin table (computed in double on the host) inside the workspace with a
+ * synchronous copy; clears the workspace's counters.  kv_k, kv_v, workspace:
+ * DEVICE, 256-byte aligned, of at least rs_kv_bytes / rs_workspace_bytes.
+ * The KV contents are not touched.
+ * Errors: RS_EINVAL (null pointer, shape rule violated, workspace too small or
+ * misaligned), RS_EHIP. */
+rs_status rs_create_model(const rs_config *cfg, const rs_weights *weights,
+                          void *kv_k, void *kv_v,
+                          void *workspace, size_t workspace_bytes,
+                          rs_model **out);
+
+/* Frees the host handle only. */
+rs_status rs_destroy_model(rs_model *model);
+
+/* Algorithm 1, "Decode": one new token for each of n_seqs sequences
+ * (1 <= n_seqs <= min(max_seqs, max_rows)).
+ *   d_seq_slot    DEVICE int32[n_seqs]  KV slot of each sequence (distinct)
+ *   d_token       DEVICE int32[n_seqs]  the token to feed (the last accepted one)
+ *   d_pos         DEVICE int32[n_seqs]  its position; its K/V rows are written
+ *                                       there and attention covers 0..pos
+ *   d_logit_scale DEVICE fp32[n_seqs] or NULL (= 1): the logits are multiplied
+ *                                       by it before the softmax
+ *   tau, active   threshold of Eq. 2 (in normalised-entropy units) and which
+ *                 model this handle plays (RS_SLM / RS_LLM), for the flags
+ *   d_out         DEVICE (or pinned host) rs_route_out[n_seqs]
+ *   d_logits      DEVICE fp32[n_seqs, vocab] or NULL: scaled logits dump
+ * Errors: RS_EINVAL, RS_ECAPACITY (n_seqs too large), RS_EHIP. */
+rs_status rs_decode_step(rs_model *model, int32_t n_seqs,
+                         const int32_t *d_seq_slot, const int32_t *d_token,
+                         const int32_t *d_pos, const float *d_logit_scale,
+                         float tau, int32_t active,
+                         rs_route_out *d_out, float *d_logits, void *stream);
+
+/* Algorithm 1, "Prefill" of the unseen suffix (Section "KV Cache management"):
+ * for each sequence b, feed the span d_tokens[off[b] .. off[b+1]) at positions
+ * pos0[b], pos0[b]+1, ...; write the K/V rows of every span token; row i
+ * attends to cache positions 0 .. pos0[b]+i (causal); the router record is
+ * produced from the LAST row of each span.
+ *   n_rows        HOST value: total number of span tokens = off[n_seqs]
+ *                 (1 <= n_rows <= max_rows; every span has at least 1 token)
+ *   d_tokens      DEVICE int32[n_rows], spans packed back to back
+ *   d_span_offset DEVICE int32[n_seqs+1], off[0] = 0, non-decreasing
+ *   d_pos0        DEVICE int32[n_seqs]
+ *   d_logit_scale DEVICE fp32[n_seqs] or NULL
+ * A kernel that finds off[n_seqs] != n_rows, an empty span or a span running
+ * past max_ctx flags RS_FLAG_BADARG for that sequence and skips its rows.
+ * Errors: RS_EINVAL, RS_ECAPACITY (n_rows > max_rows, n_seqs > max_seqs), RS_EHIP. */
+rs_status rs_catchup_prefill(rs_model *model, int32_t n_seqs, int32_t n_rows,
+                             const int32_t *d_seq_slot, const int32_t *d_tokens,
+                             const int32_t *d_span_offset, const int32_t *d_pos0,
+                             const float *d_logit_scale,
+                             float tau, int32_t active,
+                             rs_route_out *d_out, float *d_logits, void *stream);
+
+/* Eq. 1 and Eq. 2 on caller-provided logits: for each of n rows of
+ * d_logits (DEVICE fp32 [n, vocab], row-major) compute, in one pass, the
+ * entropy of softmax(scale * logits), its normalised value, the argmax and the
+ * routing flags.  Same reduction code as the epilogue fused behind the LM head.
+ *   d_scratch / scratch_bytes  DEVICE scratch of at least
+ *                              rs_route_scratch_bytes(n, vocab), 256-byte aligned
+ * Errors: RS_EINVAL (n < 1, vocab < 2, null pointer, scratch too small). */
+size_t    rs_route_scratch_bytes(int32_t n, int32_t vocab);
+rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
+                   const float *d_logit_scale, float tau, int32_t active,
+                   rs_route_out *d_out, void *d_scratch, size_t scratch_bytes,
+                   void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSTITCH_H */

@@ -1,0 +1,35 @@
+"""Compile the HIP library for gfx950 in-tree (paper_2507_17307_amd/librstitch.so)."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "csrc", "rstitch.hip")
+LIB = os.path.join(HERE, "librstitch.so")
+
+FLAGS = [
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def build(verbose: bool = True) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + FLAGS + [SRC, "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    # the host pass does not know the packed-fp32 feature name and says so; that is harmless
+    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if err.strip() and verbose:
+        print(err, file=sys.stderr)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + err)
+    return LIB
+
+
+if __name__ == "__main__":
+    build()

@@ -1,0 +1,136 @@
+// Device helpers shared by the gfx950 kernels: bf16 packing, wave64 reductions,
+// and the single-pass softmax/entropy/argmax state with its associative merge.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define RS_WAVE 64
+
+namespace rs {
+
+// ---------------------------------------------------------------- bf16 <-> fp32
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// dot product of 8 bf16 weights (one 16-byte load) with 8 bf16 activations, fp32 accumulate
+__device__ __forceinline__ float dot8(const uint4 &w, const uint4 &x, float acc) {
+    acc = fmaf(bf16_lo(w.x), bf16_lo(x.x), acc);
+    acc = fmaf(bf16_hi(w.x), bf16_hi(x.x), acc);
+    acc = fmaf(bf16_lo(w.y), bf16_lo(x.y), acc);
+    acc = fmaf(bf16_hi(w.y), bf16_hi(x.y), acc);
+    acc = fmaf(bf16_lo(w.z), bf16_lo(x.z), acc);
+    acc = fmaf(bf16_hi(w.z), bf16_hi(x.z), acc);
+    acc = fmaf(bf16_lo(w.w), bf16_lo(x.w), acc);
+    acc = fmaf(bf16_hi(w.w), bf16_hi(x.w), acc);
+    return acc;
+}
+
+// streaming 16-byte load of weights that are read exactly once per step
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4 *p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// ---------------------------------------------------------------- wave64 reductions
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, RS_WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, RS_WAVE));
+    return v;
+}
+
+// ---------------------------------------------------------------- softmax / entropy / argmax in one pass
+// Carries m = max, z = sum e^(x-m), s = sum (x-m) e^(x-m), the running argmax
+// (lowest index among equal maxima) and whether a non-finite value was seen.
+// Entropy of softmax(x) in nats is ln z - s / z  (the quantity of Eq. 1 before
+// it is divided by ln V).  merge() is associative and commutative up to
+// rounding, so partial states can be combined in any tree.
+struct SoftState {
+    float m, z, s, best;
+    int idx, bad;
+
+    __device__ __forceinline__ void init() {
+        m = -INFINITY; z = 0.f; s = 0.f; best = -INFINITY; idx = 0x7fffffff; bad = 0;
+    }
+    __device__ __forceinline__ void push(float x, int i) {
+        if (!(fabsf(x) <= 3.0e38f)) { bad = 1; return; }     // NaN or +-Inf
+        if (x > best || (x == best && i < idx)) { best = x; idx = i; }
+        if (x > m) {
+            if (z > 0.f) { float d = m - x, e = expf(d); s = e * (s + d * z); z = z * e + 1.f; }
+            else { s = 0.f; z = 1.f; }
+            m = x;
+        } else {
+            float d = x - m, e = expf(d);
+            z += e; s = fmaf(d, e, s);
+        }
+    }
+    __device__ __forceinline__ void merge(const SoftState &o) {
+        bad |= o.bad;
+        if (o.best > best || (o.best == best && o.idx < idx)) { best = o.best; idx = o.idx; }
+        if (o.z <= 0.f) return;
+        if (z <= 0.f) { m = o.m; z = o.z; s = o.s; return; }
+        float mm = fmaxf(m, o.m);
+        float da = m - mm, db = o.m - mm;
+        float ea = expf(da), eb = expf(db);
+        s = ea * (s + da * z) + eb * (o.s + db * o.z);
+        z = z * ea + o.z * eb;
+        m = mm;
+    }
+};
+
+__device__ __forceinline__ SoftState shfl_xor_state(const SoftState &a, int o) {
+    SoftState b;
+    b.m = __shfl_xor(a.m, o, RS_WAVE);
+    b.z = __shfl_xor(a.z, o, RS_WAVE);
+    b.s = __shfl_xor(a.s, o, RS_WAVE);
+    b.best = __shfl_xor(a.best, o, RS_WAVE);
+    b.idx = __shfl_xor(a.idx, o, RS_WAVE);
+    b.bad = __shfl_xor(a.bad, o, RS_WAVE);
+    return b;
+}
+
+// all lanes end up with the merged state of the lanes that share the bits of
+// the lane id NOT covered by `span` (span = 64: whole wave; span = 16: groups of 16)
+__device__ __forceinline__ void wave_merge_state(SoftState &a, int span = RS_WAVE) {
+    for (int o = span >> 1; o > 0; o >>= 1) {
+        SoftState b = shfl_xor_state(a, o);
+        // merge in a fixed order (lower lane first) so that both partners compute the same bits
+        if ((threadIdx.x & o) == 0) { a.merge(b); }
+        else { b.merge(a); a = b; }
+    }
+}
+
+// What a workgroup (or wave) leaves in global memory for the final merge: 32 bytes.
+struct __align__(16) SoftPartial {
+    float m, z, s, best;
+    int idx, bad, pad0, pad1;
+};
+__device__ __forceinline__ SoftPartial to_partial(const SoftState &a) {
+    SoftPartial p; p.m = a.m; p.z = a.z; p.s = a.s; p.best = a.best; p.idx = a.idx; p.bad = a.bad; p.pad0 = 0; p.pad1 = 0;
+    return p;
+}
+__device__ __forceinline__ SoftState from_partial(const SoftPartial &p) {
+    SoftState a; a.m = p.m; a.z = p.z; a.s = p.s; a.best = p.best; a.idx = p.idx; a.bad = p.bad;
+    return a;
+}
+
+}  // namespace rs

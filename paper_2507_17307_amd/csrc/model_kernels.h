@@ -1,0 +1,441 @@
+// Decode-step kernels for one token row (batch 1): row table + embedding,
+// bandwidth-bound GEMV phases with fused prologues/epilogues, split-K GQA
+// decode attention with an in-kernel combine.  Wave64, 256-thread workgroups.
+#pragma once
+
+#include "device_utils.h"
+#include "router.h"
+
+namespace rs {
+
+// ------------------------------------------------------------------------------------------------
+// Row table.  One block per token row.  Turns the caller's per-sequence arrays into per-row
+// (slot, position, token, bad) entries, validates everything that lives in device memory, and
+// gathers the embedding row into the fp32 residual stream.
+//   decode:  n_seqs rows, row b = sequence b (span_off == nullptr)
+//   catchup: n_rows rows; row r belongs to the sequence b with off[b] <= r < off[b+1]
+// ------------------------------------------------------------------------------------------------
+struct PrepArgs {
+    int n_seqs, n_rows, d_model, vocab, max_ctx, max_seqs;
+    const int *seq_slot, *tokens, *span_off, *pos0;
+    const float *scale;
+    const uint16_t *embed;
+    int *row_slot, *row_pos, *row_bad, *out_row, *seq_bad;
+    float *seq_scale;
+    float *h;
+};
+
+__global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
+    const int r = blockIdx.x, tid = threadIdx.x;
+    __shared__ int sh[4];     // b, first row, last row (exclusive), bad
+    if (tid == 0) {
+        int b = -1, lo = 0, hi = 0, bad = 0;
+        if (a.span_off == nullptr) { b = r; lo = r; hi = r + 1; }
+        else {
+            if (a.span_off[0] != 0 || a.span_off[a.n_seqs] != a.n_rows) bad = 1;
+            for (int i = 0; i < a.n_seqs; ++i) {
+                int o0 = a.span_off[i], o1 = a.span_off[i + 1];
+                if (o1 <= o0 || o0 < 0 || o1 > a.n_rows) bad = 1;        // empty or malformed span
+                if (r >= o0 && r < o1 && b < 0) { b = i; lo = o0; hi = o1; }
+            }
+            if (b < 0) bad = 1;
+        }
+        if (!bad) {
+            int slot = a.seq_slot[b], p0 = a.pos0[b];
+            if (slot < 0 || slot >= a.max_seqs || p0 < 0 || p0 > a.max_ctx - (hi - lo)) bad = 1;
+            for (int i = 0; i < a.n_seqs && !bad; ++i)                   // slots must be distinct
+                if (i != b && a.seq_slot[i] == slot) bad = 1;
+            for (int i = lo; i < hi && !bad; ++i) {
+                int t = a.tokens[i];
+                if (t < 0 || t >= a.vocab) bad = 1;
+            }
+        }
+        sh[0] = b; sh[1] = lo; sh[2] = hi; sh[3] = bad;
+    }
+    __syncthreads();
+    const int b = sh[0], lo = sh[1], hi = sh[2], bad = sh[3];
+    if (tid == 0) {
+        a.row_bad[r] = bad;
+        a.row_slot[r] = bad ? 0 : a.seq_slot[b];
+        a.row_pos[r] = bad ? 0 : a.pos0[b] + (r - lo);
+        if (b >= 0 && r == hi - 1 && b < a.n_seqs) {
+            a.out_row[b] = r; a.seq_bad[b] = bad;
+            a.seq_scale[b] = a.scale ? a.scale[b] : 1.f;
+        }
+        // a malformed offset table can leave sequences without any row: flag them all
+        if (bad && a.span_off != nullptr && r == 0)
+            for (int i = 0; i < a.n_seqs; ++i) { a.seq_bad[i] = 1; a.out_row[i] = 0; a.seq_scale[i] = 1.f; }
+    }
+    float *h = a.h + (size_t)r * a.d_model;
+    if (bad) { for (int i = tid; i < a.d_model; i += 256) h[i] = 0.f; return; }
+    const uint16_t *e = a.embed + (size_t)a.tokens[r] * a.d_model;
+    for (int i = tid; i < a.d_model; i += 256) h[i] = bf16_to_f32(e[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// GEMV phases, one token row.  y[n] = sum_k W[n,k] x[k], W bf16 row-major streamed once from HBM
+// with 16-byte loads, x (bf16) staged in LDS, fp32 accumulation.  A wave owns RT rows at a time
+// (its lanes stride over K); with KS = 4 the four waves of a workgroup split K of the same rows
+// (for short, wide matrices).  Prologue and epilogue depend on the phase.
+// ------------------------------------------------------------------------------------------------
+enum { G_QKV = 0, G_OPROJ = 1, G_GATEUP = 2, G_DOWN = 3, G_LMHEAD = 4 };
+
+struct GemvArgs {
+    const uint16_t *W; int N, K;
+    // input: either the fp32 residual row with RMSNorm gains, or a ready bf16 vector
+    const float *h_in; const uint16_t *gain; float eps;
+    const uint16_t *x_in;
+    // outputs
+    float *h_out;                                    // residual stream (O-proj, down)
+    uint16_t *act;                                   // SwiGLU output (gate/up)
+    uint16_t *qbuf, *kcache, *vcache;                // QKV: rotated q (bf16) and the cache rows
+    const float *rope_cos, *rope_sin;                // [max_ctx, head_dim/2]
+    int n_q, n_kv, head_dim, max_ctx, max_seqs, layer, d_ffn;
+    const int *row_pos, *row_slot, *row_bad;
+    // LM head
+    const float *seq_scale; SoftPartial *parts; float *logits;
+};
+
+template <int RT>
+__device__ __forceinline__ void gemv_rows(const uint16_t *__restrict__ W, int K, const int (&rows)[RT],
+                                          const uint4 *__restrict__ xs, int c0, int cstride, float (&acc)[RT]) {
+    const int nch = K >> 3;
+    const uint4 *wp[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(W + (size_t)rows[r] * K); acc[r] = 0.f; }
+#pragma unroll 2
+    for (int c = c0; c < nch; c += cstride) {
+        uint4 wv[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
+        const uint4 xv = xs[c];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) acc[r] = dot8(wv[r], xv, acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+}
+
+template <int MODE, int RT, int KS>
+__global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4 *xs = reinterpret_cast<uint4 *>(smem);                  // K bf16
+    __shared__ float red[2][4][RT];
+    __shared__ float red_ss[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int K = a.K;
+
+    // ---- prologue: x into LDS as bf16
+    if (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD) {
+        const float2 *h2 = reinterpret_cast<const float2 *>(a.h_in);
+        float ss = 0.f;
+        for (int i = tid; i < (K >> 1); i += 256) { float2 v = h2[i]; ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); }
+        ss = wave_sum(ss);
+        if (lane == 0) red_ss[wave] = ss;
+        __syncthreads();
+        const float inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)K + a.eps);
+        uint32_t *x32 = reinterpret_cast<uint32_t *>(smem);
+        const uint32_t *g32 = reinterpret_cast<const uint32_t *>(a.gain);
+        for (int i = tid; i < (K >> 1); i += 256) {
+            float2 v = h2[i]; uint32_t g = g32[i];
+            x32[i] = pack_bf16x2(v.x * inv * bf16_lo(g), v.y * inv * bf16_hi(g));
+        }
+    } else {
+        const uint4 *xi = reinterpret_cast<const uint4 *>(a.x_in);
+        for (int i = tid; i < (K >> 3); i += 256) xs[i] = xi[i];
+    }
+    __syncthreads();
+
+    // ---- tiles
+    constexpr int P = RT / 2;
+    const int half = a.head_dim >> 1;
+    int n_tiles, n_rot_tiles = 0;
+    if (MODE == G_QKV) {
+        n_rot_tiles = (a.n_q + a.n_kv) * (half / P);
+        n_tiles = n_rot_tiles + (a.n_kv * a.head_dim) / RT;
+    } else if (MODE == G_GATEUP) {
+        n_tiles = a.d_ffn / P;
+    } else {
+        n_tiles = (a.N + RT - 1) / RT;
+    }
+    const int unit0 = (KS == 1) ? blockIdx.x * 4 + wave : blockIdx.x;
+    const int ustride = (KS == 1) ? gridDim.x * 4 : gridDim.x;
+    const int c0 = (KS == 1) ? lane : wave * 64 + lane;
+    const int cstride = 64 * KS;
+
+    SoftState st; st.init();
+    const float lm_scale = (MODE == G_LMHEAD) ? a.seq_scale[0] : 1.f;
+    int parity = 0;
+
+    for (int t = unit0; t < n_tiles; t += ustride) {
+        int rows[RT];
+        int head = 0, pair0 = 0; bool rot = false;
+        if (MODE == G_QKV) {
+            if (t < n_rot_tiles) {
+                rot = true; head = t / (half / P); pair0 = (t % (half / P)) * P;
+#pragma unroll
+                for (int j = 0; j < P; ++j) { rows[2 * j] = head * a.head_dim + pair0 + j; rows[2 * j + 1] = rows[2 * j] + half; }
+            } else {
+#pragma unroll
+                for (int j = 0; j < RT; ++j) rows[j] = (a.n_q + a.n_kv) * a.head_dim + (t - n_rot_tiles) * RT + j;
+            }
+        } else if (MODE == G_GATEUP) {
+#pragma unroll
+            for (int j = 0; j < P; ++j) { rows[2 * j] = t * P + j; rows[2 * j + 1] = a.d_ffn + t * P + j; }
+        } else {
+#pragma unroll
+            for (int j = 0; j < RT; ++j) rows[j] = min(t * RT + j, a.N - 1);
+        }
+        float acc[RT];
+        gemv_rows<RT>(a.W, K, rows, xs, c0, cstride, acc);
+        if (KS > 1) {
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < RT; ++r) red[parity][wave][r] = acc[r];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < RT; ++r) acc[r] = red[parity][0][r] + red[parity][1][r] + red[parity][2][r] + red[parity][3][r];
+            parity ^= 1;
+        }
+        const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
+        if (!writer) continue;
+
+        // ---- epilogue (one lane)
+        if (MODE == G_QKV) {
+            if (a.row_bad[0]) continue;
+            const int pos = a.row_pos[0], slot = a.row_slot[0];
+            if (rot) {
+                const float *cs = a.rope_cos + (size_t)pos * half, *sn = a.rope_sin + (size_t)pos * half;
+#pragma unroll
+                for (int j = 0; j < P; ++j) {
+                    const int i = pair0 + j;
+                    const float c = cs[i], s = sn[i], x0 = acc[2 * j], x1 = acc[2 * j + 1];
+                    const uint16_t y0 = f32_to_bf16(x0 * c - x1 * s), y1 = f32_to_bf16(x1 * c + x0 * s);
+                    if (head < a.n_q) {
+                        a.qbuf[head * a.head_dim + i] = y0; a.qbuf[head * a.head_dim + i + half] = y1;
+                    } else {
+                        const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + pos) * a.head_dim;
+                        a.kcache[base + i] = y0; a.kcache[base + i + half] = y1;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < RT; ++j) {
+                    const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
+                    const int vh = vr / a.head_dim, e = vr % a.head_dim;
+                    const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * a.max_ctx + pos) * a.head_dim;
+                    a.vcache[base + e] = f32_to_bf16(acc[j]);
+                }
+            }
+        } else if (MODE == G_GATEUP) {
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+                const float g = acc[2 * j], u = acc[2 * j + 1];
+                a.act[t * P + j] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+            }
+        } else if (MODE == G_OPROJ || MODE == G_DOWN) {
+#pragma unroll
+            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[t * RT + j] += acc[j];
+        } else {   // G_LMHEAD
+#pragma unroll
+            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
+                const float lg = acc[j] * lm_scale;
+                st.push(lg, t * RT + j);
+                if (a.logits) a.logits[t * RT + j] = lg;
+            }
+        }
+    }
+    if (MODE == G_LMHEAD) {
+        const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
+        if (writer) a.parts[(KS == 1) ? blockIdx.x * 4 + wave : blockIdx.x] = to_partial(st);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Split-K grouped-query decode attention.  grid (n_splits, n_kv_heads, n_rows), block 256.
+// A workgroup owns one KV head, one slice of the context and ALL query heads of that KV head's
+// group, so every K/V byte is read once per row.  Scores go through LDS (one exp per score);
+// running max / sum are carried across 256-token sub-chunks; the last workgroup to finish for a
+// (row, kv head) merges the slices and writes the bf16 attention output.
+// ------------------------------------------------------------------------------------------------
+struct AttnArgs {
+    const uint16_t *qbuf;          // [rows, n_q*hd] bf16, rotated
+    const uint16_t *kcache, *vcache;
+    float *partials;               // [rows, n_q, n_splits, hd+2]
+    int *counters;                 // [rows, n_kv], zero between launches
+    uint16_t *out;                 // [rows, n_q*hd] bf16
+    const int *row_pos, *row_slot, *row_bad;
+    int n_q, n_kv, max_ctx, max_seqs, layer;
+};
+
+constexpr int ATT_GMAX = 8;
+constexpr int ATT_TS = 256;
+
+template <int HD>
+__global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
+    constexpr int LPR = HD / 8, RPW = 64 / LPR, TPI = 4 * RPW;   // lanes per row, rows per wave-load, tokens per iteration
+    const int split = blockIdx.x, S = gridDim.x, kvh = blockIdx.y, row = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = a.n_q / a.n_kv;
+    const int sub_lane = lane % LPR, grp = lane / LPR, e0 = sub_lane * 8;
+
+    __shared__ float s_lds[ATT_GMAX][ATT_TS];
+    __shared__ float m_lds[ATT_GMAX], alpha_lds[ATT_GMAX];
+    __shared__ float accw[4][ATT_GMAX][HD + 1];
+    __shared__ float lw[4][ATT_GMAX];
+    __shared__ int last_flag;
+
+    const int ctx = a.row_bad[row] ? 0 : a.row_pos[row] + 1;
+    const int slot = a.row_bad[row] ? 0 : a.row_slot[row];
+    int C = (ctx + S - 1) / S;
+    C = ((C + TPI - 1) / TPI) * TPI;
+    const int t_begin = split * C;
+    const int t_end = min(ctx, t_begin + C);
+    const size_t kv_base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + kvh) * (size_t)a.max_ctx * HD;
+    const uint16_t *Kp = a.kcache + kv_base, *Vp = a.vcache + kv_base;
+    const float scale = 1.0f / sqrtf((float)HD);
+
+    float q[ATT_GMAX][8], acc[ATT_GMAX][8], l[ATT_GMAX];
+    if (tid < ATT_GMAX) m_lds[tid] = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < ATT_GMAX; ++g) {
+        l[g] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { acc[g][j] = 0.f; q[g][j] = 0.f; }
+        if (g < G) {
+            const uint4 qv = *reinterpret_cast<const uint4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + g) * HD + e0);
+            q[g][0] = bf16_lo(qv.x); q[g][1] = bf16_hi(qv.x); q[g][2] = bf16_lo(qv.y); q[g][3] = bf16_hi(qv.y);
+            q[g][4] = bf16_lo(qv.z); q[g][5] = bf16_hi(qv.z); q[g][6] = bf16_lo(qv.w); q[g][7] = bf16_hi(qv.w);
+        }
+    }
+
+    for (int sub = t_begin; sub < t_end; sub += ATT_TS) {
+        const int n_sub = min(ATT_TS, t_end - sub);
+        // scores
+        for (int it = 0; it * TPI < n_sub; ++it) {
+            const int tl = it * TPI + wave * RPW + grp;
+            float part[ATT_GMAX];
+#pragma unroll
+            for (int g = 0; g < ATT_GMAX; ++g) part[g] = 0.f;
+            if (tl < n_sub) {
+                const uint4 kv = *reinterpret_cast<const uint4 *>(Kp + (size_t)(sub + tl) * HD + e0);
+                const float k0 = bf16_lo(kv.x), k1 = bf16_hi(kv.x), k2 = bf16_lo(kv.y), k3 = bf16_hi(kv.y);
+                const float k4 = bf16_lo(kv.z), k5 = bf16_hi(kv.z), k6 = bf16_lo(kv.w), k7 = bf16_hi(kv.w);
+#pragma unroll
+                for (int g = 0; g < ATT_GMAX; ++g) {
+                    float p = q[g][0] * k0;
+                    p = fmaf(q[g][1], k1, p); p = fmaf(q[g][2], k2, p); p = fmaf(q[g][3], k3, p);
+                    p = fmaf(q[g][4], k4, p); p = fmaf(q[g][5], k5, p); p = fmaf(q[g][6], k6, p); p = fmaf(q[g][7], k7, p);
+                    part[g] = p;
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < ATT_GMAX; ++g) {
+#pragma unroll
+                for (int o = LPR >> 1; o > 0; o >>= 1) part[g] += __shfl_xor(part[g], o, RS_WAVE);
+            }
+            if (sub_lane == 0 && tl < n_sub) {
+#pragma unroll
+                for (int g = 0; g < ATT_GMAX; ++g) if (g < G) s_lds[g][tl] = part[g] * scale;
+            }
+        }
+        __syncthreads();
+        // sub-chunk maxima -> new running maxima and rescale factors (one wave per head)
+        for (int g = wave; g < G; g += 4) {
+            float mx = -INFINITY;
+            for (int i = lane; i < n_sub; i += 64) mx = fmaxf(mx, s_lds[g][i]);
+            mx = wave_max(mx);
+            if (lane == 0) {
+                const float m_old = m_lds[g], m_new = fmaxf(m_old, mx);
+                alpha_lds[g] = (m_old == -INFINITY) ? 0.f : expf(m_old - m_new);
+                m_lds[g] = m_new;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
+            const float alpha = alpha_lds[g];
+            l[g] *= alpha;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[g][j] *= alpha;
+        }
+        for (int i = tid; i < G * n_sub; i += 256) {
+            const int g = i / n_sub, tl = i - g * n_sub;
+            s_lds[g][tl] = expf(s_lds[g][tl] - m_lds[g]);
+        }
+        __syncthreads();
+        // P V
+        for (int it = 0; it * TPI < n_sub; ++it) {
+            const int tl = it * TPI + wave * RPW + grp;
+            if (tl < n_sub) {
+                const uint4 vv = *reinterpret_cast<const uint4 *>(Vp + (size_t)(sub + tl) * HD + e0);
+                const float v0 = bf16_lo(vv.x), v1 = bf16_hi(vv.x), v2 = bf16_lo(vv.y), v3 = bf16_hi(vv.y);
+                const float v4 = bf16_lo(vv.z), v5 = bf16_hi(vv.z), v6 = bf16_lo(vv.w), v7 = bf16_hi(vv.w);
+#pragma unroll
+                for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
+                    const float p = s_lds[g][tl];
+                    l[g] += p;
+                    acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
+                    acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
+                    acc[g][4] = fmaf(p, v4, acc[g][4]); acc[g][5] = fmaf(p, v5, acc[g][5]);
+                    acc[g][6] = fmaf(p, v6, acc[g][6]); acc[g][7] = fmaf(p, v7, acc[g][7]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // reduce over the token groups inside the wave (lanes with equal sub_lane), then over waves
+#pragma unroll
+    for (int g = 0; g < ATT_GMAX; ++g) {
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) {
+            l[g] += __shfl_xor(l[g], o, RS_WAVE);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[g][j] += __shfl_xor(acc[g][j], o, RS_WAVE);
+        }
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) accw[wave][g][e0 + j] = acc[g][j];
+            if (sub_lane == 0) lw[wave][g] = l[g];
+        }
+    }
+    __syncthreads();
+    const int PS = HD + 2;
+    for (int i = tid; i < G * HD; i += 256) {
+        const int g = i / HD, e = i - g * HD;
+        const float v = accw[0][g][e] + accw[1][g][e] + accw[2][g][e] + accw[3][g][e];
+        float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
+        p[2 + e] = v;
+        if (e == 0) { p[0] = m_lds[g]; p[1] = lw[0][g] + lw[1][g] + lw[2][g] + lw[3][g]; }
+    }
+    // completion ticket
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int old = atomicAdd(&a.counters[row * a.n_kv + kvh], 1);
+        last_flag = (old == S - 1);
+    }
+    __syncthreads();
+    if (!last_flag) return;
+    __threadfence();
+    for (int i = tid; i < G * HD; i += 256) {
+        const int g = i / HD, e = i - g * HD;
+        const float *p = a.partials + ((size_t)row * a.n_q + kvh * G + g) * S * PS;
+        float M = -INFINITY;
+        for (int s = 0; s < S; ++s) if (p[s * PS + 1] > 0.f) M = fmaxf(M, p[s * PS]);
+        float L = 0.f, O = 0.f;
+        for (int s = 0; s < S; ++s) {
+            const float ls = p[s * PS + 1];
+            if (ls > 0.f) { const float w = expf(p[s * PS] - M); L = fmaf(ls, w, L); O = fmaf(p[s * PS + 2 + e], w, O); }
+        }
+        a.out[((size_t)row * a.n_q + kvh * G + g) * HD + e] = f32_to_bf16(L > 0.f ? O / L : 0.f);
+    }
+    if (tid == 0) a.counters[row * a.n_kv + kvh] = 0;
+}
+
+}  // namespace rs

@@ -1,0 +1,173 @@
+"""GPU parity of rs_decode_step / rs_catchup_prefill against the oracle, through the C ABI.
+
+The oracle's token sequence and routing decisions are teacher-forced: the GPU replays the
+oracle's invocations and its outputs are never fed forward.
+"""
+import math
+
+import pytest
+import torch
+
+import workloads as W
+from oracle import decoder, router, stitch
+from workloads.recipes import misc_normal
+from parity import check_invocation
+
+pytestmark = pytest.mark.gpu
+
+
+def pair_run(wl, n_tokens=None):
+    """Oracle run of a stitched workload; returns weights, trace, logits per invocation, tau, scales."""
+    ws, wl_ = W.make_weights(wl.slm, wl.seed, 0), W.make_weights(wl.llm, wl.seed, 1)
+    prompt = W.make_prompt(wl).tolist()
+    n = wl.n_decode if n_tokens is None else n_tokens
+    scales = W.logit_scale(wl, 0, wl.max_ctx + 1)
+    mk = lambda: [decoder.OracleModel(ws, wl.max_ctx + 1), decoder.OracleModel(wl_, wl.max_ctx + 1)]  # noqa: E731
+    sc = lambda p: float(scales[p])  # noqa: E731
+    hs = [t.h_norm for t in stitch.generate(prompt, stitch.decoder_forward(mk(), sc), 2.0, n).trace]
+    tau = W.pick_tau(hs, wl.tau_percentile, 4e-3 / math.log(wl.slm.vocab))
+    log = []
+    models = mk()
+    res = stitch.generate(prompt, stitch.decoder_forward(models, sc, log), tau, n)
+    return (ws, wl_), models, res, log, tau, scales
+
+
+def test_config1_tiny_pair_teacher_forced():
+    import paper_2507_17307_amd as P
+    wl = W.WORKLOADS["cfg1_tiny_pair"]
+    weights, oracle_models, res, ref_logits, tau, scales = pair_run(wl)
+    assert 0 < res.n_llm_tokens < wl.n_decode and res.n_rejected > 0
+    gpu = [P.Model(w.to("cuda"), max_ctx=wl.max_ctx + 1, max_rows=64) for w in weights]
+    for i, inv in enumerate(res.trace):
+        got, lg = gpu[inv.model].forward_span(inv.span, inv.pos0, tau, inv.model,
+                                              float(scales[inv.pos0 + len(inv.span)]), want_logits=True)
+        torch.cuda.synchronize()
+        want = check_invocation(got[0], lg[0], ref_logits[i], tau, inv.model, where=f"invocation {i} {inv.model} span {len(inv.span)}")
+        assert bool(want["flags"] & 2) == inv.accept
+    # the caches the two sides built agree to bf16 rounding of nearly equal fp32 values
+    for m in (0, 1):
+        n = len(W.make_prompt(wl)) + wl.n_decode - 1
+        for name, ref in (("k", oracle_models[m].k_cache), ("v", oracle_models[m].v_cache)):
+            g = gpu[m].kv_view(name)[:, 0, :, :n].float().cpu().double()
+            r = ref[:, 0, :, :n]
+            assert float((g - r).abs().max()) <= 2 ** -7 * float(r.abs().max()) + 1e-6
+
+
+def test_catchup_equals_sequential_decode_on_gpu():
+    import paper_2507_17307_amd as P
+    w = W.make_weights(W.TINY_L, 3, 1).to("cuda")
+    toks = W.rng.randint(3, 77, 0, 40, 1024).tolist()
+    a, b = P.Model(w, 64), P.Model(w, 64)
+    ra, la = a.forward_span(toks[:23], 0, 0.5, P.RS_LLM, 2.0, want_logits=True)
+    ra, la = a.forward_span(toks[23:], 23, 0.5, P.RS_LLM, 2.0, want_logits=True)
+    for i, t in enumerate(toks):
+        rb, lb = b.forward_span([t], i, 0.5, P.RS_LLM, 2.0, want_logits=True)
+    torch.cuda.synchronize()
+    assert float((la - lb).abs().max()) <= 2e-2
+    assert abs(ra[0].h_nats - rb[0].h_nats) <= 1e-3 and ra[0].token == rb[0].token
+    ka, kb = a.kv_view("k").float(), b.kv_view("k").float()
+    assert float((ka - kb).abs().max()) <= 2 ** -7 * float(ka.abs().max())
+
+
+@pytest.mark.parametrize("spans", [[1, 1, 1], [3, 1, 17, 2], [16, 16, 16, 16], [5, 33, 1, 1, 1, 1, 1, 2]])
+def test_batched_ragged_calls_match_per_sequence_oracle(spans):
+    """Several sequences in one call (ragged spans, distinct slots) against one oracle model per slot."""
+    import paper_2507_17307_amd as P
+    shape = W.TINY_L
+    w = W.make_weights(shape, 4, 1)
+    n = len(spans)
+    gpu = P.Model(w.to("cuda"), max_ctx=96, max_seqs=8, max_rows=64)
+    refs = [decoder.OracleModel(w, 96) for _ in range(n)]
+    slots = [(3 * i + 1) % 8 for i in range(n)]
+    pre = [7 + 5 * i for i in range(n)]                       # every sequence already holds a different prefix
+    toks = [W.rng.randint(4, 200 + i, 0, pre[i] + spans[i] + 1, shape.vocab).tolist() for i in range(n)]
+    for i in range(n):
+        refs[i].forward(toks[i][:pre[i]], 0)
+        gpu.forward_span(toks[i][:pre[i]], 0, 0.5, P.RS_LLM, slot=slots[i])
+    scales = [1.0 + i for i in range(n)]
+    got, lg = gpu.catchup_prefill([toks[i][pre[i]:pre[i] + spans[i]] for i in range(n)], pre, 0.7, P.RS_LLM,
+                                  scales, slots, want_logits=True)
+    torch.cuda.synchronize()
+    for i in range(n):
+        ref = refs[i].forward(toks[i][pre[i]:pre[i] + spans[i]], pre[i], logit_scale=scales[i])["logits"]
+        check_invocation(got[i], lg[i], ref, 0.7, router.LLM, where=f"seq {i}")
+    # then one batched decode step for all of them
+    nxt = [toks[i][pre[i] + spans[i]] for i in range(n)]
+    pos = [pre[i] + spans[i] for i in range(n)]
+    got, lg = gpu.decode_step(nxt, pos, 0.7, P.RS_SLM, scales, slots, want_logits=True)
+    torch.cuda.synchronize()
+    for i in range(n):
+        ref = refs[i].forward([nxt[i]], pos[i], logit_scale=scales[i])["logits"]
+        check_invocation(got[i], lg[i], ref, 0.7, router.SLM, where=f"decode seq {i}")
+
+
+def test_device_side_argument_errors_are_flagged_not_faulted():
+    import paper_2507_17307_amd as P
+    w = W.make_weights(W.TINY_S, 5, 0).to("cuda")
+    m = P.Model(w, max_ctx=16, max_seqs=2, max_rows=8)
+    ok = m.decode_step([3], [0], 0.5, P.RS_SLM)
+    assert not ok[0].flags & P.FLAG_BADARG
+    assert m.decode_step([3], [16], 0.5, P.RS_SLM)[0].flags & P.FLAG_BADARG          # position beyond the cache
+    assert m.decode_step([3], [-1], 0.5, P.RS_SLM)[0].flags & P.FLAG_BADARG
+    assert m.decode_step([1024], [1], 0.5, P.RS_SLM)[0].flags & P.FLAG_BADARG        # token out of vocabulary
+    assert m.decode_step([3], [1], 0.5, P.RS_SLM, slots=[2])[0].flags & P.FLAG_BADARG  # slot out of range
+    r = m.decode_step([3, 4], [1, 1], 0.5, P.RS_SLM, slots=[1, 1])                    # duplicate slots
+    assert r[0].flags & P.FLAG_BADARG and r[1].flags & P.FLAG_BADARG
+    r = m.catchup_prefill([[1, 2, 3]], [14], 0.5, P.RS_SLM)                           # span runs past max_ctx
+    assert r[0].flags & P.FLAG_BADARG
+    r = m.catchup_prefill([[1, 2, 3], [4]], [0, 0], 0.5, P.RS_SLM)                    # one good, one good
+    assert not (r[0].flags | r[1].flags) & P.FLAG_BADARG
+    with pytest.raises(P.RsError):
+        m.catchup_prefill([[1] * 9], [0], 0.5, P.RS_SLM)                               # more rows than max_rows
+    with pytest.raises(P.RsError):
+        m.decode_step([1, 2, 3], [0, 0, 0], 0.5, P.RS_SLM)                             # more sequences than max_seqs
+    torch.cuda.synchronize()
+
+
+def synthetic_cache(gpu, ref, n_ctx, seed):
+    """Fill positions [0, n_ctx) of slot 0 of both caches with the same bf16 noise."""
+    c = gpu.cfg
+    shape = (c.n_layers, c.n_kv_heads, n_ctx, c.head_dim)
+    cnt = c.n_layers * c.n_kv_heads * n_ctx * c.head_dim
+    for which, tag in (("k", 1), ("v", 2)):
+        vals = torch.empty(cnt, dtype=torch.bfloat16)
+        step = 1 << 22
+        for s in range(0, cnt, step):
+            vals[s:s + step] = W.rng.normal(seed, 900 + tag, s, min(step, cnt - s)).to(torch.float32).to(torch.bfloat16)
+        vals = vals.view(shape)
+        gpu.kv_view(which)[:, 0, :, :n_ctx] = vals.cuda()
+        cache = ref.k_cache if which == "k" else ref.v_cache
+        cache[:, 0, :, :n_ctx] = vals.double()
+
+
+FULL_SHAPES = [
+    # (shape, layers kept, context already cached, spans to run)
+    ("s15", W.S15, 28, 2559 - 8, [1, 7]),
+    ("m7", W.M7, 28, 4607 - 40, [1, 2, 37]),
+    ("m14_4layers", W.ModelShape("m14_4", 4, 5120, 40, 8, 128, 13824, 152064, False), 4, 9215 - 20, [1, 19]),
+    ("m32_2layers", W.ModelShape("m32_2", 2, 5120, 40, 8, 128, 27648, 152064, False), 2, 10239 - 70, [1, 64, 5]),
+]
+
+
+@pytest.mark.parametrize("name,shape,n_layers,n_ctx,spans", FULL_SHAPES, ids=[f[0] for f in FULL_SHAPES])
+def test_full_size_shapes_at_full_context(name, shape, n_layers, n_ctx, spans):
+    """Full layer dimensions, vocabulary and context length of configs 2-5.  The KV cache is
+    pre-filled with seeded noise on both sides (the oracle cannot afford a 4k-10k token prefill),
+    then decode steps and catch-up spans run on top of it."""
+    import paper_2507_17307_amd as P
+    w_gpu = W.make_weights(shape, seed=11, role=1, device="cuda")
+    w_cpu = w_gpu.to("cpu")
+    max_ctx = n_ctx + sum(spans) + 1
+    gpu = P.Model(w_gpu, max_ctx=max_ctx, max_rows=64)
+    ref = decoder.OracleModel(w_cpu, max_ctx, keep_fp64_weights=(shape.d_model <= 1536))
+    synthetic_cache(gpu, ref, n_ctx, seed=12)
+    toks = W.rng.randint(13, 5, 0, sum(spans), shape.vocab).tolist()
+    pos, tau = n_ctx, 0.5
+    for k, span in enumerate(spans):
+        chunk, toks = toks[:span], toks[span:]
+        scale = 2.0 + 1.5 * k
+        out = ref.forward(chunk, pos, logit_scale=scale)["logits"]
+        got, lg = gpu.forward_span(chunk, pos, tau, P.RS_LLM, scale, want_logits=True)
+        torch.cuda.synchronize()
+        check_invocation(got[0], lg[0], out, tau, router.LLM, where=f"{name} span {span} at {pos}")
+        pos += span
