@@ -8,12 +8,21 @@ Qwen2-style decoder block: pre-RMSNorm, grouped-query attention with rotary
 position embedding (rotate-half pairing), SwiGLU MLP, residual connections,
 final RMSNorm and a linear LM head (tied to the embedding or not).  No biases.
 
-Arithmetic: fp64 everywhere.  With ``contract=True`` the values are rounded to
-bf16 (via fp32, round to nearest even) at the points where the bf16 pipeline
-rounds them: every matmul input activation, the rotated key and the value as
-stored in the KV cache.  With ``contract=False`` nothing is rounded, which
-makes the function the textbook decoder and lets a test compare it with an
-independent library implementation.
+Arithmetic: fp64 everywhere.  The weights are bf16 values (inputs).  With
+``contract=True`` the rotated key and the value are rounded to bf16 (via fp32,
+round to nearest even) when they are stored in the KV cache, which is the one
+place where the pipeline keeps an activation in bf16; every other activation
+(residual stream, normalised inputs, queries, attention probabilities and
+outputs, MLP activations, logits) stays unrounded.  With ``contract=False``
+nothing is rounded, which makes the function the textbook decoder and lets a
+test compare it with an independent library implementation.
+
+Why no other rounding point: rounding an activation to bf16 turns a relative
+difference delta between two otherwise equivalent computations (fp32 versus
+fp64 accumulation, a different summation order) into sqrt(delta * 2^-8), and a
+chain of such roundings drives it up to the bf16 step itself within a couple of
+layers; logits of two correct implementations would then differ by ~1e-2 and
+no entropy or argmax tolerance finer than that could be met by anyone.
 """
 
 from __future__ import annotations
@@ -119,7 +128,7 @@ class OracleModel:
         hq, hkv, hd = s.n_q_heads, s.n_kv_heads, s.head_dim
         h = self._f64("embed", self.w.embed)[list(tokens)].clone()          # [n, d]
         for l, lw in enumerate(self.w.layers):
-            x = self._r(rmsnorm(h, self._f64((l, "an"), lw.attn_norm), s.rms_eps))
+            x = rmsnorm(h, self._f64((l, "an"), lw.attn_norm), s.rms_eps)
             qkv = x @ self._f64((l, "qkv"), lw.w_qkv).T                         # [n, (Hq+2Hkv) hd]
             q = qkv[:, :hq * hd].reshape(n, hq, hd)
             k = qkv[:, hq * hd:(hq + hkv) * hd].reshape(n, hkv, hd)
@@ -129,15 +138,15 @@ class OracleModel:
                 self.v_cache[l, slot, :, pos0 + i] = self._r(v[i])
             o = torch.empty(n, hq * hd, dtype=F64)
             for i in range(n):
-                qi = self._r(rope(q[i], pos0 + i, s.rope_theta))
+                qi = rope(q[i], pos0 + i, s.rope_theta)
                 ctx = pos0 + i + 1
                 o[i] = attention(qi, self.k_cache[l, slot, :, :ctx], self.v_cache[l, slot, :, :ctx]).reshape(-1)
-            h = h + self._r(o) @ self._f64((l, "o"), lw.w_o).T
-            x = self._r(rmsnorm(h, self._f64((l, "mn"), lw.mlp_norm), s.rms_eps))
+            h = h + o @ self._f64((l, "o"), lw.w_o).T
+            x = rmsnorm(h, self._f64((l, "mn"), lw.mlp_norm), s.rms_eps)
             gu = x @ self._f64((l, "gu"), lw.w_gate_up).T                       # [n, 2 ffn]
-            a = self._r(silu(gu[:, :s.d_ffn]) * gu[:, s.d_ffn:])
+            a = silu(gu[:, :s.d_ffn]) * gu[:, s.d_ffn:]
             h = h + a @ self._f64((l, "dn"), lw.w_down).T
-        x_last = self._r(rmsnorm(h[-1], self._f64("fn", self.w.final_norm), s.rms_eps))
+        x_last = rmsnorm(h[-1], self._f64("fn", self.w.final_norm), s.rms_eps)
         lm = self._f64("embed", self.w.embed) if s.tied_lm_head else self._f64("lm", self.w.lm_head)
         logits = (lm @ x_last) * float(logit_scale)
         out = dict(logits=logits)

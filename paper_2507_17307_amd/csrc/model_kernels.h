@@ -73,78 +73,103 @@ __global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// GEMV phases, one token row.  y[n] = sum_k W[n,k] x[k], W bf16 row-major streamed once from HBM
-// with 16-byte loads, x (bf16) staged in LDS, fp32 accumulation.  A wave owns RT rows at a time
-// (its lanes stride over K); with KS = 4 the four waves of a workgroup split K of the same rows
-// (for short, wide matrices).  Prologue and epilogue depend on the phase.
+// GEMV phases, one token row.  y[n] = sum_k W[n,k] x[k]: W is bf16, row-major, streamed once from
+// HBM with 16-byte non-temporal loads; x is fp32 and staged in LDS; accumulation is fp32.
+// A wave owns RT rows at a time and its lanes stride over K (KS = 1); with KS = 4 the four waves
+// of a workgroup split K of the same rows (short, wide matrices).  When K exceeds the LDS segment
+// the workgroup walks K in segments, restaging x (KS = 4 only, one tile per workgroup).
+// Prologue and epilogue depend on the phase:
+//   G_QKV     x = RMSNorm(h);  rows come in rotary pairs (i, i + hd/2); epilogue rotates q and k,
+//             writes q (fp32) and the bf16 K/V rows of this position into the cache
+//   G_OPROJ   x = attention output;  h += y
+//   G_GATEUP  x = RMSNorm(h);  rows come in (gate i, up i) pairs; act[i] = silu(gate) * up
+//   G_DOWN    x = act;  h += y
+//   G_LMHEAD  x = RMSNorm(h);  logit = y * scale feeds the single-pass softmax state of the wave
 // ------------------------------------------------------------------------------------------------
 enum { G_QKV = 0, G_OPROJ = 1, G_GATEUP = 2, G_DOWN = 3, G_LMHEAD = 4 };
 
+constexpr int GEMV_KSEG = 12288;     // fp32 elements of x held in LDS at a time (48 KB)
+
 struct GemvArgs {
     const uint16_t *W; int N, K;
-    // input: either the fp32 residual row with RMSNorm gains, or a ready bf16 vector
-    const float *h_in; const uint16_t *gain; float eps;
-    const uint16_t *x_in;
-    // outputs
-    float *h_out;                                    // residual stream (O-proj, down)
-    uint16_t *act;                                   // SwiGLU output (gate/up)
-    uint16_t *qbuf, *kcache, *vcache;                // QKV: rotated q (bf16) and the cache rows
-    const float *rope_cos, *rope_sin;                // [max_ctx, head_dim/2]
+    const float *h_in; const uint16_t *gain; float eps;   // RMSNorm input (norm phases)
+    const float *x_in;                                    // ready fp32 vector (other phases)
+    float *h_out;                                         // residual stream (O-proj, down)
+    float *act;                                           // SwiGLU output (gate/up)
+    float *qbuf; uint16_t *kcache, *vcache;               // QKV outputs
+    const float *rope_cos, *rope_sin;                     // [max_ctx, head_dim/2]
     int n_q, n_kv, head_dim, max_ctx, max_seqs, layer, d_ffn;
     const int *row_pos, *row_slot, *row_bad;
-    // LM head
-    const float *seq_scale; SoftPartial *parts; float *logits;
+    const float *seq_scale; SoftPartial *parts; float *logits;   // LM head
 };
 
+// 8 bf16 weights times 8 fp32 activations
+__device__ __forceinline__ float dot8f(const uint4 &w, const float4 &xa, const float4 &xb, float acc) {
+    acc = fmaf(bf16_lo(w.x), xa.x, acc); acc = fmaf(bf16_hi(w.x), xa.y, acc);
+    acc = fmaf(bf16_lo(w.y), xa.z, acc); acc = fmaf(bf16_hi(w.y), xa.w, acc);
+    acc = fmaf(bf16_lo(w.z), xb.x, acc); acc = fmaf(bf16_hi(w.z), xb.y, acc);
+    acc = fmaf(bf16_lo(w.w), xb.z, acc); acc = fmaf(bf16_hi(w.w), xb.w, acc);
+    return acc;
+}
+
+// accumulate chunks [c_begin, c_end) of the rows; xs holds the segment starting at chunk seg_c0 as
+// two float4 planes (first and second half of every 8-element chunk) of plane_len chunks each
 template <int RT>
-__device__ __forceinline__ void gemv_rows(const uint16_t *__restrict__ W, int K, const int (&rows)[RT],
-                                          const uint4 *__restrict__ xs, int c0, int cstride, float (&acc)[RT]) {
-    const int nch = K >> 3;
-    const uint4 *wp[RT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(W + (size_t)rows[r] * K); acc[r] = 0.f; }
+__device__ __forceinline__ void gemv_accumulate(const uint4 *const (&wp)[RT], const float4 *__restrict__ xs, int plane_len,
+                                                int seg_c0, int c_begin, int c_end, int cstride, float (&acc)[RT]) {
 #pragma unroll 2
-    for (int c = c0; c < nch; c += cstride) {
+    for (int c = c_begin; c < c_end; c += cstride) {
         uint4 wv[RT];
 #pragma unroll
         for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
-        const uint4 xv = xs[c];
+        const float4 xa = xs[c - seg_c0], xb = xs[plane_len + c - seg_c0];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) acc[r] = dot8(wv[r], xv, acc[r]);
+        for (int r = 0; r < RT; ++r) acc[r] = dot8f(wv[r], xa, xb, acc[r]);
     }
-#pragma unroll
-    for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
 }
 
 template <int MODE, int RT, int KS>
 __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint4 *xs = reinterpret_cast<uint4 *>(smem);                  // K bf16
+    float4 *xs = reinterpret_cast<float4 *>(smem);
     __shared__ float red[2][4][RT];
     __shared__ float red_ss[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int K = a.K;
+    const int seg = K < GEMV_KSEG ? K : GEMV_KSEG;       // elements per LDS segment
+    const int plane_len = seg >> 3;
+    const bool resident = K <= GEMV_KSEG;
+    constexpr bool NORM = (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD);
 
-    // ---- prologue: x into LDS as bf16
-    if (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD) {
-        const float2 *h2 = reinterpret_cast<const float2 *>(a.h_in);
+    float inv = 1.f;
+    if (NORM) {
+        const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in);
         float ss = 0.f;
-        for (int i = tid; i < (K >> 1); i += 256) { float2 v = h2[i]; ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); }
+        for (int i = tid; i < (K >> 2); i += 256) {
+            const float4 v = h4[i];
+            ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+        }
         ss = wave_sum(ss);
         if (lane == 0) red_ss[wave] = ss;
         __syncthreads();
-        const float inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)K + a.eps);
-        uint32_t *x32 = reinterpret_cast<uint32_t *>(smem);
-        const uint32_t *g32 = reinterpret_cast<const uint32_t *>(a.gain);
-        for (int i = tid; i < (K >> 1); i += 256) {
-            float2 v = h2[i]; uint32_t g = g32[i];
-            x32[i] = pack_bf16x2(v.x * inv * bf16_lo(g), v.y * inv * bf16_hi(g));
-        }
-    } else {
-        const uint4 *xi = reinterpret_cast<const uint4 *>(a.x_in);
-        for (int i = tid; i < (K >> 3); i += 256) xs[i] = xi[i];
+        inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)K + a.eps);
     }
-    __syncthreads();
+    // stage the K-range [k0, k0+len) of x: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
+    auto stage = [&](int k0, int len) {
+        if (NORM) {
+            const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in + k0);
+            const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain + k0);
+            for (int i = tid; i < (len >> 2); i += 256) {
+                float4 v = h4[i]; const uint2 g = g2[i];
+                v.x *= inv * bf16_lo(g.x); v.y *= inv * bf16_hi(g.x); v.z *= inv * bf16_lo(g.y); v.w *= inv * bf16_hi(g.y);
+                xs[(i & 1) * plane_len + (i >> 1)] = v;
+            }
+        } else {
+            const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in + k0);
+            for (int i = tid; i < (len >> 2); i += 256) xs[(i & 1) * plane_len + (i >> 1)] = x4[i];
+        }
+    };
+    if (resident) { stage(0, K); __syncthreads(); }
 
     // ---- tiles
     constexpr int P = RT / 2;
@@ -186,8 +211,23 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 #pragma unroll
             for (int j = 0; j < RT; ++j) rows[j] = min(t * RT + j, a.N - 1);
         }
+        const uint4 *wp[RT];
         float acc[RT];
-        gemv_rows<RT>(a.W, K, rows, xs, c0, cstride, acc);
+#pragma unroll
+        for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K); acc[r] = 0.f; }
+        if (resident) {
+            gemv_accumulate<RT>(wp, xs, plane_len, 0, c0, K >> 3, cstride, acc);
+        } else {
+            for (int k0 = 0; k0 < K; k0 += GEMV_KSEG) {        // KS == 4 only: the tile loop is workgroup-uniform
+                const int len = min(GEMV_KSEG, K - k0);
+                __syncthreads();
+                stage(k0, len);
+                __syncthreads();
+                gemv_accumulate<RT>(wp, xs, plane_len, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, cstride, acc);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
         if (KS > 1) {
             if (lane == 0) {
 #pragma unroll
@@ -211,12 +251,12 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
                 for (int j = 0; j < P; ++j) {
                     const int i = pair0 + j;
                     const float c = cs[i], s = sn[i], x0 = acc[2 * j], x1 = acc[2 * j + 1];
-                    const uint16_t y0 = f32_to_bf16(x0 * c - x1 * s), y1 = f32_to_bf16(x1 * c + x0 * s);
+                    const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
                     if (head < a.n_q) {
                         a.qbuf[head * a.head_dim + i] = y0; a.qbuf[head * a.head_dim + i + half] = y1;
                     } else {
                         const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + pos) * a.head_dim;
-                        a.kcache[base + i] = y0; a.kcache[base + i + half] = y1;
+                        a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
                     }
                 }
             } else {
@@ -232,7 +272,7 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 #pragma unroll
             for (int j = 0; j < P; ++j) {
                 const float g = acc[2 * j], u = acc[2 * j + 1];
-                a.act[t * P + j] = f32_to_bf16(g / (1.0f + expf(-g)) * u);
+                a.act[t * P + j] = g / (1.0f + expf(-g)) * u;
             }
         } else if (MODE == G_OPROJ || MODE == G_DOWN) {
 #pragma unroll
@@ -257,14 +297,15 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 // A workgroup owns one KV head, one slice of the context and ALL query heads of that KV head's
 // group, so every K/V byte is read once per row.  Scores go through LDS (one exp per score);
 // running max / sum are carried across 256-token sub-chunks; the last workgroup to finish for a
-// (row, kv head) merges the slices and writes the bf16 attention output.
+// (row, kv head) merges the slices and writes the attention output.
 // ------------------------------------------------------------------------------------------------
 struct AttnArgs {
-    const uint16_t *qbuf;          // [rows, n_q*hd] bf16, rotated
+    const float *qbuf;             // [rows, n_q*hd] fp32, rotated
     const uint16_t *kcache, *vcache;
     float *partials;               // [rows, n_q, n_splits, hd+2]
     int *counters;                 // [rows, n_kv], zero between launches
-    uint16_t *out;                 // [rows, n_q*hd] bf16
+    float *out;                    // [rows, n_q*hd] fp32
+    uint16_t *out_planes; size_t out_plane;   // optional three-plane bf16 split of the same values, or null
     const int *row_pos, *row_slot, *row_bad;
     int n_q, n_kv, max_ctx, max_seqs, layer;
 };
@@ -304,9 +345,10 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) { acc[g][j] = 0.f; q[g][j] = 0.f; }
         if (g < G) {
-            const uint4 qv = *reinterpret_cast<const uint4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + g) * HD + e0);
-            q[g][0] = bf16_lo(qv.x); q[g][1] = bf16_hi(qv.x); q[g][2] = bf16_lo(qv.y); q[g][3] = bf16_hi(qv.y);
-            q[g][4] = bf16_lo(qv.z); q[g][5] = bf16_hi(qv.z); q[g][6] = bf16_lo(qv.w); q[g][7] = bf16_hi(qv.w);
+            const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + g) * HD + e0);
+            const float4 qa = qp[0], qb = qp[1];
+            q[g][0] = qa.x; q[g][1] = qa.y; q[g][2] = qa.z; q[g][3] = qa.w;
+            q[g][4] = qb.x; q[g][5] = qb.y; q[g][6] = qb.z; q[g][7] = qb.w;
         }
     }
 
@@ -433,7 +475,16 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
             const float ls = p[s * PS + 1];
             if (ls > 0.f) { const float w = expf(p[s * PS] - M); L = fmaf(ls, w, L); O = fmaf(p[s * PS + 2 + e], w, O); }
         }
-        a.out[((size_t)row * a.n_q + kvh * G + g) * HD + e] = f32_to_bf16(L > 0.f ? O / L : 0.f);
+        const float o = L > 0.f ? O / L : 0.f;
+        const size_t oi = ((size_t)row * a.n_q + kvh * G + g) * HD + e;
+        a.out[oi] = o;
+        if (a.out_planes) {
+            const uint16_t p0 = f32_to_bf16(o);
+            const float r1 = o - bf16_to_f32(p0);
+            const uint16_t p1 = f32_to_bf16(r1);
+            a.out_planes[oi] = p0; a.out_planes[a.out_plane + oi] = p1;
+            a.out_planes[2 * a.out_plane + oi] = f32_to_bf16(r1 - bf16_to_f32(p1));
+        }
     }
     if (tid == 0) a.counters[row * a.n_kv + kvh] = 0;
 }

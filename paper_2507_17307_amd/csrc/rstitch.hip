@@ -58,13 +58,14 @@ const char *check_config(const rs_config *c) {
     if (c->max_seqs < 1 || c->max_seqs > 8) return "max_seqs must be in 1..8";
     if (c->max_rows < 1 || c->max_rows > 64) return "max_rows must be in 1..64";
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return "rms_eps must be > 0 and rope_theta > 1";
-    if ((size_t)c->d_ffn * 2 > 64 * 1024 - 1024) return "d_ffn too large for the LDS-staged activation vector";
+    if (c->d_model > rs::GEMV_KSEG || c->n_q_heads * c->head_dim > rs::GEMV_KSEG)
+        return "d_model and n_q_heads*head_dim must not exceed 12288";
     return nullptr;
 }
 
 struct Layout {
     size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, h, xn, qkv_raw, qbuf,
-        attn_out, act, attn_part, attn_cnt, lm_x, lm_parts, total;
+        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, total;
     int attn_rows_x_splits;   // capacity of attn_part in (row, split) pairs
     int lm_parts_cap;         // partial states per sequence
 };
@@ -88,15 +89,17 @@ Layout make_layout(const rs_config &c) {
     L.seq_bad = take(c.max_seqs * 4);
     L.seq_scale = take(c.max_seqs * 4);
     L.h = take((size_t)c.max_rows * c.d_model * 4);
-    L.xn = take((size_t)c.max_rows * c.d_model * 2);
+    L.xn = take((size_t)3 * c.max_rows * c.d_model * 2);
     L.qkv_raw = take((size_t)c.max_rows * qkv * 4);
-    L.qbuf = take((size_t)c.max_rows * qdim * 2);
-    L.attn_out = take((size_t)c.max_rows * qdim * 2);
-    L.act = take((size_t)c.max_rows * c.d_ffn * 2);
+    L.qbuf = take((size_t)c.max_rows * qdim * 4);
+    L.attn_out = take((size_t)c.max_rows * qdim * 4);
+    L.attn_pl = take((size_t)3 * c.max_rows * qdim * 2);
+    L.act = take((size_t)c.d_ffn * 4);
+    L.act_pl = take((size_t)3 * c.max_rows * c.d_ffn * 2);
     L.attn_rows_x_splits = attn_pairs_cap(c);
     L.attn_part = take((size_t)L.attn_rows_x_splits * c.n_q_heads * (c.head_dim + 2) * 4);
     L.attn_cnt = take((size_t)c.max_rows * c.n_kv_heads * 4);
-    L.lm_x = take((size_t)c.max_seqs * c.d_model * 2);
+    L.lm_pl = take((size_t)3 * c.max_seqs * c.d_model * 2);
     L.lm_parts_cap = LM_PARTS_CAP;
     L.lm_parts = take((size_t)c.max_seqs * L.lm_parts_cap * sizeof(rs::SoftPartial));
     L.total = o;
@@ -130,9 +133,13 @@ template <int MODE, int RT, int KS>
 rs_status launch_gemv(const rs_model *m, GemvArgs &a, int n_tiles, hipStream_t st, const char *name,
                       int *blocks_out = nullptr) {
     const int units = (KS == 1) ? (n_tiles + 3) / 4 : n_tiles;
-    const size_t lds = (size_t)a.K * 2;
+    const size_t lds = (size_t)(a.K < GEMV_KSEG ? a.K : GEMV_KSEG) * 4;
     const int per_cu = lds > 40 * 1024 ? 2 : 4;
     int blocks = gemv_blocks(units, m->n_cu, per_cu);
+    if (a.K > GEMV_KSEG) {                 // x is restaged per tile: one tile per workgroup
+        if (KS != 4) return fail(RS_EINVAL, "internal: segmented K needs the split-K launch");
+        blocks = units;
+    }
     if (MODE == G_LMHEAD && blocks * 4 > LM_PARTS_CAP) blocks = LM_PARTS_CAP / 4;   // one partial per wave
     if (blocks_out) *blocks_out = blocks;
     hipLaunchKernelGGL((k_gemv<MODE, RT, KS>), dim3(blocks), dim3(256), lds, st, a);
@@ -197,9 +204,11 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
     rs_status rc;
     for (int l = 0; l < c.n_layers; ++l) {
         AttnArgs aa{};
-        aa.qbuf = m->at<uint16_t>(L.qbuf); aa.kcache = m->kv_k; aa.vcache = m->kv_v;
+        aa.qbuf = m->at<float>(L.qbuf); aa.kcache = m->kv_k; aa.vcache = m->kv_v;
         aa.partials = m->at<float>(L.attn_part); aa.counters = m->at<int>(L.attn_cnt);
-        aa.out = m->at<uint16_t>(L.attn_out);
+        aa.out = m->at<float>(L.attn_out);
+        aa.out_planes = single ? nullptr : m->at<uint16_t>(L.attn_pl);
+        aa.out_plane = (size_t)c.max_rows * qdim;
         aa.row_pos = row_pos; aa.row_slot = row_slot; aa.row_bad = row_bad;
         aa.n_q = c.n_q_heads; aa.n_kv = c.n_kv_heads; aa.max_ctx = c.max_ctx; aa.max_seqs = c.max_seqs; aa.layer = l;
 
@@ -209,8 +218,8 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             g.max_seqs = c.max_seqs; g.layer = l; g.d_ffn = c.d_ffn;
             g.row_pos = row_pos; g.row_slot = row_slot; g.row_bad = row_bad;
             g.rope_cos = m->at<float>(L.rope_cos); g.rope_sin = m->at<float>(L.rope_sin);
-            g.qbuf = m->at<uint16_t>(L.qbuf); g.kcache = m->kv_k; g.vcache = m->kv_v;
-            g.act = m->at<uint16_t>(L.act); g.h_out = h;
+            g.qbuf = m->at<float>(L.qbuf); g.kcache = m->kv_k; g.vcache = m->kv_v;
+            g.act = m->at<float>(L.act); g.h_out = h;
 
             // QKV (+ RMSNorm, RoPE, KV write)
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
@@ -231,7 +240,7 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             if (rc) return rc;
             // O projection + residual
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
-            g.x_in = m->at<uint16_t>(L.attn_out);
+            g.x_in = m->at<float>(L.attn_out);
             if (c.d_model <= 2048) rc = launch_gemv<G_OPROJ, 2, 1>(m, g, (c.d_model + 1) / 2, st, "gemv_oproj");
             else rc = launch_gemv<G_OPROJ, 4, 1>(m, g, (c.d_model + 3) / 4, st, "gemv_oproj");
             if (rc) return rc;
@@ -241,22 +250,24 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             if (rc) return rc;
             // down + residual
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
-            g.x_in = m->at<uint16_t>(L.act);
-            if (c.d_model <= 2048) rc = launch_gemv<G_DOWN, 2, 4>(m, g, (c.d_model + 1) / 2, st, "gemv_down");
+            g.x_in = m->at<float>(L.act);
+            if (c.d_ffn > GEMV_KSEG) rc = launch_gemv<G_DOWN, 8, 4>(m, g, (c.d_model + 7) / 8, st, "gemv_down");
+            else if (c.d_model <= 2048) rc = launch_gemv<G_DOWN, 2, 4>(m, g, (c.d_model + 1) / 2, st, "gemv_down");
             else rc = launch_gemv<G_DOWN, 4, 4>(m, g, (c.d_model + 3) / 4, st, "gemv_down");
             if (rc) return rc;
         } else {
             uint16_t *xn = m->at<uint16_t>(L.xn);
+            const size_t xn_plane = (size_t)c.max_rows * c.d_model;
             GemmArgs g{};
             g.M = n_rows; g.d_ffn = c.d_ffn;
-            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, h, m->attn_norm[l], c.rms_eps, c.d_model,
-                               (const int *)nullptr, xn);
+            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, (const float *)h, m->attn_norm[l], c.rms_eps,
+                               c.d_model, (const int *)nullptr, xn, xn_plane);
             RS_LAUNCHED("rmsnorm_rows");
-            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn;
+            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
             g.out_f32 = m->at<float>(L.qkv_raw); g.ld_out = qkv_rows;
-            if ((rc = launch_gemm<G_QKV>(m, g, qkv_rows / 16, st, "gemm_qkv"))) return rc;
+            if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 31) / 32, st, "gemm_qkv"))) return rc;
             RopeArgs ra{};
-            ra.qkv = m->at<float>(L.qkv_raw); ra.qbuf = m->at<uint16_t>(L.qbuf); ra.kcache = m->kv_k; ra.vcache = m->kv_v;
+            ra.qkv = m->at<float>(L.qkv_raw); ra.qbuf = m->at<float>(L.qbuf); ra.kcache = m->kv_k; ra.vcache = m->kv_v;
             ra.rope_cos = m->at<float>(L.rope_cos); ra.rope_sin = m->at<float>(L.rope_sin);
             ra.row_pos = row_pos; ra.row_slot = row_slot; ra.row_bad = row_bad;
             ra.n_q = c.n_q_heads; ra.n_kv = c.n_kv_heads; ra.head_dim = hd; ra.max_ctx = c.max_ctx;
@@ -269,16 +280,19 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
                 default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
             }
             if (rc) return rc;
-            g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.X = m->at<uint16_t>(L.attn_out);
+            g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim;
+            g.X = m->at<uint16_t>(L.attn_pl); g.x_plane = (size_t)c.max_rows * qdim;
             g.h_out = h; g.ld_h = c.d_model;
-            if ((rc = launch_gemm<G_OPROJ>(m, g, c.d_model / 16, st, "gemm_oproj"))) return rc;
-            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, h, m->mlp_norm[l], c.rms_eps, c.d_model,
-                               (const int *)nullptr, xn);
+            if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 31) / 32, st, "gemm_oproj"))) return rc;
+            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, (const float *)h, m->mlp_norm[l], c.rms_eps,
+                               c.d_model, (const int *)nullptr, xn, xn_plane);
             RS_LAUNCHED("rmsnorm_rows");
-            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.act = m->at<uint16_t>(L.act);
-            if ((rc = launch_gemm<G_GATEUP>(m, g, c.d_ffn / 16, st, "gemm_gateup"))) return rc;
-            g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.X = m->at<uint16_t>(L.act);
-            if ((rc = launch_gemm<G_DOWN>(m, g, c.d_model / 16, st, "gemm_down"))) return rc;
+            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
+            g.act = m->at<uint16_t>(L.act_pl); g.act_plane = (size_t)c.max_rows * c.d_ffn;
+            if ((rc = launch_gemm<G_GATEUP>(m, g, (c.d_ffn + 15) / 16, st, "gemm_gateup"))) return rc;
+            g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn;
+            g.X = m->at<uint16_t>(L.act_pl); g.x_plane = (size_t)c.max_rows * c.d_ffn;
+            if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 31) / 32, st, "gemm_down"))) return rc;
         }
     }
 
@@ -293,14 +307,15 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
         if ((rc = launch_gemv<G_LMHEAD, 8, 1>(m, g, (c.vocab + 7) / 8, st, "gemv_lmhead", &blocks))) return rc;
         n_parts = blocks * 4;
     } else {
-        uint16_t *lm_x = m->at<uint16_t>(L.lm_x);
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seqs), dim3(256), 0, st, h, m->final_norm, c.rms_eps, c.d_model,
-                           (const int *)m->at<int>(L.out_row), lm_x);
+        uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
+        const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seqs), dim3(256), 0, st, (const float *)h, m->final_norm, c.rms_eps,
+                           c.d_model, (const int *)m->at<int>(L.out_row), lm_pl, lm_plane);
         RS_LAUNCHED("rmsnorm_rows");
         GemmArgs g{};
-        g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_x;
+        g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
-        if ((rc = launch_gemm<G_LMHEAD>(m, g, (c.vocab + 15) / 16, st, "gemm_lmhead"))) return rc;
+        if ((rc = launch_gemm<G_LMHEAD>(m, g, (c.vocab + 31) / 32, st, "gemm_lmhead"))) return rc;
         n_parts = g.n_parts;
     }
     if (n_parts > L.lm_parts_cap) return fail(RS_EINVAL, "internal: %d router partials exceed capacity", n_parts);
