@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Headline benchmark: stitched decode tokens/s at batch 1 on the 1.5B + 7B shapes
+(workload cfg3_s15_m7), with the fraction of the per-token HBM roofline.
+
+A "step" is one ACCEPTED token of the live stitched run (Algorithm 1 driven from
+the host through the C ABI): it costs one or more model invocations - small-model
+decode steps (accepted or rejected), large-model catch-up prefills and decode
+steps.  All inputs (weights, prompt, logit-scale schedule) are seeded synthetic
+data resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  Extra objects:
+  roofline      live HIP-event timing of the dominant kernel (the large model's
+                gate/up projection) against the 8 TB/s HBM peak
+  per_model     decode ms/token of each model alone and its roofline fraction
+  stitched      invocation mix of the timed region and its roofline fraction
+  cpu_baseline  the CPU oracle timed on this machine's cores on a small sample
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12   # bytes/s, MI355X published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs through the HIP runtime (torch's events only see torch's stream API)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventQuery.argtypes = [C.c_void_p]
+
+    def create(self) -> int:
+        ev = C.c_void_p()
+        assert self.hip.hipEventCreate(C.byref(ev)) == 0
+        return ev.value
+
+    def record(self, ev: int, stream: int) -> None:
+        assert self.hip.hipEventRecord(ev, stream) == 0
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        return ms.value if rc == 0 else float("nan")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1024, help="accepted tokens in the timed region")
+    ap.add_argument("--warmup", type=int, default=64, help="accepted tokens before the timed region")
+    ap.add_argument("--workload", default="cfg3_s15_m7")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tau-steps", type=int, default=None, help="small-model-only tokens used to place tau")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as W
+    from workloads import shapes as S
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedPair, SLM, LLM
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = W.WORKLOADS[args.workload]
+    assert wl.n_seqs == 1 and wl.llm is not None, "bench.py times the batch-1 stitched workloads"
+    if args.warmup + args.steps > wl.n_decode:
+        print(f"bench.py: warmup + steps must not exceed {wl.n_decode}", file=sys.stderr)
+        return 2
+    dev = "cuda"
+    t0 = time.time()
+    w_s = W.make_weights(wl.slm, wl.seed, 0, device=dev)
+    w_l = W.make_weights(wl.llm, wl.seed, 1, device=dev)
+    torch.cuda.synchronize()
+    log(f"[bench] weights generated on the GPU in {time.time() - t0:.1f}s")
+    max_ctx = wl.max_ctx
+    slm = P.Model(w_s, max_ctx=max_ctx, max_rows=64)
+    llm = P.Model(w_l, max_ctx=max_ctx, max_rows=64)
+    prompt = W.make_prompt(wl).tolist()
+    scales = W.logit_scale(wl, 0, max_ctx + 1)
+    pair = StitchedPair(slm, llm, max_ctx, scales)
+    ln_v = math.log(wl.slm.vocab)
+
+    # ---- tau: percentile of the small model's normalised entropies over a small-model-only run
+    n_tau = wl.n_decode if args.tau_steps is None else args.tau_steps
+    t0 = time.time()
+    solo = pair.generate(prompt, 2.0, n_tau, single_model=SLM)
+    tau = W.pick_tau([t.h_norm for t in solo.trace], wl.tau_percentile, 4e-3 / ln_v)
+    log(f"[bench] small-model-only run: {n_tau} tokens in {time.time() - t0:.2f}s; tau = {tau:.6f}")
+
+    # ---- phase timer on the large model's gate/up projection (dominant kernel)
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    P.rs_set_phase_timer(llm.handle, P.binding.PHASE_GATEUP, wl.llm.n_layers // 2, e0, e1)
+    gateup_bytes = 2 * wl.llm.d_ffn * wl.llm.d_model * 2
+    stats = {"timed": False, "inv": [], "kern": {}}
+
+    def on_inv(model, pos0, n_rows):
+        if not stats["timed"]:
+            return
+        stats["inv"].append((model, pos0, n_rows))
+        if model == LLM:
+            name = "k_gemv<GATEUP>" if n_rows == 1 else f"k_gemm_rows<GATEUP,NB={(min(n_rows, 64) + 15) // 16}>"
+            ms = ev.elapsed_ms(e0, e1)
+            k = stats["kern"].setdefault(name, [0, 0.0])
+            k[0] += 1
+            k[1] += ms
+
+    pair.on_invocation = on_inv
+
+    # ---- live stitched run: warmup tokens, then the timed region
+    marks = {}
+
+    def stop_after(n_acc):
+        if n_acc == args.warmup:
+            torch.cuda.synchronize()
+            stats["timed"] = True
+            marks["t0"] = time.perf_counter()
+        return False
+
+    if args.warmup == 0:
+        stats["timed"] = True
+        torch.cuda.synchronize()
+        marks["t0"] = time.perf_counter()
+    run = pair.generate(prompt, tau, args.warmup + args.steps, stop_after=stop_after)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - marks["t0"]
+    P.rs_set_phase_timer(llm.handle, -1)
+    tokens_per_s = args.steps / elapsed
+
+    # ---- invocation mix and stitched roofline of the timed region
+    inv = stats["inv"]
+    shapes = {SLM: wl.slm, LLM: wl.llm}
+    ideal_s = sum(S.step_bytes(shapes[m], [p0 + n], n) for m, p0, n in inv) / HBM_PEAK
+    n_llm_inv = sum(1 for m, _, _ in inv if m == LLM)
+    n_slm_inv = len(inv) - n_llm_inv
+    timed_trace = run.trace[-len(inv):] if inv else []
+    llm_tokens = sum(1 for t in timed_trace if t.model == LLM and t.accept)
+    rejected = sum(1 for t in timed_trace if not t.accept)
+    spans = [n for m, _, n in inv if m == LLM]
+
+    # dominant kernel
+    dom = max(stats["kern"].items(), key=lambda kv: kv[1][1]) if stats["kern"] else None
+    roofline = None
+    if dom:
+        name, (cnt, tot_ms) = dom
+        avg_s = tot_ms / cnt * 1e-3
+        roofline = {"bound": "hbm", "kernel": name, "launches": cnt, "avg_us": round(avg_s * 1e6, 2),
+                    "achieved": round(gateup_bytes / avg_s / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                    "frac": round(gateup_bytes / avg_s / HBM_PEAK, 4), "traffic": None,
+                    "bytes_per_launch": gateup_bytes,
+                    "all_variants": {k: {"launches": v[0], "avg_us": round(v[1] / v[0] * 1e3, 2)}
+                                     for k, v in stats["kern"].items()}}
+
+    # ---- each model alone: decode steps back to back (teacher-forced tokens, no host round trip)
+    per_model = {}
+    hip_stream = torch.cuda.current_stream().cuda_stream
+    for tag, model, shape in (("slm", slm, wl.slm), ("llm", llm, wl.llm)):
+        n_steps, p_start = 64, max_ctx - 64 - 1
+        # the cache below p_start must hold something finite: it does (prefill/earlier decode or zeros)
+        out = P.binding.new_route_out(1)
+        toks = torch.tensor(run.output[:n_steps + 8], dtype=torch.int32, device=dev)
+        a, b = ev.create(), ev.create()
+        for rep in range(2):                      # first pass warms up
+            if rep == 1:
+                torch.cuda.synchronize()
+                ev.record(a, hip_stream)
+            for i in range(n_steps):
+                P.rs_decode_step(model.handle, 1, pair.slot0, toks[i:i + 1], pair.pos_table[p_start + i:p_start + i + 1],
+                                 None, tau, SLM, out, None)
+        ev.record(b, hip_stream)
+        torch.cuda.synchronize()
+        ms = ev.elapsed_ms(a, b) / n_steps
+        bytes_step = S.step_bytes(shape, [p_start + n_steps // 2 + 1])
+        per_model[tag] = {"shape": shape.name, "ctx": p_start + n_steps // 2, "ms_per_token": round(ms, 4),
+                          "roofline_ms": round(bytes_step / HBM_PEAK * 1e3, 4),
+                          "roofline_frac": round(bytes_step / HBM_PEAK / (ms * 1e-3), 4)}
+
+    # ---- CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import decoder as odec
+        torch.set_grad_enabled(False)
+        t_inv = {}
+        for tag, wts in (("slm", w_s), ("llm", w_l)):
+            t0 = time.time()
+            w_cpu = wts.to("cpu")
+            om = odec.OracleModel(w_cpu, max_ctx=8, keep_fp64_weights=False)
+            t1 = time.time()
+            om.forward(prompt[:1], 0)
+            t_inv[tag] = time.time() - t1
+            log(f"[bench] oracle {tag}: one invocation {t_inv[tag]:.1f}s (+{t1 - t0:.1f}s to copy weights to the host)")
+            del om, w_cpu
+        per_tok = (n_slm_inv * t_inv["slm"] + n_llm_inv * t_inv["llm"]) / max(args.steps, 1)
+        cpu = {"value": round(1.0 / per_tok, 4), "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+               "sample": ("one 1-token invocation of each full-shape oracle model (fp64, weights converted from bf16 per "
+                          "layer), combined with the invocation mix of the timed GPU run: "
+                          f"{n_slm_inv} small-model and {n_llm_inv} large-model invocations per {args.steps} tokens"),
+               "s_per_invocation": {k: round(v, 2) for k, v in t_inv.items()}}
+
+    line = {
+        "metric": "stitched decode tokens/s at batch 1 (7B+1.5B shapes)",
+        "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",
+        "config": {"workload": args.workload, "slm": wl.slm.name, "llm": wl.llm.name, "batch": 1,
+                   "prompt_len": len(prompt), "tau": round(tau, 6), "tau_percentile": wl.tau_percentile,
+                   "max_ctx": max_ctx},
+        "roofline": roofline,
+        "per_model": per_model,
+        "stitched": {"invocations": len(inv), "slm_invocations": n_slm_inv, "llm_invocations": n_llm_inv,
+                     "llm_token_frac": round(llm_tokens / max(args.steps, 1), 4), "rejected_slm_steps": rejected,
+                     "llm_span_mean": round(sum(spans) / max(len(spans), 1), 2), "llm_span_max": max(spans) if spans else 0,
+                     "roofline_ms_per_token": round(ideal_s / args.steps * 1e3, 4),
+                     "roofline_frac": round(ideal_s / elapsed, 4)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -187,6 +187,22 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
                    rs_route_out *d_out, void *d_scratch, size_t scratch_bytes,
                    void *stream);
 
+/* Measurement aid (not part of the method): while armed, every forward call on
+ * this model records `start_event` immediately before and `stop_event`
+ * immediately after the launch of ONE kernel on the call's stream: the kernel of
+ * phase `phase` (RS_PHASE_*) in layer `layer` (layer is ignored for
+ * RS_PHASE_LMHEAD).  Both are caller-owned hipEvent_t handles passed as void*;
+ * the caller reads them with hipEventElapsedTime after synchronising.
+ * phase < 0 disarms.  Errors: RS_EINVAL (null model/event, layer out of range). */
+#define RS_PHASE_QKV     0
+#define RS_PHASE_OPROJ   1
+#define RS_PHASE_GATEUP  2
+#define RS_PHASE_DOWN    3
+#define RS_PHASE_LMHEAD  4
+#define RS_PHASE_ATTN    5
+rs_status rs_set_phase_timer(rs_model *model, int32_t phase, int32_t layer,
+                             void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -295,14 +295,16 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 // ------------------------------------------------------------------------------------------------
 // Split-K grouped-query decode attention.  grid (n_splits, n_kv_heads, n_rows), block 256.
 // A workgroup owns one KV head, one slice of the context and ALL query heads of that KV head's
-// group, so every K/V byte is read once per row.  Scores go through LDS (one exp per score);
-// running max / sum are carried across 256-token sub-chunks; the last workgroup to finish for a
-// (row, kv head) merges the slices and writes the attention output.
+// group, so every K/V byte is read once per row.  Per sub-chunk of TS tokens every thread issues
+// its 8 K loads and 8 V loads (16 bytes each) up front, so the whole sub-chunk costs one memory
+// round trip; scores go through LDS (one exp per score); running max / sum are carried across
+// sub-chunks.  The last workgroup to finish for a (row, kv head) merges the slices.
+// Partial record per (row, q head, split): [m, l, 0, 0, acc[HD]] fp32.
 // ------------------------------------------------------------------------------------------------
 struct AttnArgs {
     const float *qbuf;             // [rows, n_q*hd] fp32, rotated
     const uint16_t *kcache, *vcache;
-    float *partials;               // [rows, n_q, n_splits, hd+2]
+    float *partials;               // [rows, n_q, n_splits, hd+4]
     int *counters;                 // [rows, n_kv], zero between launches
     float *out;                    // [rows, n_q*hd] fp32
     uint16_t *out_planes; size_t out_plane;   // optional three-plane bf16 split of the same values, or null
@@ -310,20 +312,24 @@ struct AttnArgs {
     int n_q, n_kv, max_ctx, max_seqs, layer;
 };
 
-constexpr int ATT_GMAX = 8;
-constexpr int ATT_TS = 256;
+constexpr int ATT_GMAX = 8;       // query heads per kv head, at most
+constexpr int ATT_NLD = 8;        // 16-byte K (and V) loads in flight per thread
+constexpr int ATT_SMAX = 64;      // context slices, at most
 
 template <int HD>
 __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
-    constexpr int LPR = HD / 8, RPW = 64 / LPR, TPI = 4 * RPW;   // lanes per row, rows per wave-load, tokens per iteration
+    constexpr int LPR = HD / 8, RPW = 64 / LPR, TPI = 4 * RPW;   // lanes per row, rows per wave-load, tokens per load round
+    constexpr int TS = ATT_NLD * TPI;                            // tokens per sub-chunk
+    constexpr int PS = HD + 4;                                   // floats per partial record
+    constexpr int NQ = HD / 4, NSG = 256 / NQ;                   // combine: float4 columns, slice groups
     const int split = blockIdx.x, S = gridDim.x, kvh = blockIdx.y, row = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = a.n_q / a.n_kv;
     const int sub_lane = lane % LPR, grp = lane / LPR, e0 = sub_lane * 8;
 
-    __shared__ float s_lds[ATT_GMAX][ATT_TS];
+    __shared__ float s_lds[ATT_GMAX * TS];                 // scores / probabilities; reused by the combine
     __shared__ float m_lds[ATT_GMAX], alpha_lds[ATT_GMAX];
-    __shared__ float accw[4][ATT_GMAX][HD + 1];
+    __shared__ __align__(16) float accw[NSG > 4 ? NSG : 4][ATT_GMAX][HD];   // cross-wave / cross-group sums
     __shared__ float lw[4][ATT_GMAX];
     __shared__ int last_flag;
 
@@ -352,41 +358,45 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
         }
     }
 
-    for (int sub = t_begin; sub < t_end; sub += ATT_TS) {
-        const int n_sub = min(ATT_TS, t_end - sub);
-        // scores
-        for (int it = 0; it * TPI < n_sub; ++it) {
+    for (int sub = t_begin; sub < t_end; sub += TS) {
+        const int n_sub = min(TS, t_end - sub);
+        uint4 kreg[ATT_NLD], vreg[ATT_NLD];
+#pragma unroll
+        for (int it = 0; it < ATT_NLD; ++it) {
             const int tl = it * TPI + wave * RPW + grp;
+            kreg[it] = make_uint4(0, 0, 0, 0); vreg[it] = make_uint4(0, 0, 0, 0);
+            if (tl < n_sub) {
+                kreg[it] = *reinterpret_cast<const uint4 *>(Kp + (size_t)(sub + tl) * HD + e0);
+                vreg[it] = *reinterpret_cast<const uint4 *>(Vp + (size_t)(sub + tl) * HD + e0);
+            }
+        }
+        // scores
+#pragma unroll
+        for (int it = 0; it < ATT_NLD; ++it) {
+            const int tl = it * TPI + wave * RPW + grp;
+            const uint4 kv = kreg[it];
+            const float k0 = bf16_lo(kv.x), k1 = bf16_hi(kv.x), k2 = bf16_lo(kv.y), k3 = bf16_hi(kv.y);
+            const float k4 = bf16_lo(kv.z), k5 = bf16_hi(kv.z), k6 = bf16_lo(kv.w), k7 = bf16_hi(kv.w);
             float part[ATT_GMAX];
 #pragma unroll
-            for (int g = 0; g < ATT_GMAX; ++g) part[g] = 0.f;
-            if (tl < n_sub) {
-                const uint4 kv = *reinterpret_cast<const uint4 *>(Kp + (size_t)(sub + tl) * HD + e0);
-                const float k0 = bf16_lo(kv.x), k1 = bf16_hi(kv.x), k2 = bf16_lo(kv.y), k3 = bf16_hi(kv.y);
-                const float k4 = bf16_lo(kv.z), k5 = bf16_hi(kv.z), k6 = bf16_lo(kv.w), k7 = bf16_hi(kv.w);
-#pragma unroll
-                for (int g = 0; g < ATT_GMAX; ++g) {
-                    float p = q[g][0] * k0;
-                    p = fmaf(q[g][1], k1, p); p = fmaf(q[g][2], k2, p); p = fmaf(q[g][3], k3, p);
-                    p = fmaf(q[g][4], k4, p); p = fmaf(q[g][5], k5, p); p = fmaf(q[g][6], k6, p); p = fmaf(q[g][7], k7, p);
-                    part[g] = p;
-                }
-            }
-#pragma unroll
             for (int g = 0; g < ATT_GMAX; ++g) {
+                float p = q[g][0] * k0;
+                p = fmaf(q[g][1], k1, p); p = fmaf(q[g][2], k2, p); p = fmaf(q[g][3], k3, p);
+                p = fmaf(q[g][4], k4, p); p = fmaf(q[g][5], k5, p); p = fmaf(q[g][6], k6, p); p = fmaf(q[g][7], k7, p);
 #pragma unroll
-                for (int o = LPR >> 1; o > 0; o >>= 1) part[g] += __shfl_xor(part[g], o, RS_WAVE);
+                for (int o = LPR >> 1; o > 0; o >>= 1) p += __shfl_xor(p, o, RS_WAVE);
+                part[g] = p;
             }
             if (sub_lane == 0 && tl < n_sub) {
 #pragma unroll
-                for (int g = 0; g < ATT_GMAX; ++g) if (g < G) s_lds[g][tl] = part[g] * scale;
+                for (int g = 0; g < ATT_GMAX; ++g) if (g < G) s_lds[g * TS + tl] = part[g] * scale;
             }
         }
         __syncthreads();
         // sub-chunk maxima -> new running maxima and rescale factors (one wave per head)
         for (int g = wave; g < G; g += 4) {
             float mx = -INFINITY;
-            for (int i = lane; i < n_sub; i += 64) mx = fmaxf(mx, s_lds[g][i]);
+            for (int i = lane; i < n_sub; i += 64) mx = fmaxf(mx, s_lds[g * TS + i]);
             mx = wave_max(mx);
             if (lane == 0) {
                 const float m_old = m_lds[g], m_new = fmaxf(m_old, mx);
@@ -402,21 +412,22 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[g][j] *= alpha;
         }
-        for (int i = tid; i < G * n_sub; i += 256) {
-            const int g = i / n_sub, tl = i - g * n_sub;
-            s_lds[g][tl] = expf(s_lds[g][tl] - m_lds[g]);
+        for (int g = 0; g < G; ++g) {
+            const float mg = m_lds[g];
+            for (int i = tid; i < n_sub; i += 256) s_lds[g * TS + i] = expf(s_lds[g * TS + i] - mg);
         }
         __syncthreads();
         // P V
-        for (int it = 0; it * TPI < n_sub; ++it) {
+#pragma unroll
+        for (int it = 0; it < ATT_NLD; ++it) {
             const int tl = it * TPI + wave * RPW + grp;
             if (tl < n_sub) {
-                const uint4 vv = *reinterpret_cast<const uint4 *>(Vp + (size_t)(sub + tl) * HD + e0);
+                const uint4 vv = vreg[it];
                 const float v0 = bf16_lo(vv.x), v1 = bf16_hi(vv.x), v2 = bf16_lo(vv.y), v3 = bf16_hi(vv.y);
                 const float v4 = bf16_lo(vv.z), v5 = bf16_hi(vv.z), v6 = bf16_lo(vv.w), v7 = bf16_hi(vv.w);
 #pragma unroll
                 for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
-                    const float p = s_lds[g][tl];
+                    const float p = s_lds[g * TS + tl];
                     l[g] += p;
                     acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
                     acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
@@ -447,12 +458,11 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
         }
     }
     __syncthreads();
-    const int PS = HD + 2;
     for (int i = tid; i < G * HD; i += 256) {
         const int g = i / HD, e = i - g * HD;
         const float v = accw[0][g][e] + accw[1][g][e] + accw[2][g][e] + accw[3][g][e];
         float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
-        p[2 + e] = v;
+        p[4 + e] = v;
         if (e == 0) { p[0] = m_lds[g]; p[1] = lw[0][g] + lw[1][g] + lw[2][g] + lw[3][g]; }
     }
     // completion ticket
@@ -465,17 +475,45 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
     __syncthreads();
     if (!last_flag) return;
     __threadfence();
+
+    // ---- combine (last workgroup only): weights per (head, slice), then a slice-parallel weighted sum
+    float *m_sh = s_lds, *w_sh = s_lds + ATT_GMAX * ATT_SMAX;       // S <= ATT_SMAX and 2*GMAX*SMAX <= GMAX*TS
+    const float *pbase = a.partials + ((size_t)row * a.n_q + kvh * G) * S * PS;
+    for (int i = tid; i < G * S; i += 256) {
+        const int g = i / S, s = i - g * S;
+        const float2 ml = *reinterpret_cast<const float2 *>(pbase + ((size_t)g * S + s) * PS);
+        m_sh[g * ATT_SMAX + s] = ml.y > 0.f ? ml.x : -INFINITY;
+        w_sh[g * ATT_SMAX + s] = ml.y;
+    }
+    __syncthreads();
+    for (int g = wave; g < G; g += 4) {
+        const float ms = lane < S ? m_sh[g * ATT_SMAX + lane] : -INFINITY;
+        const float ls = lane < S ? w_sh[g * ATT_SMAX + lane] : 0.f;
+        const float M = wave_max(ms);
+        const float w = ls > 0.f ? expf(ms - M) : 0.f;
+        const float L = wave_sum(ls * w);
+        if (lane < S) w_sh[g * ATT_SMAX + lane] = L > 0.f ? w / L : 0.f;
+    }
+    __syncthreads();
+    {
+        const int qd = tid % NQ, sg = tid / NQ;
+        for (int g = 0; g < G; ++g) {
+            float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+            for (int s = sg; s < S; s += NSG) {
+                const float w = w_sh[g * ATT_SMAX + s];
+                const float4 v = *reinterpret_cast<const float4 *>(pbase + ((size_t)g * S + s) * PS + 4 + 4 * qd);
+                sum.x = fmaf(w, v.x, sum.x); sum.y = fmaf(w, v.y, sum.y); sum.z = fmaf(w, v.z, sum.z); sum.w = fmaf(w, v.w, sum.w);
+            }
+            *reinterpret_cast<float4 *>(&accw[sg][g][4 * qd]) = sum;
+        }
+    }
+    __syncthreads();
     for (int i = tid; i < G * HD; i += 256) {
         const int g = i / HD, e = i - g * HD;
-        const float *p = a.partials + ((size_t)row * a.n_q + kvh * G + g) * S * PS;
-        float M = -INFINITY;
-        for (int s = 0; s < S; ++s) if (p[s * PS + 1] > 0.f) M = fmaxf(M, p[s * PS]);
-        float L = 0.f, O = 0.f;
-        for (int s = 0; s < S; ++s) {
-            const float ls = p[s * PS + 1];
-            if (ls > 0.f) { const float w = expf(p[s * PS] - M); L = fmaf(ls, w, L); O = fmaf(p[s * PS + 2 + e], w, O); }
-        }
-        const float o = L > 0.f ? O / L : 0.f;
+        float o = 0.f;
+#pragma unroll
+        for (int sg = 0; sg < NSG; ++sg) o += accw[sg][g][e];
         const size_t oi = ((size_t)row * a.n_q + kvh * G + g) * HD + e;
         a.out[oi] = o;
         if (a.out_planes) {

@@ -82,10 +82,13 @@ __global__ void __launch_bounds__(256) k_rope_kv_rows(RopeArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// out[m, n] = sum_k X[m, k] W[n, k] for M <= 16*NB token rows.  A wave owns two 16-row tiles of W
-// at a time (MFMA "A" operand, loaded straight from HBM) against all tokens ("B" operand: the three
-// planes of X, read through L2).  For gate/up the two tiles are (gate rows, matching up
-// rows); otherwise they are 32 consecutive rows.
+// out[m, n] = sum_k X[m, k] W[n, k] for M <= 16*NB token rows.
+// A workgroup of NW waves owns 16 output columns at a time (for gate/up: 16 gate rows and the 16
+// matching up rows of W); its waves split K in interleaved 128-element blocks, each wave feeding
+// the matrix cores with W rows as the MFMA "A" operand (loaded straight from HBM, next block
+// prefetched while the current one is multiplied) and the three bf16 planes of X as the "B"
+// operand (read through L2); the per-wave 16x16 accumulators are summed through LDS by wave 0,
+// which also runs the epilogue.
 // Lane (i = lane % 16, g = lane / 16) supplies, for both operands, the 8 consecutive k at
 // kb + 32 g + 8 s (s = 0..3) of its row: any k order is valid for a dot product as long as both
 // operands agree, and this one lets a lane read 64 contiguous bytes.  The accumulator lane holds
@@ -100,14 +103,15 @@ struct GemmArgs {
     const float *seq_scale; SoftPartial *parts; float *logits; int n_parts;   // LM head
 };
 
-template <int MODE, int NB>
-__global__ void __launch_bounds__(256) k_gemm_rows(GemmArgs a) {
+template <int MODE, int NB, int NW>
+__global__ void __launch_bounds__(NW * 64) k_gemm_rows(GemmArgs a) {
+    constexpr int NT = (MODE == G_GATEUP) ? 2 : 1;
+    __shared__ float4 red[NW > 1 ? NW : 1][NT][NB][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
     const int K = a.K;
     const int n_out = (MODE == G_GATEUP) ? a.d_ffn : a.N;                 // distinct output columns
-    const int n_units = (MODE == G_GATEUP) ? (n_out + 15) / 16 : (n_out + 31) / 32;
-    const int gw = blockIdx.x * 4 + wave, gstride = gridDim.x * 4;
+    const int n_tiles = (n_out + 15) / 16;
 
     const uint16_t *xp[NB];
     bool xok[NB];
@@ -120,28 +124,34 @@ __global__ void __launch_bounds__(256) k_gemm_rows(GemmArgs a) {
     SoftState st; st.init();
     const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
 
-    for (int u = gw; u < n_units; u += gstride) {
-        // rows of the two W tiles this lane feeds, and the output columns they produce
-        int n0[2];
-        const uint16_t *w[2];
-        if (MODE == G_GATEUP) {
-            n0[0] = u * 16; n0[1] = u * 16;
-            w[0] = a.W + (size_t)min(u * 16 + i16, a.d_ffn - 1) * K + g * 32;
-            w[1] = a.W + (size_t)(a.d_ffn + min(u * 16 + i16, a.d_ffn - 1)) * K + g * 32;
-        } else {
-            n0[0] = u * 32; n0[1] = u * 32 + 16;
-            w[0] = a.W + (size_t)min(n0[0] + i16, a.N - 1) * K + g * 32;
-            w[1] = a.W + (size_t)min(n0[1] + i16, a.N - 1) * K + g * 32;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int n0 = t * 16;
+        const int wrow = min(n0 + i16, n_out - 1);
+        const uint16_t *w[NT];
+        w[0] = a.W + (size_t)wrow * K + g * 32;
+        if (NT == 2) w[NT - 1] = a.W + (size_t)(a.d_ffn + wrow) * K + g * 32;
+        f32x4_t acc[NT][NB];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[nt][nb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+        uint4 av[NT][4];
+        int kb = wave * 128;
+        if (kb < K) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int s = 0; s < 4; ++s) av[nt][s] = load_stream(reinterpret_cast<const uint4 *>(w[nt] + kb + 8 * s));
         }
-        f32x4_t acc[2][NB];
+        for (; kb < K; kb += NW * 128) {
+            uint4 an[NT][4];
+            const int kn = kb + NW * 128;
+            if (kn < K) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) { acc[0][nb] = (f32x4_t){0.f, 0.f, 0.f, 0.f}; acc[1][nb] = (f32x4_t){0.f, 0.f, 0.f, 0.f}; }
-        for (int kb = 0; kb < K; kb += 128) {
-            uint4 av[2][4];
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                av[0][s] = load_stream(reinterpret_cast<const uint4 *>(w[0] + kb + 8 * s));
-                av[1][s] = load_stream(reinterpret_cast<const uint4 *>(w[1] + kb + 8 * s));
+                    for (int s = 0; s < 4; ++s) an[nt][s] = load_stream(reinterpret_cast<const uint4 *>(w[nt] + kn + 8 * s));
             }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
@@ -156,53 +166,74 @@ __global__ void __launch_bounds__(256) k_gemm_rows(GemmArgs a) {
                     for (int s = 0; s < 4; ++s) {
                         const bf16x8_t B = __builtin_bit_cast(bf16x8_t, bv[s]);
 #pragma unroll
-                        for (int wt = 0; wt < 2; ++wt)
-                            acc[wt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[wt][s]), B,
-                                                                                   acc[wt][nb], 0, 0, 0);
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[nt][s]), B,
+                                                                                   acc[nt][nb], 0, 0, 0);
                     }
                 }
             }
-        }
-        // ---- epilogue: this lane holds output columns n0[wt] + 4 g + r (r = 0..3) of token nb*16 + i16
+            if (kn < K) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int m = nb * 16 + i16;
-            if (m >= a.M) continue;
-            if (MODE == G_GATEUP) {
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) av[nt][s] = an[nt][s];
+            }
+        }
+        // ---- sum the waves' accumulators (wave 0 ends up with the totals)
+        if (NW > 1) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    red[wave][nt][nb][lane] = make_float4(acc[nt][nb][0], acc[nt][nb][1], acc[nt][nb][2], acc[nt][nb][3]);
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        float4 sum = red[0][nt][nb][lane];
+                        for (int wv = 1; wv < NW; ++wv) {
+                            const float4 v = red[wv][nt][nb][lane];
+                            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                        }
+                        acc[nt][nb] = (f32x4_t){sum.x, sum.y, sum.z, sum.w};
+                    }
+            }
+        }
+        // ---- epilogue (wave 0): this lane holds output columns n0 + 4 g + r (r = 0..3) of token nb*16 + i16
+        if (wave == 0) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int m = nb * 16 + i16;
+                if (m >= a.M) continue;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int n = n0[0] + 4 * g + r;
-                    if (n >= a.d_ffn) continue;
-                    const float gt = acc[0][nb][r], up = acc[1][nb][r];
-                    split_store(gt / (1.0f + expf(-gt)) * up, a.act, a.act_plane, (size_t)m * a.d_ffn + n);
-                }
-            } else {
-#pragma unroll
-                for (int wt = 0; wt < 2; ++wt) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int n = n0[wt] + 4 * g + r;
-                        if (n >= a.N) continue;
-                        const float v = acc[wt][nb][r];
-                        if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = v;
-                        else if (MODE == G_OPROJ || MODE == G_DOWN) a.h_out[(size_t)m * a.ld_h + n] += v;
-                        else {
-                            const float lg = v * lm_scale;
-                            st.push(lg, n);
-                            if (a.logits) a.logits[(size_t)m * a.N + n] = lg;
-                        }
+                    const int n = n0 + 4 * g + r;
+                    if (n >= n_out) continue;
+                    const float v = acc[0][nb][r];
+                    if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = v;
+                    else if (MODE == G_OPROJ || MODE == G_DOWN) a.h_out[(size_t)m * a.ld_h + n] += v;
+                    else if (MODE == G_GATEUP) {
+                        const float up = acc[NT - 1][nb][r];
+                        split_store(v / (1.0f + expf(-v)) * up, a.act, a.act_plane, (size_t)m * a.d_ffn + n);
+                    } else {
+                        const float lg = v * lm_scale;
+                        st.push(lg, n);
+                        if (a.logits) a.logits[(size_t)m * a.N + n] = lg;
                     }
                 }
             }
         }
+        if (NW > 1) __syncthreads();      // red[] is reused by the next tile
     }
-    if (MODE == G_LMHEAD) {
+    if (MODE == G_LMHEAD && wave == 0) {
         // merge the four row groups of the wave: lanes 0..15 end up with the state of token i16
         for (int o = 32; o >= 16; o >>= 1) {
             SoftState b = shfl_xor_state(st, o);
             if ((lane & o) == 0) st.merge(b); else { b.merge(st); st = b; }
         }
-        if (g == 0 && i16 < a.M) a.parts[(size_t)i16 * a.n_parts + gw] = to_partial(st);
+        if (g == 0 && i16 < a.M) a.parts[(size_t)i16 * a.n_parts + blockIdx.x] = to_partial(st);
     }
 }
 

@@ -38,16 +38,21 @@ k_route_partials(const float *__restrict__ logits, int vocab, const float *__res
     }
 }
 
-// Final merge and routing decision: grid n_rows, block 64 (one wave).
+// Final merge and routing decision: grid n_rows, block 256.
 // row_bad: optional per-row flag (nonzero = the row's inputs were out of range).
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
 k_route_merge(const SoftPartial *__restrict__ parts, int n_parts, int vocab, float tau, int active,
               const int *__restrict__ row_bad, rs_route_out *__restrict__ out) {
-    const int row = blockIdx.x, lane = threadIdx.x;
+    const int row = blockIdx.x, tid = threadIdx.x;
     SoftState st; st.init();
-    for (int p = lane; p < n_parts; p += 64) st.merge(from_partial(parts[(size_t)row * n_parts + p]));
+    for (int p = tid; p < n_parts; p += 256) st.merge(from_partial(parts[(size_t)row * n_parts + p]));
     wave_merge_state(st);
-    if (lane != 0) return;
+    __shared__ SoftPartial sh[4];
+    if ((tid & 63) == 0) sh[tid >> 6] = to_partial(st);
+    __syncthreads();
+    if (tid != 0) return;
+    st = from_partial(sh[0]);
+    for (int w = 1; w < 4; ++w) st.merge(from_partial(sh[w]));
     rs_route_out r;
     uint32_t flags = 0;
     const bool bad = row_bad && row_bad[row];

@@ -70,7 +70,7 @@ struct Layout {
     int lm_parts_cap;         // partial states per sequence
 };
 
-int attn_pairs_cap(const rs_config &c) { return c.max_rows > 512 / c.n_kv_heads ? c.max_rows : 512 / c.n_kv_heads; }
+int attn_pairs_cap(const rs_config &c) { return c.max_rows > 256 ? c.max_rows : 256; }
 
 constexpr int LM_PARTS_CAP = 4096;
 
@@ -97,7 +97,7 @@ Layout make_layout(const rs_config &c) {
     L.act = take((size_t)c.d_ffn * 4);
     L.act_pl = take((size_t)3 * c.max_rows * c.d_ffn * 2);
     L.attn_rows_x_splits = attn_pairs_cap(c);
-    L.attn_part = take((size_t)L.attn_rows_x_splits * c.n_q_heads * (c.head_dim + 2) * 4);
+    L.attn_part = take((size_t)L.attn_rows_x_splits * c.n_q_heads * (c.head_dim + 4) * 4);
     L.attn_cnt = take((size_t)c.max_rows * c.n_kv_heads * 4);
     L.lm_pl = take((size_t)3 * c.max_seqs * c.d_model * 2);
     L.lm_parts_cap = LM_PARTS_CAP;
@@ -116,6 +116,8 @@ struct rs_model {
     std::vector<const uint16_t *> attn_norm, w_qkv, w_o, mlp_norm, w_gate_up, w_down;
     uint16_t *kv_k, *kv_v;
     unsigned char *ws;
+    int timer_phase = -1, timer_layer = 0;
+    hipEvent_t timer_start = nullptr, timer_stop = nullptr;
 
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
 };
@@ -154,22 +156,42 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, hipStream
     return RS_OK;
 }
 
-template <int MODE>
-rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
-    int blocks = gemv_blocks((n_tiles + 3) / 4, m->n_cu, 4);
-    if (MODE == G_LMHEAD) {
-        if (blocks * 4 > LM_PARTS_CAP) blocks = LM_PARTS_CAP / 4;                     // one partial per wave
-        a.n_parts = blocks * 4;
-    }
-    const int nb = (a.M + 15) / 16;
-    switch (nb) {
-        case 1: hipLaunchKernelGGL((k_gemm_rows<MODE, 1>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((k_gemm_rows<MODE, 2>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((k_gemm_rows<MODE, 3>), dim3(blocks), dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((k_gemm_rows<MODE, 4>), dim3(blocks), dim3(256), 0, st, a); break;
+template <int MODE, int NB>
+rs_status launch_gemm_nb(GemmArgs &a, int blocks, int nw, hipStream_t st, const char *name) {
+    switch (nw) {
+        case 1: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 1>), dim3(blocks), dim3(64), 0, st, a); break;
+        case 4: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 4>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 8: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 8>), dim3(blocks), dim3(512), 0, st, a); break;
+        default: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 16>), dim3(blocks), dim3(1024), 0, st, a); break;
     }
     RS_LAUNCHED(name);
     return RS_OK;
+}
+
+// n_tiles = number of 16-column output tiles
+template <int MODE>
+rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
+    const int nb = (a.M + 15) / 16;
+    const int nt = (MODE == G_GATEUP) ? 2 : 1;
+    const int kblocks = a.K / 128;
+    // waves per workgroup: enough to put ~2000 waves on the chip, bounded by K and by the LDS
+    // used for the cross-wave sum (1 KB per wave, tile and token block)
+    int nw = n_tiles >= 512 ? 4 : (n_tiles >= 256 ? 8 : 16);
+    while (nw > 1 && (nw > kblocks || nw * nt * nb > 32)) nw >>= 1;
+    if (nw == 2) nw = 1;
+    int blocks = n_tiles < 2048 ? n_tiles : 2048;
+    if (MODE == G_LMHEAD) {
+        if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;                 // one partial per workgroup
+        a.n_parts = blocks;
+    }
+    (void)m;
+    if (MODE == G_LMHEAD) return launch_gemm_nb<MODE, 1>(a, blocks, nw, st, name);
+    switch (nb) {
+        case 1: return launch_gemm_nb<MODE, 1>(a, blocks, nw, st, name);
+        case 2: return launch_gemm_nb<MODE, 2>(a, blocks, nw, st, name);
+        case 3: return launch_gemm_nb<MODE, 3>(a, blocks, nw, st, name);
+        default: return launch_gemm_nb<MODE, 4>(a, blocks, nw, st, name);
+    }
 }
 
 // One forward invocation over n_rows token rows of n_seqs sequences.
@@ -194,14 +216,21 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
     RS_LAUNCHED("prepare");
 
     // attention launch shape
-    int n_splits = 512 / (c.n_kv_heads * n_rows);
-    const int by_ctx = (c.max_ctx + 63) / 64;
-    if (n_splits > by_ctx) n_splits = by_ctx;
-    if (n_splits < 1) n_splits = 1;
+    const int att_ts = 16384 / c.head_dim;                 // tokens one attention workgroup takes per round trip
+    int n_splits = (c.max_ctx + att_ts - 1) / att_ts;
+    if (n_splits > ATT_SMAX) n_splits = ATT_SMAX;
     if (n_splits * n_rows > L.attn_rows_x_splits) n_splits = L.attn_rows_x_splits / n_rows;
+    if (n_splits < 1) n_splits = 1;
 
     const bool single = (n_rows == 1);
     rs_status rc;
+    // optional event pair around one chosen kernel (rs_set_phase_timer)
+    auto tic = [&](int phase, int layer) {
+        if (m->timer_phase == phase && (phase == RS_PHASE_LMHEAD || m->timer_layer == layer)) (void)hipEventRecord(m->timer_start, st);
+    };
+    auto toc = [&](int phase, int layer) {
+        if (m->timer_phase == phase && (phase == RS_PHASE_LMHEAD || m->timer_layer == layer)) (void)hipEventRecord(m->timer_stop, st);
+    };
     for (int l = 0; l < c.n_layers; ++l) {
         AttnArgs aa{};
         aa.qbuf = m->at<float>(L.qbuf); aa.kcache = m->kv_k; aa.vcache = m->kv_v;
@@ -223,6 +252,7 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
 
             // QKV (+ RMSNorm, RoPE, KV write)
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
+            tic(RS_PHASE_QKV, l);
             if (qkv_rows <= 4096) {
                 const int tiles = (c.n_q_heads + c.n_kv_heads) * (hd / 2) + (c.n_kv_heads * hd) / 2;
                 rc = launch_gemv<G_QKV, 2, 1>(m, g, tiles, st, "gemv_qkv");
@@ -230,30 +260,39 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
                 const int tiles = (c.n_q_heads + c.n_kv_heads) * (hd / 4) + (c.n_kv_heads * hd) / 4;
                 rc = launch_gemv<G_QKV, 4, 1>(m, g, tiles, st, "gemv_qkv");
             }
+            toc(RS_PHASE_QKV, l);
             if (rc) return rc;
             // attention
+            tic(RS_PHASE_ATTN, l);
             switch (hd) {
                 case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, 1, st); break;
                 case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, 1, st); break;
                 default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, 1, st); break;
             }
+            toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
             // O projection + residual
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.attn_out);
+            tic(RS_PHASE_OPROJ, l);
             if (c.d_model <= 2048) rc = launch_gemv<G_OPROJ, 2, 1>(m, g, (c.d_model + 1) / 2, st, "gemv_oproj");
             else rc = launch_gemv<G_OPROJ, 4, 1>(m, g, (c.d_model + 3) / 4, st, "gemv_oproj");
+            toc(RS_PHASE_OPROJ, l);
             if (rc) return rc;
             // gate/up (+ RMSNorm, SwiGLU)
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
+            tic(RS_PHASE_GATEUP, l);
             rc = launch_gemv<G_GATEUP, 4, 1>(m, g, c.d_ffn / 2, st, "gemv_gateup");
+            toc(RS_PHASE_GATEUP, l);
             if (rc) return rc;
             // down + residual
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.act);
+            tic(RS_PHASE_DOWN, l);
             if (c.d_ffn > GEMV_KSEG) rc = launch_gemv<G_DOWN, 8, 4>(m, g, (c.d_model + 7) / 8, st, "gemv_down");
             else if (c.d_model <= 2048) rc = launch_gemv<G_DOWN, 2, 4>(m, g, (c.d_model + 1) / 2, st, "gemv_down");
             else rc = launch_gemv<G_DOWN, 4, 4>(m, g, (c.d_model + 3) / 4, st, "gemv_down");
+            toc(RS_PHASE_DOWN, l);
             if (rc) return rc;
         } else {
             uint16_t *xn = m->at<uint16_t>(L.xn);
@@ -265,7 +304,9 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             RS_LAUNCHED("rmsnorm_rows");
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
             g.out_f32 = m->at<float>(L.qkv_raw); g.ld_out = qkv_rows;
-            if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 31) / 32, st, "gemm_qkv"))) return rc;
+            tic(RS_PHASE_QKV, l);
+            if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv"))) return rc;
+            toc(RS_PHASE_QKV, l);
             RopeArgs ra{};
             ra.qkv = m->at<float>(L.qkv_raw); ra.qbuf = m->at<float>(L.qbuf); ra.kcache = m->kv_k; ra.vcache = m->kv_v;
             ra.rope_cos = m->at<float>(L.rope_cos); ra.rope_sin = m->at<float>(L.rope_sin);
@@ -274,25 +315,33 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             ra.max_seqs = c.max_seqs; ra.layer = l;
             hipLaunchKernelGGL(k_rope_kv_rows, dim3(n_rows), dim3(256), 0, st, ra);
             RS_LAUNCHED("rope_kv_rows");
+            tic(RS_PHASE_ATTN, l);
             switch (hd) {
                 case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
                 case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
                 default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
             }
+            toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim;
             g.X = m->at<uint16_t>(L.attn_pl); g.x_plane = (size_t)c.max_rows * qdim;
             g.h_out = h; g.ld_h = c.d_model;
-            if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 31) / 32, st, "gemm_oproj"))) return rc;
+            tic(RS_PHASE_OPROJ, l);
+            if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj"))) return rc;
+            toc(RS_PHASE_OPROJ, l);
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, (const float *)h, m->mlp_norm[l], c.rms_eps,
                                c.d_model, (const int *)nullptr, xn, xn_plane);
             RS_LAUNCHED("rmsnorm_rows");
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
             g.act = m->at<uint16_t>(L.act_pl); g.act_plane = (size_t)c.max_rows * c.d_ffn;
+            tic(RS_PHASE_GATEUP, l);
             if ((rc = launch_gemm<G_GATEUP>(m, g, (c.d_ffn + 15) / 16, st, "gemm_gateup"))) return rc;
+            toc(RS_PHASE_GATEUP, l);
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn;
             g.X = m->at<uint16_t>(L.act_pl); g.x_plane = (size_t)c.max_rows * c.d_ffn;
-            if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 31) / 32, st, "gemm_down"))) return rc;
+            tic(RS_PHASE_DOWN, l);
+            if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down"))) return rc;
+            toc(RS_PHASE_DOWN, l);
         }
     }
 
@@ -304,7 +353,9 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
         int blocks = 0;
+        tic(RS_PHASE_LMHEAD, 0);
         if ((rc = launch_gemv<G_LMHEAD, 8, 1>(m, g, (c.vocab + 7) / 8, st, "gemv_lmhead", &blocks))) return rc;
+        toc(RS_PHASE_LMHEAD, 0);
         n_parts = blocks * 4;
     } else {
         uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
@@ -315,11 +366,13 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
         GemmArgs g{};
         g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
-        if ((rc = launch_gemm<G_LMHEAD>(m, g, (c.vocab + 31) / 32, st, "gemm_lmhead"))) return rc;
+        tic(RS_PHASE_LMHEAD, 0);
+        if ((rc = launch_gemm<G_LMHEAD>(m, g, (c.vocab + 15) / 16, st, "gemm_lmhead"))) return rc;
+        toc(RS_PHASE_LMHEAD, 0);
         n_parts = g.n_parts;
     }
     if (n_parts > L.lm_parts_cap) return fail(RS_EINVAL, "internal: %d router partials exceed capacity", n_parts);
-    hipLaunchKernelGGL(k_route_merge, dim3(n_seqs), dim3(64), 0, st, (const SoftPartial *)parts, n_parts, c.vocab, tau,
+    hipLaunchKernelGGL(k_route_merge, dim3(n_seqs), dim3(256), 0, st, (const SoftPartial *)parts, n_parts, c.vocab, tau,
                        active, (const int *)m->at<int>(L.seq_bad), d_out);
     RS_LAUNCHED("route_merge");
     return RS_OK;
@@ -438,6 +491,17 @@ rs_status rs_catchup_prefill(rs_model *m, int32_t n_seqs, int32_t n_rows, const 
                    d_logits, (hipStream_t)stream);
 }
 
+rs_status rs_set_phase_timer(rs_model *m, int32_t phase, int32_t layer, void *start_event, void *stop_event) {
+    if (!m) return fail(RS_EINVAL, "null model");
+    if (phase < 0) { m->timer_phase = -1; m->timer_start = m->timer_stop = nullptr; return RS_OK; }
+    if (phase > RS_PHASE_ATTN) return fail(RS_EINVAL, "unknown phase %d", phase);
+    if (!start_event || !stop_event) return fail(RS_EINVAL, "null event");
+    if (phase != RS_PHASE_LMHEAD && (layer < 0 || layer >= m->cfg.n_layers)) return fail(RS_EINVAL, "layer %d out of range", layer);
+    m->timer_phase = phase; m->timer_layer = layer;
+    m->timer_start = (hipEvent_t)start_event; m->timer_stop = (hipEvent_t)stop_event;
+    return RS_OK;
+}
+
 static int route_parts(int vocab) {
     int p = (vocab / 4 + 255) / 256;      // one float4 per thread and pass
     if (p < 1) p = 1;
@@ -463,7 +527,7 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab, const float 
     hipLaunchKernelGGL(rs::k_route_partials, dim3(parts, n), dim3(256), 0, st, d_logits, vocab, d_logit_scale,
                        (rs::SoftPartial *)d_scratch);
     RS_LAUNCHED("route_partials");
-    hipLaunchKernelGGL(rs::k_route_merge, dim3(n), dim3(64), 0, st, (const rs::SoftPartial *)d_scratch, parts, vocab, tau,
+    hipLaunchKernelGGL(rs::k_route_merge, dim3(n), dim3(256), 0, st, (const rs::SoftPartial *)d_scratch, parts, vocab, tau,
                        active, (const int *)nullptr, d_out);
     RS_LAUNCHED("route_merge");
     return RS_OK;
