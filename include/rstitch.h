@@ -25,6 +25,13 @@
  *     valid once the caller has synchronised that stream.  `stream` is a
  *     hipStream_t passed as void* (NULL = the default stream).  Two calls that
  *     use the same rs_model must not run concurrently.
+ *   - A forward call is a sequence of ~170 small kernels.  When a call repeats
+ *     an earlier call's argument VALUES (same pointers, counts, tau, role and a
+ *     non-default stream), the library replays a cached HIP graph of that
+ *     sequence; the kernels read tokens, positions and scales from the caller's
+ *     buffers when they run, so a serving loop that keeps its buffers at fixed
+ *     addresses pays one graph launch per step.  RSTITCH_GRAPHS=0 in the
+ *     environment (read by rs_create_model) disables this.
  *   - No call throws.  Every call returns an rs_status; on failure
  *     rs_last_error() describes the most recent failure on the calling thread.
  *   - Arguments the host can see (sizes, counts, null pointers) are checked
@@ -62,6 +69,8 @@ typedef int32_t rs_status;
 #define RS_FLAG_NEXT_LLM   4u  /* the model to run next is the LLM (== HI)                            */
 #define RS_FLAG_NONFINITE  8u  /* a logit was NaN/Inf; HI is forced, entropy fields are NaN           */
 #define RS_FLAG_BADARG    16u  /* a device-side position/token/slot was out of range; record invalid */
+#define RS_FLAG_ABORTED   32u  /* a bounded wait inside a kernel ran out: the step did not complete,
+                                  the record is invalid and the model refuses further steps          */
 
 typedef struct rs_config {
     int32_t n_layers;
@@ -72,7 +81,7 @@ typedef struct rs_config {
     int32_t d_ffn;         /* multiple of 8                                                  */
     int32_t vocab;         /* >= 2                                                           */
     int32_t tied_lm_head;  /* informational; lm_head may simply alias embed                  */
-    int32_t max_ctx;       /* positions per sequence slot in the KV cache                    */
+    int32_t max_ctx;       /* positions per sequence slot in the KV cache; multiple of 8     */
     int32_t max_seqs;      /* sequence slots in the KV cache (1..8)                          */
     int32_t max_rows;      /* most token rows one call may carry (1..64)                     */
     float   rms_eps;
@@ -116,7 +125,10 @@ int32_t rs_abi_version(void);
 size_t rs_workspace_bytes(const rs_config *cfg);
 
 /* Bytes of one KV buffer (K or V): n_layers * max_seqs * n_kv_heads * max_ctx *
- * head_dim * 2.  Layout [layer][slot][kv_head][position][head_dim], bf16. */
+ * head_dim * 2, bf16.  K is laid out [layer][slot][kv_head][position][head_dim];
+ * V is laid out [layer][slot][kv_head][head_dim][position] (transposed, so that
+ * the attention kernel can feed consecutive positions of one channel to the
+ * matrix cores without a shuffle). */
 size_t rs_kv_bytes(const rs_config *cfg);
 
 /* Bind weights, KV caches and workspace into a handle.  Builds the rotary
@@ -193,7 +205,16 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
  * phase `phase` (RS_PHASE_*) in layer `layer` (layer is ignored for
  * RS_PHASE_LMHEAD).  Both are caller-owned hipEvent_t handles passed as void*;
  * the caller reads them with hipEventElapsedTime after synchronising.
- * phase < 0 disarms.  Errors: RS_EINVAL (null model/event, layer out of range). */
+ * phase < 0 disarms.  While armed, single-row steps run as one kernel per phase
+ * instead of the single-kernel step, so that there is a kernel to bracket.
+ * Errors: RS_EINVAL (null model/event, layer out of range). */
+/* Test aid: the single-kernel decode step separates its phases with grid-wide
+ * waits that give up after `polls` polls (default 2^22, about a second) instead
+ * of hanging; a tiny value forces that error path from the host.  0 restores the
+ * default.  After a wait has given up the model is unusable (RS_FLAG_ABORTED on
+ * every record) until it is created again. */
+rs_status rs_set_spin_limit(rs_model *model, uint32_t polls);
+
 #define RS_PHASE_QKV     0
 #define RS_PHASE_OPROJ   1
 #define RS_PHASE_GATEUP  2

@@ -16,7 +16,7 @@ from typing import List, Optional, Sequence
 import torch
 
 RS_SLM, RS_LLM = 0, 1
-FLAG_HI, FLAG_ACCEPT, FLAG_NEXT_LLM, FLAG_NONFINITE, FLAG_BADARG = 1, 2, 4, 8, 16
+FLAG_HI, FLAG_ACCEPT, FLAG_NEXT_LLM, FLAG_NONFINITE, FLAG_BADARG, FLAG_ABORTED = 1, 2, 4, 8, 16, 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -70,6 +70,8 @@ def _load() -> C.CDLL:
     lib.rs_route_scratch_bytes.argtypes = [i32, i32]
     lib.rs_route.restype = i32
     lib.rs_route.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp, sz, vp]
+    lib.rs_set_spin_limit.restype = i32
+    lib.rs_set_spin_limit.argtypes = [vp, C.c_uint32]
     lib.rs_set_phase_timer.restype = i32
     lib.rs_set_phase_timer.argtypes = [vp, i32, i32, vp, vp]
     return lib
@@ -157,6 +159,10 @@ def rs_route(d_logits, n: int, vocab: int, d_logit_scale, tau: float, active: in
 PHASE_QKV, PHASE_OPROJ, PHASE_GATEUP, PHASE_DOWN, PHASE_LMHEAD, PHASE_ATTN = range(6)
 
 
+def rs_set_spin_limit(handle: int, polls: int) -> None:
+    _check(lib.rs_set_spin_limit(handle, polls))
+
+
 def rs_set_phase_timer(handle: int, phase: int, layer: int = 0, start_event: int = 0, stop_event: int = 0) -> None:
     """start_event / stop_event: raw hipEvent_t handles (integers); phase < 0 disarms."""
     _check(lib.rs_set_phase_timer(handle, phase, layer, start_event or None, stop_event or None))
@@ -206,6 +212,7 @@ class Model:
     def __init__(self, weights, max_ctx: int, max_seqs: int = 1, max_rows: int = 64, device="cuda"):
         self.shape = weights.shape
         self.weights = weights                      # bf16 tensors already on `device`
+        max_ctx = (max_ctx + 7) // 8 * 8            # the library wants a multiple of 8
         self.cfg = make_config(self.shape, max_ctx, max_seqs, max_rows)
         kvb, wsb = rs_kv_bytes(self.cfg), rs_workspace_bytes(self.cfg)
         if kvb == 0 or wsb == 0:
@@ -228,9 +235,11 @@ class Model:
             pass
 
     def kv_view(self, which: str) -> torch.Tensor:
+        """[layer, slot, kv_head, position, head_dim] view of a cache (V is stored transposed)."""
         c = self.cfg
-        t = self.kv_k if which == "k" else self.kv_v
-        return t.view(c.n_layers, c.max_seqs, c.n_kv_heads, c.max_ctx, c.head_dim)
+        if which == "k":
+            return self.kv_k.view(c.n_layers, c.max_seqs, c.n_kv_heads, c.max_ctx, c.head_dim)
+        return self.kv_v.view(c.n_layers, c.max_seqs, c.n_kv_heads, c.head_dim, c.max_ctx).transpose(3, 4)
 
     def _i32(self, values: Sequence[int]) -> torch.Tensor:
         return torch.tensor(list(values), dtype=torch.int32, device=self.device)

@@ -25,9 +25,8 @@ struct PrepArgs {
     float *h;
 };
 
-__global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
-    const int r = blockIdx.x, tid = threadIdx.x;
-    __shared__ int sh[4];     // b, first row, last row (exclusive), bad
+__device__ __forceinline__ void prepare_row(const PrepArgs &a, int r, int *sh /* 4 ints of LDS */) {
+    const int tid = threadIdx.x;
     if (tid == 0) {
         int b = -1, lo = 0, hi = 0, bad = 0;
         if (a.span_off == nullptr) { b = r; lo = r; hi = r + 1; }
@@ -72,6 +71,11 @@ __global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
     for (int i = tid; i < a.d_model; i += 256) h[i] = bf16_to_f32(e[i]);
 }
 
+__global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
+    __shared__ int sh[4];     // b, first row, last row (exclusive), bad
+    prepare_row(a, blockIdx.x, sh);
+}
+
 // ------------------------------------------------------------------------------------------------
 // GEMV phases, one token row.  y[n] = sum_k W[n,k] x[k]: W is bf16, row-major, streamed once from
 // HBM with 16-byte non-temporal loads; x is fp32 and staged in LDS; accumulation is fp32.
@@ -88,7 +92,7 @@ __global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
 // ------------------------------------------------------------------------------------------------
 enum { G_QKV = 0, G_OPROJ = 1, G_GATEUP = 2, G_DOWN = 3, G_LMHEAD = 4 };
 
-constexpr int GEMV_KSEG = 12288;     // fp32 elements of x held in LDS at a time (48 KB)
+constexpr int GEMV_KSEG = 32768;     // fp32 elements of x held in LDS at a time (128 KB of the CU's 160 KB)
 
 struct GemvArgs {
     const uint16_t *W; int N, K;
@@ -114,10 +118,10 @@ __device__ __forceinline__ float dot8f(const uint4 &w, const float4 &xa, const f
 
 // accumulate chunks [c_begin, c_end) of the rows; xs holds the segment starting at chunk seg_c0 as
 // two float4 planes (first and second half of every 8-element chunk) of plane_len chunks each
-template <int RT>
+template <int RT, int UNR>
 __device__ __forceinline__ void gemv_accumulate(const uint4 *const (&wp)[RT], const float4 *__restrict__ xs, int plane_len,
                                                 int seg_c0, int c_begin, int c_end, int cstride, float (&acc)[RT]) {
-#pragma unroll 2
+#pragma unroll UNR
     for (int c = c_begin; c < c_end; c += cstride) {
         uint4 wv[RT];
 #pragma unroll
@@ -128,48 +132,23 @@ __device__ __forceinline__ void gemv_accumulate(const uint4 *const (&wp)[RT], co
     }
 }
 
-template <int MODE, int RT, int KS>
-__global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
+// LDS needed by gemv_phase for a matrix with K columns
+__host__ __device__ constexpr size_t gemv_lds_bytes(int K) { return (size_t)(K < GEMV_KSEG ? K : GEMV_KSEG) * 4 + 512; }
+
+// wg / nwg: index of this workgroup among the workgroups that share the phase.
+// PF > 0: the first PF 16-byte loads per row of the wave's first tile are issued before the
+// prologue (they do not depend on x), so the weight stream starts at kernel entry.
+template <int MODE, int RT, int KS, int UNR = 2, int PF = 0>
+__device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *smem, int wg, int nwg) {
     float4 *xs = reinterpret_cast<float4 *>(smem);
-    __shared__ float red[2][4][RT];
-    __shared__ float red_ss[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int K = a.K;
     const int seg = K < GEMV_KSEG ? K : GEMV_KSEG;       // elements per LDS segment
+    float *red = reinterpret_cast<float *>(smem + (size_t)seg * 4);    // [2][4][RT]
+    float *red_ss = red + 2 * 4 * RT;                                    // [4]
     const int plane_len = seg >> 3;
     const bool resident = K <= GEMV_KSEG;
     constexpr bool NORM = (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD);
-
-    float inv = 1.f;
-    if (NORM) {
-        const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in);
-        float ss = 0.f;
-        for (int i = tid; i < (K >> 2); i += 256) {
-            const float4 v = h4[i];
-            ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
-        }
-        ss = wave_sum(ss);
-        if (lane == 0) red_ss[wave] = ss;
-        __syncthreads();
-        inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)K + a.eps);
-    }
-    // stage the K-range [k0, k0+len) of x: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
-    auto stage = [&](int k0, int len) {
-        if (NORM) {
-            const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in + k0);
-            const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain + k0);
-            for (int i = tid; i < (len >> 2); i += 256) {
-                float4 v = h4[i]; const uint2 g = g2[i];
-                v.x *= inv * bf16_lo(g.x); v.y *= inv * bf16_hi(g.x); v.z *= inv * bf16_lo(g.y); v.w *= inv * bf16_hi(g.y);
-                xs[(i & 1) * plane_len + (i >> 1)] = v;
-            }
-        } else {
-            const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in + k0);
-            for (int i = tid; i < (len >> 2); i += 256) xs[(i & 1) * plane_len + (i >> 1)] = x4[i];
-        }
-    };
-    if (resident) { stage(0, K); __syncthreads(); }
 
     // ---- tiles
     constexpr int P = RT / 2;
@@ -183,18 +162,16 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
     } else {
         n_tiles = (a.N + RT - 1) / RT;
     }
-    const int unit0 = (KS == 1) ? blockIdx.x * 4 + wave : blockIdx.x;
-    const int ustride = (KS == 1) ? gridDim.x * 4 : gridDim.x;
+    // each workgroup owns a contiguous range of tiles (a contiguous stretch of W); with KS == 1 its
+    // four waves interleave inside that range
+    const int t_lo = (int)(((long long)n_tiles * wg) / nwg), t_hi = (int)(((long long)n_tiles * (wg + 1)) / nwg);
+    const int unit0 = (KS == 1) ? t_lo + wave : t_lo;
+    const int ustride = (KS == 1) ? 4 : 1;
     const int c0 = (KS == 1) ? lane : wave * 64 + lane;
     const int cstride = 64 * KS;
 
-    SoftState st; st.init();
-    const float lm_scale = (MODE == G_LMHEAD) ? a.seq_scale[0] : 1.f;
-    int parity = 0;
-
-    for (int t = unit0; t < n_tiles; t += ustride) {
-        int rows[RT];
-        int head = 0, pair0 = 0; bool rot = false;
+    auto tile_rows = [&](int t, int (&rows)[RT], int &head, int &pair0, bool &rot) {
+        head = 0; pair0 = 0; rot = false;
         if (MODE == G_QKV) {
             if (t < n_rot_tiles) {
                 rot = true; head = t / (half / P); pair0 = (t % (half / P)) * P;
@@ -211,19 +188,134 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 #pragma unroll
             for (int j = 0; j < RT; ++j) rows[j] = min(t * RT + j, a.N - 1);
         }
+    };
+
+    // row position / slot (QKV only), read once up front so that no epilogue waits on it
+    int row_bad = 0, row_pos = 0, row_slot = 0;
+    if (MODE == G_QKV) { row_bad = a.row_bad[0]; row_pos = a.row_pos[0]; row_slot = a.row_slot[0]; }
+
+    // ---- early weight loads of the first tile
+    constexpr int NPF = PF > 0 ? PF : 1;
+    uint4 pre[RT][NPF];
+    if (PF > 0 && unit0 < t_hi) {
+        int rows[RT]; int hd_, p0_; bool rot_;
+        tile_rows(unit0, rows, hd_, p0_, rot_);
+#pragma unroll
+        for (int j = 0; j < NPF; ++j) {
+            const int c = c0 + j * cstride;
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                pre[r][j] = make_uint4(0, 0, 0, 0);
+                if (c < (K >> 3)) pre[r][j] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K) + c);
+            }
+        }
+    }
+
+    // ---- prologue: x (fp32) into LDS
+    float inv = 1.f;
+    constexpr int HCACHE = 6;                 // float4 per thread kept between the two passes over h (K <= 6144)
+    float4 hreg[HCACHE];
+    uint2 greg[HCACHE];
+    if (NORM) {
+        const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in);
+        const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain);
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < HCACHE; ++j) {
+            const int i = tid + j * 256;
+            hreg[j] = make_float4(0.f, 0.f, 0.f, 0.f); greg[j] = make_uint2(0, 0);
+            if (i < (K >> 2)) { hreg[j] = h4[i]; greg[j] = g2[i]; }
+        }
+#pragma unroll
+        for (int j = 0; j < HCACHE; ++j) {
+            ss = fmaf(hreg[j].x, hreg[j].x, ss); ss = fmaf(hreg[j].y, hreg[j].y, ss);
+            ss = fmaf(hreg[j].z, hreg[j].z, ss); ss = fmaf(hreg[j].w, hreg[j].w, ss);
+        }
+        for (int i = tid + HCACHE * 256; i < (K >> 2); i += 256) {
+            const float4 v = h4[i];
+            ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) red_ss[wave] = ss;
+        __syncthreads();
+        inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)K + a.eps);
+    }
+    // stage the K-range [k0, k0+len) of x: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
+    auto stage = [&](int k0, int len) {
+        if (NORM) {                       // k0 == 0 and len == K in the norm phases (K fits one segment)
+            const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in + k0);
+            const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain + k0);
+#pragma unroll
+            for (int j = 0; j < HCACHE; ++j) {
+                const int i = tid + j * 256;
+                if (i < (len >> 2)) {
+                    float4 v = hreg[j]; const uint2 g = greg[j];
+                    v.x *= inv * bf16_lo(g.x); v.y *= inv * bf16_hi(g.x); v.z *= inv * bf16_lo(g.y); v.w *= inv * bf16_hi(g.y);
+                    xs[(i & 1) * plane_len + (i >> 1)] = v;
+                }
+            }
+            for (int i = tid + HCACHE * 256; i < (len >> 2); i += 256) {
+                float4 v = h4[i]; const uint2 g = g2[i];
+                v.x *= inv * bf16_lo(g.x); v.y *= inv * bf16_hi(g.x); v.z *= inv * bf16_lo(g.y); v.w *= inv * bf16_hi(g.y);
+                xs[(i & 1) * plane_len + (i >> 1)] = v;
+            }
+        } else {
+            const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in + k0);
+            for (int i = tid; i < (len >> 2); i += 256) xs[(i & 1) * plane_len + (i >> 1)] = x4[i];
+        }
+    };
+    if (resident) { stage(0, K); __syncthreads(); }
+
+    SoftState st; st.init();
+    const float lm_scale = (MODE == G_LMHEAD) ? a.seq_scale[0] : 1.f;
+    int parity = 0;
+
+    for (int t = unit0; t < t_hi; t += ustride) {
+        int rows[RT];
+        int head, pair0; bool rot;
+        tile_rows(t, rows, head, pair0, rot);
         const uint4 *wp[RT];
         float acc[RT];
 #pragma unroll
         for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K); acc[r] = 0.f; }
+        // what the epilogue will need from memory is requested now, ahead of the weight stream
+        float epi[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) epi[r] = 0.f;
+        if (MODE == G_QKV) {
+            if (rot && !row_bad) {
+#pragma unroll
+                for (int j = 0; j < P; ++j) {
+                    epi[2 * j] = a.rope_cos[(size_t)row_pos * half + pair0 + j];
+                    epi[2 * j + 1] = a.rope_sin[(size_t)row_pos * half + pair0 + j];
+                }
+            }
+        } else if (MODE == G_OPROJ || MODE == G_DOWN) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) epi[r] = a.h_out[rows[r]];
+        }
         if (resident) {
-            gemv_accumulate<RT>(wp, xs, plane_len, 0, c0, K >> 3, cstride, acc);
+            int c_start = c0;
+            if (PF > 0 && t == unit0) {
+#pragma unroll
+                for (int j = 0; j < NPF; ++j) {
+                    const int c = c0 + j * cstride;
+                    if (c < (K >> 3)) {
+                        const float4 xa = xs[c], xb = xs[plane_len + c];
+#pragma unroll
+                        for (int r = 0; r < RT; ++r) acc[r] = dot8f(pre[r][j], xa, xb, acc[r]);
+                    }
+                }
+                c_start = c0 + NPF * cstride;
+            }
+            gemv_accumulate<RT, UNR>(wp, xs, plane_len, 0, c_start, K >> 3, cstride, acc);
         } else {
             for (int k0 = 0; k0 < K; k0 += GEMV_KSEG) {        // KS == 4 only: the tile loop is workgroup-uniform
                 const int len = min(GEMV_KSEG, K - k0);
                 __syncthreads();
                 stage(k0, len);
                 __syncthreads();
-                gemv_accumulate<RT>(wp, xs, plane_len, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, cstride, acc);
+                gemv_accumulate<RT, UNR>(wp, xs, plane_len, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, cstride, acc);
             }
         }
 #pragma unroll
@@ -231,11 +323,13 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
         if (KS > 1) {
             if (lane == 0) {
 #pragma unroll
-                for (int r = 0; r < RT; ++r) red[parity][wave][r] = acc[r];
+                for (int r = 0; r < RT; ++r) red[(parity * 4 + wave) * RT + r] = acc[r];
             }
             __syncthreads();
 #pragma unroll
-            for (int r = 0; r < RT; ++r) acc[r] = red[parity][0][r] + red[parity][1][r] + red[parity][2][r] + red[parity][3][r];
+            for (int r = 0; r < RT; ++r)
+                acc[r] = red[(parity * 4 + 0) * RT + r] + red[(parity * 4 + 1) * RT + r] + red[(parity * 4 + 2) * RT + r] +
+                         red[(parity * 4 + 3) * RT + r];
             parity ^= 1;
         }
         const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
@@ -243,14 +337,13 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 
         // ---- epilogue (one lane)
         if (MODE == G_QKV) {
-            if (a.row_bad[0]) continue;
-            const int pos = a.row_pos[0], slot = a.row_slot[0];
+            if (row_bad) continue;
+            const int pos = row_pos, slot = row_slot;
             if (rot) {
-                const float *cs = a.rope_cos + (size_t)pos * half, *sn = a.rope_sin + (size_t)pos * half;
 #pragma unroll
                 for (int j = 0; j < P; ++j) {
                     const int i = pair0 + j;
-                    const float c = cs[i], s = sn[i], x0 = acc[2 * j], x1 = acc[2 * j + 1];
+                    const float c = epi[2 * j], s = epi[2 * j + 1], x0 = acc[2 * j], x1 = acc[2 * j + 1];
                     const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
                     if (head < a.n_q) {
                         a.qbuf[head * a.head_dim + i] = y0; a.qbuf[head * a.head_dim + i + half] = y1;
@@ -264,8 +357,8 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
                 for (int j = 0; j < RT; ++j) {
                     const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
                     const int vh = vr / a.head_dim, e = vr % a.head_dim;
-                    const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * a.max_ctx + pos) * a.head_dim;
-                    a.vcache[base + e] = f32_to_bf16(acc[j]);
+                    const size_t base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * (size_t)a.max_ctx * a.head_dim;
+                    a.vcache[base + (size_t)e * a.max_ctx + pos] = f32_to_bf16(acc[j]);     // V is stored [hd][position]
                 }
             }
         } else if (MODE == G_GATEUP) {
@@ -276,7 +369,7 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
             }
         } else if (MODE == G_OPROJ || MODE == G_DOWN) {
 #pragma unroll
-            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[t * RT + j] += acc[j];
+            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[t * RT + j] = epi[j] + acc[j];
         } else {   // G_LMHEAD
 #pragma unroll
             for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
@@ -288,233 +381,296 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
     }
     if (MODE == G_LMHEAD) {
         const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
-        if (writer) a.parts[(KS == 1) ? blockIdx.x * 4 + wave : blockIdx.x] = to_partial(st);
+        if (writer) a.parts[(KS == 1) ? wg * 4 + wave : wg] = to_partial(st);
     }
 }
 
+template <int MODE, int RT, int KS, int UNR = 2, int PF = 0>
+__global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    gemv_phase<MODE, RT, KS, UNR, PF>(a, smem, blockIdx.x, gridDim.x);
+}
+
 // ------------------------------------------------------------------------------------------------
-// Split-K grouped-query decode attention.  grid (n_splits, n_kv_heads, n_rows), block 256.
-// A workgroup owns one KV head, one slice of the context and ALL query heads of that KV head's
-// group, so every K/V byte is read once per row.  Per sub-chunk of TS tokens every thread issues
-// its 8 K loads and 8 V loads (16 bytes each) up front, so the whole sub-chunk costs one memory
-// round trip; scores go through LDS (one exp per score); running max / sum are carried across
-// sub-chunks.  The last workgroup to finish for a (row, kv head) merges the slices.
-// Partial record per (row, q head, split): [m, l, 0, 0, acc[HD]] fp32.
+// Split-K grouped-query decode attention in two kernels.
+//
+// k_attn_partial: grid (n_slices, n_kv_heads, n_rows), block 256.  A workgroup owns one KV head,
+// one slice of the context and ALL query heads of that KV head's group, so every K/V byte is read
+// once per row.  Both contractions run on the matrix cores (v_mfma_f32_16x16x32_bf16):
+//   scores[token, head] = sum_d K[token, d] q[head, d]     A = K rows (16 tokens x 32 d, 16-byte
+//                                                           loads straight from the cache),
+//                                                           B = q as three bf16 planes (exact fp32)
+//   out[d, head]        = sum_t V[t, d] p[head, t]          A = V, which the cache stores TRANSPOSED
+//                                                           ([head_dim][position]) so that a lane's
+//                                                           8 tokens are contiguous, B = p as three
+//                                                           bf16 planes taken directly from the score
+//                                                           accumulator registers (the token <-> k
+//                                                           slot assignment is free as long as both
+//                                                           operands agree)
+// A wave handles 64 tokens per pass with an online softmax; the four waves are merged through LDS
+// and the workgroup writes one partial record per query head: [m, l, 0, 0, acc[HD]] fp32.
+//
+// k_attn_combine: grid (n_q_heads, n_rows), block 256: merges the slices of one head.
 // ------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
 struct AttnArgs {
     const float *qbuf;             // [rows, n_q*hd] fp32, rotated
-    const uint16_t *kcache, *vcache;
-    float *partials;               // [rows, n_q, n_splits, hd+4]
-    int *counters;                 // [rows, n_kv], zero between launches
+    const uint16_t *kcache;        // [layer][slot][kv_head][position][hd] bf16
+    const uint16_t *vcache;        // [layer][slot][kv_head][hd][position] bf16
+    float *partials;               // [rows, n_q, n_slices, hd+4]
     float *out;                    // [rows, n_q*hd] fp32
     uint16_t *out_planes; size_t out_plane;   // optional three-plane bf16 split of the same values, or null
     const int *row_pos, *row_slot, *row_bad;
-    int n_q, n_kv, max_ctx, max_seqs, layer;
+    int n_q, n_kv, max_ctx, max_seqs, layer, n_slices;
 };
 
 constexpr int ATT_GMAX = 8;       // query heads per kv head, at most
-constexpr int ATT_NLD = 8;        // 16-byte K (and V) loads in flight per thread
 constexpr int ATT_SMAX = 64;      // context slices, at most
+constexpr int ATT_WT = 64;        // tokens per wave and pass
+constexpr int ATT_BT = 256;       // tokens per workgroup and pass
+
+// split 8 fp32 values into three bf16x8 planes whose sum is exact
+__device__ __forceinline__ void split3(const float (&x)[8], bf16x8_t (&pl)[3]) {
+    uint32_t w0[4], w1[4], w2[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint16_t a[2], b[2], c[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float v = x[2 * i + h];
+            a[h] = f32_to_bf16(v);
+            const float r1 = v - bf16_to_f32(a[h]);
+            b[h] = f32_to_bf16(r1);
+            c[h] = f32_to_bf16(r1 - bf16_to_f32(b[h]));
+        }
+        w0[i] = (uint32_t)a[0] | ((uint32_t)a[1] << 16);
+        w1[i] = (uint32_t)b[0] | ((uint32_t)b[1] << 16);
+        w2[i] = (uint32_t)c[0] | ((uint32_t)c[1] << 16);
+    }
+    pl[0] = __builtin_bit_cast(bf16x8_t, make_uint4(w0[0], w0[1], w0[2], w0[3]));
+    pl[1] = __builtin_bit_cast(bf16x8_t, make_uint4(w1[0], w1[1], w1[2], w1[3]));
+    pl[2] = __builtin_bit_cast(bf16x8_t, make_uint4(w2[0], w2[1], w2[2], w2[3]));
+}
 
 template <int HD>
-__global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
-    constexpr int LPR = HD / 8, RPW = 64 / LPR, TPI = 4 * RPW;   // lanes per row, rows per wave-load, tokens per load round
-    constexpr int TS = ATT_NLD * TPI;                            // tokens per sub-chunk
-    constexpr int PS = HD + 4;                                   // floats per partial record
-    constexpr int NQ = HD / 4, NSG = 256 / NQ;                   // combine: float4 columns, slice groups
-    const int split = blockIdx.x, S = gridDim.x, kvh = blockIdx.y, row = blockIdx.z;
+__host__ __device__ constexpr size_t attn_lds_bytes() { return (size_t)(4 * 16 * (HD + 4) + 2 * 4 * 16) * 4; }
+
+template <int HD>
+__device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned char *smem, int split, int S, int kvh, int row) {
+    constexpr int NDS = HD / 32;       // 32-wide d steps of the score contraction
+    constexpr int NDB = HD / 16;       // 16-wide d blocks of the output
+    constexpr int PS = HD + 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
     const int G = a.n_q / a.n_kv;
-    const int sub_lane = lane % LPR, grp = lane / LPR, e0 = sub_lane * 8;
 
-    __shared__ float s_lds[ATT_GMAX * TS];                 // scores / probabilities; reused by the combine
-    __shared__ float m_lds[ATT_GMAX], alpha_lds[ATT_GMAX];
-    __shared__ __align__(16) float accw[NSG > 4 ? NSG : 4][ATT_GMAX][HD];   // cross-wave / cross-group sums
-    __shared__ float lw[4][ATT_GMAX];
-    __shared__ int last_flag;
+    float (*acc_lds)[16][HD + 4] = reinterpret_cast<float (*)[16][HD + 4]>(smem);        // [4 waves][16 heads][HD+4]
+    float (*m_lds)[16] = reinterpret_cast<float (*)[16]>(smem + (size_t)4 * 16 * (HD + 4) * 4);   // [4][16]
+    float (*l_lds)[16] = m_lds + 4;
 
-    const int ctx = a.row_bad[row] ? 0 : a.row_pos[row] + 1;
-    const int slot = a.row_bad[row] ? 0 : a.row_slot[row];
+    const int bad = a.row_bad[row];
+    const int ctx = bad ? 0 : a.row_pos[row] + 1;
+    const int slot = bad ? 0 : a.row_slot[row];
     int C = (ctx + S - 1) / S;
-    C = ((C + TPI - 1) / TPI) * TPI;
+    C = ((C + ATT_WT - 1) / ATT_WT) * ATT_WT;
     const int t_begin = split * C;
     const int t_end = min(ctx, t_begin + C);
     const size_t kv_base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + kvh) * (size_t)a.max_ctx * HD;
-    const uint16_t *Kp = a.kcache + kv_base, *Vp = a.vcache + kv_base;
+    const uint16_t *Kp = a.kcache + kv_base;      // [position][hd]
+    const uint16_t *Vp = a.vcache + kv_base;      // [hd][position]
     const float scale = 1.0f / sqrtf((float)HD);
 
-    float q[ATT_GMAX][8], acc[ATT_GMAX][8], l[ATT_GMAX];
-    if (tid < ATT_GMAX) m_lds[tid] = -INFINITY;
+    // q of head j as the B operand of the score contraction: three exact bf16 planes per d step
+    bf16x8_t qB[NDS][3];
 #pragma unroll
-    for (int g = 0; g < ATT_GMAX; ++g) {
-        l[g] = 0.f;
+    for (int ds = 0; ds < NDS; ++ds) {
+        float qv[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { acc[g][j] = 0.f; q[g][j] = 0.f; }
-        if (g < G) {
-            const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + g) * HD + e0);
-            const float4 qa = qp[0], qb = qp[1];
-            q[g][0] = qa.x; q[g][1] = qa.y; q[g][2] = qa.z; q[g][3] = qa.w;
-            q[g][4] = qb.x; q[g][5] = qb.y; q[g][6] = qb.z; q[g][7] = qb.w;
+        for (int e = 0; e < 8; ++e) qv[e] = 0.f;
+        if (j < G) {
+            const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + j) * HD + 32 * ds + 8 * kg);
+            const float4 x0 = qp[0], x1 = qp[1];
+            qv[0] = x0.x; qv[1] = x0.y; qv[2] = x0.z; qv[3] = x0.w; qv[4] = x1.x; qv[5] = x1.y; qv[6] = x1.z; qv[7] = x1.w;
         }
+        split3(qv, qB[ds]);
     }
 
-    for (int sub = t_begin; sub < t_end; sub += TS) {
-        const int n_sub = min(TS, t_end - sub);
-        uint4 kreg[ATT_NLD], vreg[ATT_NLD];
+    float m_run = -INFINITY, l_run = 0.f;          // head j (replicated over the four kg groups)
+    f32x4_t acc[NDB];                              // out[d = 16 db + 4 kg + r][head j]
 #pragma unroll
-        for (int it = 0; it < ATT_NLD; ++it) {
-            const int tl = it * TPI + wave * RPW + grp;
-            kreg[it] = make_uint4(0, 0, 0, 0); vreg[it] = make_uint4(0, 0, 0, 0);
-            if (tl < n_sub) {
-                kreg[it] = *reinterpret_cast<const uint4 *>(Kp + (size_t)(sub + tl) * HD + e0);
-                vreg[it] = *reinterpret_cast<const uint4 *>(Vp + (size_t)(sub + tl) * HD + e0);
+    for (int db = 0; db < NDB; ++db) acc[db] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+    for (int t0 = t_begin + wave * ATT_WT; t0 < t_end; t0 += ATT_BT) {
+        // ---- scores of 4 blocks of 16 tokens
+        f32x4_t sc[4];
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            sc[tb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            const int tok = t0 + tb * 16 + j;                          // A row of this lane
+            uint4 kv[NDS];
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds) {
+                kv[ds] = make_uint4(0, 0, 0, 0);
+                if (tok < t_end) kv[ds] = *reinterpret_cast<const uint4 *>(Kp + (size_t)tok * HD + 32 * ds + 8 * kg);
+            }
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds) {
+                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, kv[ds]);
+#pragma unroll
+                for (int pl = 2; pl >= 0; --pl) sc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc[tb], 0, 0, 0);
             }
         }
-        // scores
+        // ---- V^T operand loads: lane (d = 16 db + j, kg) reads tokens t0 + 32 ks + {4 kg .. +4} and + 16
+        uint2 vv[2][NDB][2];
 #pragma unroll
-        for (int it = 0; it < ATT_NLD; ++it) {
-            const int tl = it * TPI + wave * RPW + grp;
-            const uint4 kv = kreg[it];
-            const float k0 = bf16_lo(kv.x), k1 = bf16_hi(kv.x), k2 = bf16_lo(kv.y), k3 = bf16_hi(kv.y);
-            const float k4 = bf16_lo(kv.z), k5 = bf16_hi(kv.z), k6 = bf16_lo(kv.w), k7 = bf16_hi(kv.w);
-            float part[ATT_GMAX];
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int g = 0; g < ATT_GMAX; ++g) {
-                float p = q[g][0] * k0;
-                p = fmaf(q[g][1], k1, p); p = fmaf(q[g][2], k2, p); p = fmaf(q[g][3], k3, p);
-                p = fmaf(q[g][4], k4, p); p = fmaf(q[g][5], k5, p); p = fmaf(q[g][6], k6, p); p = fmaf(q[g][7], k7, p);
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                for (int o = LPR >> 1; o > 0; o >>= 1) p += __shfl_xor(p, o, RS_WAVE);
-                part[g] = p;
-            }
-            if (sub_lane == 0 && tl < n_sub) {
-#pragma unroll
-                for (int g = 0; g < ATT_GMAX; ++g) if (g < G) s_lds[g * TS + tl] = part[g] * scale;
-            }
-        }
-        __syncthreads();
-        // sub-chunk maxima -> new running maxima and rescale factors (one wave per head)
-        for (int g = wave; g < G; g += 4) {
-            float mx = -INFINITY;
-            for (int i = lane; i < n_sub; i += 64) mx = fmaxf(mx, s_lds[g * TS + i]);
-            mx = wave_max(mx);
-            if (lane == 0) {
-                const float m_old = m_lds[g], m_new = fmaxf(m_old, mx);
-                alpha_lds[g] = (m_old == -INFINITY) ? 0.f : expf(m_old - m_new);
-                m_lds[g] = m_new;
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
-            const float alpha = alpha_lds[g];
-            l[g] *= alpha;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[g][j] *= alpha;
-        }
-        for (int g = 0; g < G; ++g) {
-            const float mg = m_lds[g];
-            for (int i = tid; i < n_sub; i += 256) s_lds[g * TS + i] = expf(s_lds[g * TS + i] - mg);
-        }
-        __syncthreads();
-        // P V
-#pragma unroll
-        for (int it = 0; it < ATT_NLD; ++it) {
-            const int tl = it * TPI + wave * RPW + grp;
-            if (tl < n_sub) {
-                const uint4 vv = vreg[it];
-                const float v0 = bf16_lo(vv.x), v1 = bf16_hi(vv.x), v2 = bf16_lo(vv.y), v3 = bf16_hi(vv.y);
-                const float v4 = bf16_lo(vv.z), v5 = bf16_hi(vv.z), v6 = bf16_lo(vv.w), v7 = bf16_hi(vv.w);
-#pragma unroll
-                for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
-                    const float p = s_lds[g * TS + tl];
-                    l[g] += p;
-                    acc[g][0] = fmaf(p, v0, acc[g][0]); acc[g][1] = fmaf(p, v1, acc[g][1]);
-                    acc[g][2] = fmaf(p, v2, acc[g][2]); acc[g][3] = fmaf(p, v3, acc[g][3]);
-                    acc[g][4] = fmaf(p, v4, acc[g][4]); acc[g][5] = fmaf(p, v5, acc[g][5]);
-                    acc[g][6] = fmaf(p, v6, acc[g][6]); acc[g][7] = fmaf(p, v7, acc[g][7]);
+                for (int hf = 0; hf < 2; ++hf) {
+                    const int tok = t0 + 32 * ks + 16 * hf + 4 * kg;
+                    vv[ks][db][hf] = make_uint2(0, 0);
+                    if (tok < t_end)      // t_end <= max_ctx (multiple of 8): the 4 tokens are inside the row
+                        vv[ks][db][hf] = *reinterpret_cast<const uint2 *>(Vp + (size_t)(16 * db + j) * a.max_ctx + tok);
                 }
+        // ---- online softmax over this pass: lane holds tokens t0 + 16 tb + 4 kg + r of head j
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int tok = t0 + tb * 16 + 4 * kg + r;
+                const float v = tok < t_end ? sc[tb][r] * scale : -INFINITY;
+                sc[tb][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, RS_WAVE));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, RS_WAVE));
+        const float m_new = fmaxf(m_run, mx);                         // finite: the pass has at least one valid token
+        const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) { acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha; }
+        // ---- P V: k slot (kg, e = 4 hf + r) of k-step ks is token t0 + 32 ks + 16 hf + 4 kg + r
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            float pv[8];
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float s_ = sc[2 * ks + hf][r];
+                    const float p = (s_ == -INFINITY) ? 0.f : expf(s_ - m_new);
+                    pv[4 * hf + r] = p;
+                    l_run += p;
+                }
+            bf16x8_t pB[3];
+            split3(pv, pB);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                // tokens past t_end may hold anything (even NaN patterns): they were loaded as zeros above,
+                // but a partially valid group of 4 needs its tail cleared as well
+                uint2 lo = vv[ks][db][0], hi = vv[ks][db][1];
+                const int tok_lo = t0 + 32 * ks + 4 * kg, tok_hi = tok_lo + 16;
+                if (tok_lo + 3 >= t_end) {
+                    if (tok_lo + 1 >= t_end) lo.x &= 0x0000ffffu;
+                    if (tok_lo + 2 >= t_end) lo.y = 0; else if (tok_lo + 3 >= t_end) lo.y &= 0x0000ffffu;
+                    if (tok_lo >= t_end) lo.x = 0;
+                }
+                if (tok_hi + 3 >= t_end) {
+                    if (tok_hi + 1 >= t_end) hi.x &= 0x0000ffffu;
+                    if (tok_hi + 2 >= t_end) hi.y = 0; else if (tok_hi + 3 >= t_end) hi.y &= 0x0000ffffu;
+                    if (tok_hi >= t_end) hi.x = 0;
+                }
+                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, make_uint4(lo.x, lo.y, hi.x, hi.y));
+#pragma unroll
+                for (int pl = 2; pl >= 0; --pl) acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, pB[pl], acc[db], 0, 0, 0);
             }
         }
-        __syncthreads();
     }
+    // l_run so far covers this lane's own tokens: add the other three kg groups
+    l_run += __shfl_xor(l_run, 16, RS_WAVE);
+    l_run += __shfl_xor(l_run, 32, RS_WAVE);
 
-    // reduce over the token groups inside the wave (lanes with equal sub_lane), then over waves
+    // ---- merge the four waves
 #pragma unroll
-    for (int g = 0; g < ATT_GMAX; ++g) {
-#pragma unroll
-        for (int o = LPR; o < 64; o <<= 1) {
-            l[g] += __shfl_xor(l[g], o, RS_WAVE);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[g][j] += __shfl_xor(acc[g][j], o, RS_WAVE);
-        }
-    }
-    if (grp == 0) {
-#pragma unroll
-        for (int g = 0; g < ATT_GMAX; ++g) if (g < G) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) accw[wave][g][e0 + j] = acc[g][j];
-            if (sub_lane == 0) lw[wave][g] = l[g];
-        }
-    }
+    for (int db = 0; db < NDB; ++db)
+        *reinterpret_cast<float4 *>(&acc_lds[wave][j][16 * db + 4 * kg]) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+    if (kg == 0) { m_lds[wave][j] = m_run; l_lds[wave][j] = l_run; }
     __syncthreads();
     for (int i = tid; i < G * HD; i += 256) {
-        const int g = i / HD, e = i - g * HD;
-        const float v = accw[0][g][e] + accw[1][g][e] + accw[2][g][e] + accw[3][g][e];
+        const int g = i / HD, d = i - g * HD;
+        const float m0 = m_lds[0][g], m1 = m_lds[1][g], m2 = m_lds[2][g], m3 = m_lds[3][g];
+        const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+        float L = 0.f, O = 0.f;
+        if (M > -INFINITY) {
+            const float w0 = m0 > -INFINITY ? expf(m0 - M) : 0.f, w1 = m1 > -INFINITY ? expf(m1 - M) : 0.f;
+            const float w2 = m2 > -INFINITY ? expf(m2 - M) : 0.f, w3 = m3 > -INFINITY ? expf(m3 - M) : 0.f;
+            L = l_lds[0][g] * w0 + l_lds[1][g] * w1 + l_lds[2][g] * w2 + l_lds[3][g] * w3;
+            O = acc_lds[0][g][d] * w0 + acc_lds[1][g][d] * w1 + acc_lds[2][g][d] * w2 + acc_lds[3][g][d] * w3;
+        }
         float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
-        p[4 + e] = v;
-        if (e == 0) { p[0] = m_lds[g]; p[1] = lw[0][g] + lw[1][g] + lw[2][g] + lw[3][g]; }
+        p[4 + d] = O;
+        if (d == 0) { p[0] = M; p[1] = L; }
     }
-    // completion ticket
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int old = atomicAdd(&a.counters[row * a.n_kv + kvh], 1);
-        last_flag = (old == S - 1);
-    }
-    __syncthreads();
-    if (!last_flag) return;
-    __threadfence();
+}
 
-    // ---- combine (last workgroup only): weights per (head, slice), then a slice-parallel weighted sum
-    float *m_sh = s_lds, *w_sh = s_lds + ATT_GMAX * ATT_SMAX;       // S <= ATT_SMAX and 2*GMAX*SMAX <= GMAX*TS
-    const float *pbase = a.partials + ((size_t)row * a.n_q + kvh * G) * S * PS;
-    for (int i = tid; i < G * S; i += 256) {
-        const int g = i / S, s = i - g * S;
-        const float2 ml = *reinterpret_cast<const float2 *>(pbase + ((size_t)g * S + s) * PS);
-        m_sh[g * ATT_SMAX + s] = ml.y > 0.f ? ml.x : -INFINITY;
-        w_sh[g * ATT_SMAX + s] = ml.y;
+template <int HD>
+__global__ void __launch_bounds__(256) k_attn_partial(AttnArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    attn_partial_unit<HD>(a, smem, blockIdx.x, gridDim.x, blockIdx.y, blockIdx.z);
+}
+
+// merge the context slices of one (row, query head): 256 threads = (HD/4 float4 columns) x slice groups.
+// smem: ATT_SMAX + (256 / (HD/4)) * HD floats
+template <int HD>
+__host__ __device__ constexpr size_t attn_combine_lds_bytes() { return (size_t)(ATT_SMAX + (256 / (HD / 4)) * HD) * 4; }
+
+template <int HD>
+__device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned char *smem, int head, int row) {
+    constexpr int PS = HD + 4, NQ = HD / 4, NSG = 256 / NQ, NLD = (ATT_SMAX + NSG - 1) / NSG;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int S = a.n_slices;
+    float *w_sh = reinterpret_cast<float *>(smem);                               // [ATT_SMAX]
+    float (*red)[HD] = reinterpret_cast<float (*)[HD]>(w_sh + ATT_SMAX);         // [NSG][HD]
+    const float *pbase = a.partials + ((size_t)row * a.n_q + head) * S * PS;
+    const int qd = tid % NQ, sg = tid / NQ;
+    float4 buf[NLD];
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+        const int s = sg + k * NSG;
+        buf[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s < S) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + 4 * qd);
     }
-    __syncthreads();
-    for (int g = wave; g < G; g += 4) {
-        const float ms = lane < S ? m_sh[g * ATT_SMAX + lane] : -INFINITY;
-        const float ls = lane < S ? w_sh[g * ATT_SMAX + lane] : 0.f;
+    if (wave == 0) {
+        float ms = -INFINITY, ls = 0.f;
+        if (lane < S) {
+            const float2 ml = *reinterpret_cast<const float2 *>(pbase + (size_t)lane * PS);
+            ls = ml.y; ms = ls > 0.f ? ml.x : -INFINITY;
+        }
         const float M = wave_max(ms);
         const float w = ls > 0.f ? expf(ms - M) : 0.f;
         const float L = wave_sum(ls * w);
-        if (lane < S) w_sh[g * ATT_SMAX + lane] = L > 0.f ? w / L : 0.f;
+        w_sh[lane] = L > 0.f ? w / L : 0.f;
     }
     __syncthreads();
-    {
-        const int qd = tid % NQ, sg = tid / NQ;
-        for (int g = 0; g < G; ++g) {
-            float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-            for (int s = sg; s < S; s += NSG) {
-                const float w = w_sh[g * ATT_SMAX + s];
-                const float4 v = *reinterpret_cast<const float4 *>(pbase + ((size_t)g * S + s) * PS + 4 + 4 * qd);
-                sum.x = fmaf(w, v.x, sum.x); sum.y = fmaf(w, v.y, sum.y); sum.z = fmaf(w, v.z, sum.z); sum.w = fmaf(w, v.w, sum.w);
-            }
-            *reinterpret_cast<float4 *>(&accw[sg][g][4 * qd]) = sum;
-        }
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+        const int s = sg + k * NSG;
+        const float w = s < S ? w_sh[s] : 0.f;
+        sum.x = fmaf(w, buf[k].x, sum.x); sum.y = fmaf(w, buf[k].y, sum.y); sum.z = fmaf(w, buf[k].z, sum.z); sum.w = fmaf(w, buf[k].w, sum.w);
     }
+    *reinterpret_cast<float4 *>(&red[sg][4 * qd]) = sum;
     __syncthreads();
-    for (int i = tid; i < G * HD; i += 256) {
-        const int g = i / HD, e = i - g * HD;
+    if (tid < HD) {
         float o = 0.f;
 #pragma unroll
-        for (int sg = 0; sg < NSG; ++sg) o += accw[sg][g][e];
-        const size_t oi = ((size_t)row * a.n_q + kvh * G + g) * HD + e;
+        for (int g = 0; g < NSG; ++g) o += red[g][tid];
+        const size_t oi = ((size_t)row * a.n_q + head) * HD + tid;
         a.out[oi] = o;
         if (a.out_planes) {
             const uint16_t p0 = f32_to_bf16(o);
@@ -524,7 +680,12 @@ __global__ void __launch_bounds__(256) k_attn_decode(AttnArgs a) {
             a.out_planes[2 * a.out_plane + oi] = f32_to_bf16(r1 - bf16_to_f32(p1));
         }
     }
-    if (tid == 0) a.counters[row * a.n_kv + kvh] = 0;
+}
+
+template <int HD>
+__global__ void __launch_bounds__(256) k_attn_combine(AttnArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    attn_combine_unit<HD>(a, smem, blockIdx.x, blockIdx.y);
 }
 
 }  // namespace rs

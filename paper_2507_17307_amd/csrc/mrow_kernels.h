@@ -13,9 +13,6 @@
 
 namespace rs {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
 // planes: p[0], p[1], p[2] each [rows, cols]; `plane` = elements per plane
 __device__ __forceinline__ void split_store(float v, uint16_t *p, size_t plane, size_t i) {
     const uint16_t a = f32_to_bf16(v);
@@ -76,8 +73,8 @@ __global__ void __launch_bounds__(256) k_rope_kv_rows(RopeArgs a) {
     }
     for (int p = tid; p < a.n_kv * hd; p += 256) {
         const int vh = p / hd, e = p - vh * hd;
-        const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * a.max_ctx + pos) * hd;
-        a.vcache[base + e] = f32_to_bf16(x[(a.n_q + a.n_kv) * hd + p]);
+        const size_t base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * (size_t)a.max_ctx * hd;
+        a.vcache[base + (size_t)e * a.max_ctx + pos] = f32_to_bf16(x[(a.n_q + a.n_kv) * hd + p]);   // V is stored [hd][position]
     }
 }
 

@@ -38,16 +38,15 @@ k_route_partials(const float *__restrict__ logits, int vocab, const float *__res
     }
 }
 
-// Final merge and routing decision: grid n_rows, block 256.
-// row_bad: optional per-row flag (nonzero = the row's inputs were out of range).
-__global__ void __launch_bounds__(256)
-k_route_merge(const SoftPartial *__restrict__ parts, int n_parts, int vocab, float tau, int active,
-              const int *__restrict__ row_bad, rs_route_out *__restrict__ out) {
-    const int row = blockIdx.x, tid = threadIdx.x;
+// Final merge and routing decision for one row by one 256-thread workgroup.
+// row_bad: optional per-row flag (nonzero = the row's inputs were out of range); sh: 4 SoftPartial of LDS.
+__device__ __forceinline__ void route_merge_row(const SoftPartial *__restrict__ parts, int n_parts, int vocab, float tau,
+                                                int active, const int *__restrict__ row_bad, rs_route_out *__restrict__ out,
+                                                int row, SoftPartial *sh) {
+    const int tid = threadIdx.x;
     SoftState st; st.init();
     for (int p = tid; p < n_parts; p += 256) st.merge(from_partial(parts[(size_t)row * n_parts + p]));
     wave_merge_state(st);
-    __shared__ SoftPartial sh[4];
     if ((tid & 63) == 0) sh[tid >> 6] = to_partial(st);
     __syncthreads();
     if (tid != 0) return;
@@ -73,6 +72,14 @@ k_route_merge(const SoftPartial *__restrict__ parts, int n_parts, int vocab, flo
     }
     r.flags = flags;
     out[row] = r;
+}
+
+// grid n_rows, block 256
+__global__ void __launch_bounds__(256)
+k_route_merge(const SoftPartial *__restrict__ parts, int n_parts, int vocab, float tau, int active,
+              const int *__restrict__ row_bad, rs_route_out *__restrict__ out) {
+    __shared__ SoftPartial sh[4];
+    route_merge_row(parts, n_parts, vocab, tau, active, row_bad, out, blockIdx.x, sh);
 }
 
 }  // namespace rs

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -16,6 +17,7 @@
 #include "router.h"
 #include "model_kernels.h"
 #include "mrow_kernels.h"
+#include "persistent.h"
 
 namespace {
 
@@ -54,7 +56,7 @@ const char *check_config(const rs_config *c) {
         return "d_model, d_ffn and n_q_heads*head_dim must be multiples of 128";
     if (c->d_ffn < 128) return "d_ffn too small";
     if (c->vocab < 2) return "vocab must be at least 2";
-    if (c->max_ctx < 1) return "max_ctx must be positive";
+    if (c->max_ctx < 8 || c->max_ctx % 8) return "max_ctx must be a positive multiple of 8";
     if (c->max_seqs < 1 || c->max_seqs > 8) return "max_seqs must be in 1..8";
     if (c->max_rows < 1 || c->max_rows > 64) return "max_rows must be in 1..64";
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return "rms_eps must be > 0 and rope_theta > 1";
@@ -65,9 +67,13 @@ const char *check_config(const rs_config *c) {
 
 struct Layout {
     size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, h, xn, qkv_raw, qbuf,
-        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, total;
+        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, total;
     int attn_rows_x_splits;   // capacity of attn_part in (row, split) pairs
     int lm_parts_cap;         // partial states per sequence
+};
+
+struct GemvPlan {
+    int qkv_rt, qkv_blocks, o_rt, o_blocks, gu_blocks, down_rt, down_blocks, lm_blocks;
 };
 
 int attn_pairs_cap(const rs_config &c) { return c.max_rows > 256 ? c.max_rows : 256; }
@@ -102,6 +108,8 @@ Layout make_layout(const rs_config &c) {
     L.lm_pl = take((size_t)3 * c.max_seqs * c.d_model * 2);
     L.lm_parts_cap = LM_PARTS_CAP;
     L.lm_parts = take((size_t)c.max_seqs * L.lm_parts_cap * sizeof(rs::SoftPartial));
+    L.sync = take(sizeof(rs::SyncState));
+    L.layer_ptrs = take((size_t)c.n_layers * sizeof(rs::LayerPtrs));
     L.total = o;
     return L;
 }
@@ -118,6 +126,24 @@ struct rs_model {
     unsigned char *ws;
     int timer_phase = -1, timer_layer = 0;
     hipEvent_t timer_start = nullptr, timer_stop = nullptr;
+    GemvPlan plan{};
+    // replayable launch sequences, one per distinct call signature (see forward())
+    struct GraphEntry {
+        int n_seqs, n_rows, active; float tau;
+        const void *slot, *tok, *off, *pos, *scale, *out, *logits; hipStream_t st;
+        hipGraph_t graph; hipGraphExec_t exec;
+    };
+    std::vector<GraphEntry> graphs;
+    std::vector<size_t> seen_once;                 // signatures launched eagerly once (ring buffer)
+    size_t seen_next = 0;
+    bool use_graphs = true;
+    // single-kernel decode step (experimental: slower than one kernel per phase on MI355X, where a
+    // grid-wide software barrier costs more than a kernel boundary)
+    bool use_persistent = false;
+    int persist_blocks = 0;
+    size_t persist_lds = 0;
+    unsigned long long arrivals_expected = 0;     // barrier arrivals of all launches so far
+    unsigned int spin_limit = 1u << 22;
 
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
 };
@@ -126,33 +152,62 @@ namespace {
 
 using namespace rs;
 
-int gemv_blocks(int n_units_per_wg_granularity, int n_cu, int per_cu) {
-    int cap = n_cu * per_cu;
-    return n_units_per_wg_granularity < cap ? (n_units_per_wg_granularity < 1 ? 1 : n_units_per_wg_granularity) : cap;
+int clamp_blocks(int want, int n_tiles_per_wg_unit) {
+    if (want > n_tiles_per_wg_unit) want = n_tiles_per_wg_unit;
+    return want < 1 ? 1 : want;
 }
 
-template <int MODE, int RT, int KS>
-rs_status launch_gemv(const rs_model *m, GemvArgs &a, int n_tiles, hipStream_t st, const char *name,
-                      int *blocks_out = nullptr) {
-    const int units = (KS == 1) ? (n_tiles + 3) / 4 : n_tiles;
-    const size_t lds = (size_t)(a.K < GEMV_KSEG ? a.K : GEMV_KSEG) * 4;
-    const int per_cu = lds > 40 * 1024 ? 2 : 4;
-    int blocks = gemv_blocks(units, m->n_cu, per_cu);
-    if (a.K > GEMV_KSEG) {                 // x is restaged per tile: one tile per workgroup
-        if (KS != 4) return fail(RS_EINVAL, "internal: segmented K needs the split-K launch");
-        blocks = units;
+// `blocks` workgroups share the phase; every workgroup takes a contiguous range of tiles
+template <int MODE, int RT, int KS, int UNR>
+rs_status launch_gemv(const rs_model *m, GemvArgs &a, int blocks, hipStream_t st, const char *name) {
+    const size_t lds = gemv_lds_bytes(a.K);
+    if (lds > 64 * 1024) {
+        static bool raised = false;                       // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_gemv<MODE, RT, KS, UNR, 0>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
+            raised = true;
+        }
     }
-    if (MODE == G_LMHEAD && blocks * 4 > LM_PARTS_CAP) blocks = LM_PARTS_CAP / 4;   // one partial per wave
-    if (blocks_out) *blocks_out = blocks;
-    hipLaunchKernelGGL((k_gemv<MODE, RT, KS>), dim3(blocks), dim3(256), lds, st, a);
+    if (a.K > GEMV_KSEG && KS != 4) return fail(RS_EINVAL, "internal: segmented K needs the split-K launch");
+    (void)m;
+    hipLaunchKernelGGL((k_gemv<MODE, RT, KS, UNR, 0>), dim3(blocks), dim3(256), lds, st, a);
     RS_LAUNCHED(name);
     return RS_OK;
 }
 
+// Launch shapes from sweeps on MI355X: about three workgroups per CU for matrices under ~128 MB,
+// two above; the down projection gets one tile per workgroup.
+GemvPlan make_plan(const rs_config &c, int n_cu) {
+    GemvPlan p{};
+    const int hd = c.head_dim, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * hd;
+    auto pick = [&](size_t bytes) { return bytes >= ((size_t)128 << 20) ? 2 * n_cu : 3 * n_cu; };
+    p.qkv_rt = 2;
+    const int qkv_tiles = (c.n_q_heads + c.n_kv_heads) * (hd / 2) + (c.n_kv_heads * hd) / 2;
+    p.qkv_blocks = clamp_blocks(pick((size_t)qkv_rows * c.d_model * 2), (qkv_tiles + 3) / 4);
+    p.o_rt = 2;
+    p.o_blocks = clamp_blocks(pick((size_t)c.d_model * c.n_q_heads * hd * 2), ((c.d_model + 1) / 2 + 3) / 4);
+    p.gu_blocks = clamp_blocks(pick((size_t)2 * c.d_ffn * c.d_model * 2), (c.d_ffn / 2 + 3) / 4);
+    // down: split-K workgroups, rows per workgroup chosen so that ~2 workgroups per CU have one tile each
+    const int want = (c.d_model + 2 * n_cu - 1) / (2 * n_cu);
+    const int opts[] = {2, 4, 5, 7, 8, 10};
+    p.down_rt = 10;
+    for (int o : opts) if (o >= want) { p.down_rt = o; break; }
+    if (c.d_model <= 2048) p.down_rt = 2;
+    p.down_blocks = clamp_blocks(3 * n_cu, (c.d_model + p.down_rt - 1) / p.down_rt);
+    p.lm_blocks = clamp_blocks(4 * n_cu, ((c.vocab + 7) / 8 + 3) / 4);
+    if (p.lm_blocks * 4 > LM_PARTS_CAP) p.lm_blocks = LM_PARTS_CAP / 4;
+    return p;
+}
+
 template <int HD>
 rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, hipStream_t st) {
-    hipLaunchKernelGGL((k_attn_decode<HD>), dim3(n_splits, n_kv, n_rows), dim3(256), 0, st, a);
-    RS_LAUNCHED("attn_decode");
+    a.n_slices = n_splits;
+    hipLaunchKernelGGL((k_attn_partial<HD>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(), st, a);
+    RS_LAUNCHED("attn_partial");
+    hipLaunchKernelGGL((k_attn_combine<HD>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
+    RS_LAUNCHED("attn_combine");
     return RS_OK;
 }
 
@@ -194,10 +249,83 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
     }
 }
 
-// One forward invocation over n_rows token rows of n_seqs sequences.
-rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, const int *d_tokens,
-                  const int *d_span_off, const int *d_pos0, const float *d_scale, float tau, int active,
-                  rs_route_out *d_out, float *d_logits, hipStream_t st) {
+const void *persistent_kernel(int hd) {
+    switch (hd) {
+        case 32: return (const void *)k_decode_persistent<32>;
+        case 64: return (const void *)k_decode_persistent<64>;
+        default: return (const void *)k_decode_persistent<128>;
+    }
+}
+
+size_t persistent_lds(const rs_config &c) {
+    size_t need = gemv_lds_bytes(c.d_model);
+    const size_t cand[] = {gemv_lds_bytes(c.n_q_heads * c.head_dim), gemv_lds_bytes(c.d_ffn),
+                           c.head_dim == 32 ? attn_lds_bytes<32>() : (c.head_dim == 64 ? attn_lds_bytes<64>() : attn_lds_bytes<128>()),
+                           attn_combine_lds_bytes<32>()};
+    for (size_t v : cand) if (v > need) need = v;
+    return need;
+}
+
+int attn_splits(const rs_config &c, const Layout &L, int n_rows) {
+    const int att_ts = 128;                                // tokens per context slice at full context
+    int n_splits = (c.max_ctx + att_ts - 1) / att_ts;
+    if (n_splits > ATT_SMAX) n_splits = ATT_SMAX;
+    if (n_splits * n_rows > L.attn_rows_x_splits) n_splits = L.attn_rows_x_splits / n_rows;
+    return n_splits < 1 ? 1 : n_splits;
+}
+
+// The whole single-row decode step as one cooperative kernel.
+rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_token, const int *d_pos, const float *d_scale,
+                             float tau, int active, rs_route_out *d_out, float *d_logits, hipStream_t st) {
+    const rs_config &c = m->cfg;
+    const Layout &L = m->lay;
+    const int hd = c.head_dim;
+    PersistArgs p{};
+    p.prep.n_seqs = 1; p.prep.n_rows = 1; p.prep.d_model = c.d_model; p.prep.vocab = c.vocab;
+    p.prep.max_ctx = c.max_ctx; p.prep.max_seqs = c.max_seqs;
+    p.prep.seq_slot = d_seq_slot; p.prep.tokens = d_token; p.prep.span_off = nullptr; p.prep.pos0 = d_pos; p.prep.scale = d_scale;
+    p.prep.embed = m->embed;
+    p.prep.row_slot = m->at<int>(L.row_slot); p.prep.row_pos = m->at<int>(L.row_pos); p.prep.row_bad = m->at<int>(L.row_bad);
+    p.prep.out_row = m->at<int>(L.out_row); p.prep.seq_bad = m->at<int>(L.seq_bad); p.prep.seq_scale = m->at<float>(L.seq_scale);
+    p.prep.h = m->at<float>(L.h);
+
+    GemvArgs &g = p.gemv;
+    g.eps = c.rms_eps; g.n_q = c.n_q_heads; g.n_kv = c.n_kv_heads; g.head_dim = hd; g.max_ctx = c.max_ctx;
+    g.max_seqs = c.max_seqs; g.d_ffn = c.d_ffn;
+    g.row_pos = p.prep.row_pos; g.row_slot = p.prep.row_slot; g.row_bad = p.prep.row_bad;
+    g.rope_cos = m->at<float>(L.rope_cos); g.rope_sin = m->at<float>(L.rope_sin);
+    g.qbuf = m->at<float>(L.qbuf); g.kcache = m->kv_k; g.vcache = m->kv_v;
+    g.act = m->at<float>(L.act); g.h_out = p.prep.h;
+    g.seq_scale = p.prep.seq_scale; g.parts = m->at<SoftPartial>(L.lm_parts); g.logits = d_logits;
+
+    AttnArgs &aa = p.attn;
+    aa.qbuf = g.qbuf; aa.kcache = m->kv_k; aa.vcache = m->kv_v;
+    aa.partials = m->at<float>(L.attn_part);
+    aa.out = m->at<float>(L.attn_out); aa.out_planes = nullptr; aa.out_plane = 0;
+    aa.row_pos = p.prep.row_pos; aa.row_slot = p.prep.row_slot; aa.row_bad = p.prep.row_bad;
+    aa.n_q = c.n_q_heads; aa.n_kv = c.n_kv_heads; aa.max_ctx = c.max_ctx; aa.max_seqs = c.max_seqs;
+
+    p.layers = m->at<LayerPtrs>(L.layer_ptrs); p.n_layers = c.n_layers;
+    p.qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * hd; p.qdim = c.n_q_heads * hd;
+    p.lm_head = m->lm_head; p.final_norm = m->final_norm;
+    p.qkv_rt = 2; p.o_rt = 2; p.down_rt = (m->plan.down_rt == 2 || m->plan.down_rt == 4) ? m->plan.down_rt : 8;
+    p.n_splits = attn_splits(c, L, 1); aa.n_slices = p.n_splits;
+    p.vocab = c.vocab; p.tau = tau; p.active = active;
+    p.seq_bad = p.prep.seq_bad; p.out = d_out;
+    p.sync = m->at<SyncState>(L.sync); p.bar_base = m->arrivals_expected; p.spin_limit = m->spin_limit;
+
+    void *args[] = {&p};
+    hipError_t e = hipLaunchCooperativeKernel(persistent_kernel(hd), dim3(m->persist_blocks), dim3(256), args,
+                                              (unsigned int)m->persist_lds, st);
+    if (e != hipSuccess) return fail(RS_EHIP, "cooperative launch of the decode step: %s", hipGetErrorString(e));
+    m->arrivals_expected += (unsigned long long)(6 * c.n_layers + 2) * (unsigned long long)m->persist_blocks;
+    return RS_OK;
+}
+
+// One forward invocation over n_rows token rows of n_seqs sequences, one kernel per phase.
+rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, const int *d_tokens,
+                          const int *d_span_off, const int *d_pos0, const float *d_scale, float tau, int active,
+                          rs_route_out *d_out, float *d_logits, hipStream_t st) {
     const rs_config &c = m->cfg;
     const Layout &L = m->lay;
     const int hd = c.head_dim, qdim = c.n_q_heads * hd, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * hd;
@@ -216,11 +344,7 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
     RS_LAUNCHED("prepare");
 
     // attention launch shape
-    const int att_ts = 16384 / c.head_dim;                 // tokens one attention workgroup takes per round trip
-    int n_splits = (c.max_ctx + att_ts - 1) / att_ts;
-    if (n_splits > ATT_SMAX) n_splits = ATT_SMAX;
-    if (n_splits * n_rows > L.attn_rows_x_splits) n_splits = L.attn_rows_x_splits / n_rows;
-    if (n_splits < 1) n_splits = 1;
+    const int n_splits = attn_splits(c, L, n_rows);
 
     const bool single = (n_rows == 1);
     rs_status rc;
@@ -234,7 +358,7 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
     for (int l = 0; l < c.n_layers; ++l) {
         AttnArgs aa{};
         aa.qbuf = m->at<float>(L.qbuf); aa.kcache = m->kv_k; aa.vcache = m->kv_v;
-        aa.partials = m->at<float>(L.attn_part); aa.counters = m->at<int>(L.attn_cnt);
+        aa.partials = m->at<float>(L.attn_part);
         aa.out = m->at<float>(L.attn_out);
         aa.out_planes = single ? nullptr : m->at<uint16_t>(L.attn_pl);
         aa.out_plane = (size_t)c.max_rows * qdim;
@@ -250,16 +374,11 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             g.qbuf = m->at<float>(L.qbuf); g.kcache = m->kv_k; g.vcache = m->kv_v;
             g.act = m->at<float>(L.act); g.h_out = h;
 
+            const GemvPlan &pl = m->plan;
             // QKV (+ RMSNorm, RoPE, KV write)
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_QKV, l);
-            if (qkv_rows <= 4096) {
-                const int tiles = (c.n_q_heads + c.n_kv_heads) * (hd / 2) + (c.n_kv_heads * hd) / 2;
-                rc = launch_gemv<G_QKV, 2, 1>(m, g, tiles, st, "gemv_qkv");
-            } else {
-                const int tiles = (c.n_q_heads + c.n_kv_heads) * (hd / 4) + (c.n_kv_heads * hd) / 4;
-                rc = launch_gemv<G_QKV, 4, 1>(m, g, tiles, st, "gemv_qkv");
-            }
+            rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, pl.qkv_blocks, st, "gemv_qkv");
             toc(RS_PHASE_QKV, l);
             if (rc) return rc;
             // attention
@@ -275,23 +394,27 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.attn_out);
             tic(RS_PHASE_OPROJ, l);
-            if (c.d_model <= 2048) rc = launch_gemv<G_OPROJ, 2, 1>(m, g, (c.d_model + 1) / 2, st, "gemv_oproj");
-            else rc = launch_gemv<G_OPROJ, 4, 1>(m, g, (c.d_model + 3) / 4, st, "gemv_oproj");
+            rc = launch_gemv<G_OPROJ, 2, 1, 2>(m, g, pl.o_blocks, st, "gemv_oproj");
             toc(RS_PHASE_OPROJ, l);
             if (rc) return rc;
             // gate/up (+ RMSNorm, SwiGLU)
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_GATEUP, l);
-            rc = launch_gemv<G_GATEUP, 4, 1>(m, g, c.d_ffn / 2, st, "gemv_gateup");
+            rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, pl.gu_blocks, st, "gemv_gateup");
             toc(RS_PHASE_GATEUP, l);
             if (rc) return rc;
             // down + residual
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
-            if (c.d_ffn > GEMV_KSEG) rc = launch_gemv<G_DOWN, 8, 4>(m, g, (c.d_model + 7) / 8, st, "gemv_down");
-            else if (c.d_model <= 2048) rc = launch_gemv<G_DOWN, 2, 4>(m, g, (c.d_model + 1) / 2, st, "gemv_down");
-            else rc = launch_gemv<G_DOWN, 4, 4>(m, g, (c.d_model + 3) / 4, st, "gemv_down");
+            switch (pl.down_rt) {
+                case 2: rc = launch_gemv<G_DOWN, 2, 4, 2>(m, g, pl.down_blocks, st, "gemv_down"); break;
+                case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, pl.down_blocks, st, "gemv_down"); break;
+                case 5: rc = launch_gemv<G_DOWN, 5, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
+                case 7: rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
+                case 8: rc = launch_gemv<G_DOWN, 8, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
+                default: rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
+            }
             toc(RS_PHASE_DOWN, l);
             if (rc) return rc;
         } else {
@@ -352,11 +475,10 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
         GemvArgs g{};
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
-        int blocks = 0;
         tic(RS_PHASE_LMHEAD, 0);
-        if ((rc = launch_gemv<G_LMHEAD, 8, 1>(m, g, (c.vocab + 7) / 8, st, "gemv_lmhead", &blocks))) return rc;
+        if ((rc = launch_gemv<G_LMHEAD, 8, 1, 2>(m, g, m->plan.lm_blocks, st, "gemv_lmhead"))) return rc;
         toc(RS_PHASE_LMHEAD, 0);
-        n_parts = blocks * 4;
+        n_parts = m->plan.lm_blocks * 4;
     } else {
         uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
         const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
@@ -375,6 +497,66 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
     hipLaunchKernelGGL(k_route_merge, dim3(n_seqs), dim3(256), 0, st, (const SoftPartial *)parts, n_parts, c.vocab, tau,
                        active, (const int *)m->at<int>(L.seq_bad), d_out);
     RS_LAUNCHED("route_merge");
+    return RS_OK;
+}
+
+// Dispatch of one forward invocation.  A step is ~170 small kernels, more than a host thread can
+// launch in the time the GPU needs to run them, so the launch sequence of every distinct call
+// signature (same pointers, counts, tau, model role and stream) is captured once into a HIP graph
+// and replayed afterwards; the kernels read tokens, positions and scales from the caller's buffers
+// at run time, so a caller that reuses its buffers replays the same graph for every step.
+// Falls back to plain launches when the stream cannot be captured (the legacy default stream, or
+// a capture already in progress), when the phase timer is armed, or with RSTITCH_GRAPHS=0.
+rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, const int *d_tokens,
+                  const int *d_span_off, const int *d_pos0, const float *d_scale, float tau, int active,
+                  rs_route_out *d_out, float *d_logits, hipStream_t st) {
+    if (n_rows == 1 && m->use_persistent && m->timer_phase < 0)
+        return forward_persistent(m, d_seq_slot, d_tokens, d_pos0, d_scale, tau, active, d_out, d_logits, st);
+    auto eager = [&]() {
+        return forward_kernels(m, n_seqs, n_rows, d_seq_slot, d_tokens, d_span_off, d_pos0, d_scale, tau, active, d_out,
+                               d_logits, st);
+    };
+    if (!m->use_graphs || m->timer_phase >= 0 || st == nullptr) return eager();
+    for (auto &g : m->graphs)
+        if (g.n_seqs == n_seqs && g.n_rows == n_rows && g.active == active && g.tau == tau && g.slot == d_seq_slot &&
+            g.tok == d_tokens && g.off == d_span_off && g.pos == d_pos0 && g.scale == d_scale && g.out == d_out &&
+            g.logits == d_logits && g.st == st) {
+            hipError_t e = hipGraphLaunch(g.exec, st);
+            if (e != hipSuccess) return fail(RS_EHIP, "graph launch: %s", hipGetErrorString(e));
+            return RS_OK;
+        }
+    // a signature is captured the second time it shows up: one-off calls stay plain launches
+    size_t sig = (size_t)n_seqs * 1000003u + (size_t)n_rows * 10007u + (size_t)active;
+    for (const void *p : {(const void *)d_seq_slot, (const void *)d_tokens, (const void *)d_span_off, (const void *)d_pos0,
+                          (const void *)d_scale, (const void *)d_out, (const void *)d_logits, (const void *)st})
+        sig = sig * 0x9E3779B97F4A7C15ull + (size_t)(uintptr_t)p;
+    { uint32_t tb; memcpy(&tb, &tau, 4); sig = sig * 0x9E3779B97F4A7C15ull + tb; }
+    bool seen = false;
+    for (size_t v : m->seen_once) if (v == sig) { seen = true; break; }
+    if (!seen) {
+        if (m->seen_once.size() < 64) m->seen_once.push_back(sig);
+        else { m->seen_once[m->seen_next] = sig; m->seen_next = (m->seen_next + 1) % 64; }
+        return eager();
+    }
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return eager(); }
+    if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) != hipSuccess) { (void)hipGetLastError(); return eager(); }
+    const rs_status rc = eager();
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(st, &graph);
+    if (rc != RS_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess || !graph) { (void)hipGetLastError(); return eager(); }
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) { (void)hipGraphDestroy(graph); (void)hipGetLastError(); return eager(); }
+    if (m->graphs.size() >= 256) {                      // callers that never reuse buffers: stop hoarding
+        for (auto &g : m->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
+        m->graphs.clear();
+    }
+    m->graphs.push_back(rs_model::GraphEntry{n_seqs, n_rows, active, tau, d_seq_slot, d_tokens, d_span_off, d_pos0, d_scale,
+                                             d_out, d_logits, st, graph, exec});
+    e = hipGraphLaunch(exec, st);
+    if (e != hipSuccess) return fail(RS_EHIP, "graph launch: %s", hipGetErrorString(e));
     return RS_OK;
 }
 
@@ -438,6 +620,7 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *w, void *kv_k,
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) { delete m; return fail(RS_EHIP, "device query: %s", hipGetErrorString(e)); }
     m->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    m->plan = make_plan(*cfg, m->n_cu);
 
     // rotary table: angle(pos, i) = pos * theta^(-2 i / head_dim), evaluated in double
     const int half = cfg->head_dim / 2;
@@ -453,6 +636,32 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *w, void *kv_k,
     e = hipMemcpy(m->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(m->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(m->ws + L.attn_cnt, 0, (size_t)cfg->max_rows * cfg->n_kv_heads * 4);
+    if (e == hipSuccess) e = hipMemset(m->ws + L.sync, 0, sizeof(SyncState));
+    if (e == hipSuccess) {
+        std::vector<LayerPtrs> lp(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers; ++l)
+            lp[l] = LayerPtrs{m->attn_norm[l], m->w_qkv[l], m->w_o[l], m->mlp_norm[l], m->w_gate_up[l], m->w_down[l]};
+        e = hipMemcpy(m->ws + L.layer_ptrs, lp.data(), lp.size() * sizeof(LayerPtrs), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) {
+        // single-kernel decode step: as many co-resident workgroups as the device holds, at most 1024
+        m->persist_lds = persistent_lds(*cfg);
+        int per_cu = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_kernel(cfg->head_dim), 256, m->persist_lds);
+        int coop = 0;
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev);
+        const char *genv = getenv("RSTITCH_GRAPHS");
+        m->use_graphs = !(genv && strcmp(genv, "0") == 0);
+        const char *env = getenv("RSTITCH_DECODE");
+        m->use_persistent = coop != 0 && per_cu > 0 && env && strcmp(env, "persistent") == 0;
+        if (m->use_persistent && m->persist_lds > 64 * 1024)
+            e = hipFuncSetAttribute(persistent_kernel(cfg->head_dim), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)m->persist_lds);
+        int blocks = per_cu * m->n_cu;
+        if (blocks > 1024) blocks = 1024;
+        if (blocks * 4 > LM_PARTS_CAP) blocks = LM_PARTS_CAP / 4;
+        m->persist_blocks = blocks;
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) { delete m; return fail(RS_EHIP, "workspace initialisation: %s", hipGetErrorString(e)); }
     *out = m;
@@ -460,6 +669,8 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *w, void *kv_k,
 }
 
 rs_status rs_destroy_model(rs_model *model) {
+    if (model)
+        for (auto &g : model->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     delete model;
     return RS_OK;
 }
@@ -489,6 +700,12 @@ rs_status rs_catchup_prefill(rs_model *m, int32_t n_seqs, int32_t n_rows, const 
     if (active != RS_SLM && active != RS_LLM) return fail(RS_EINVAL, "active must be RS_SLM or RS_LLM");
     return forward(m, n_seqs, n_rows, d_seq_slot, d_tokens, d_span_offset, d_pos0, d_logit_scale, tau, active, d_out,
                    d_logits, (hipStream_t)stream);
+}
+
+rs_status rs_set_spin_limit(rs_model *m, uint32_t polls) {
+    if (!m) return fail(RS_EINVAL, "null model");
+    m->spin_limit = polls ? polls : (1u << 22);
+    return RS_OK;
 }
 
 rs_status rs_set_phase_timer(rs_model *m, int32_t phase, int32_t layer, void *start_event, void *stop_event) {

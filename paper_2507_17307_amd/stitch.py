@@ -10,9 +10,11 @@ number of tokens each model has cached is all the state there is, so the
 "rollback" of a rejected step is simply not advancing it.
 
 Per invocation the host does one library call, one stream synchronisation and
-reads one 24-byte record.  Tokens and the record live in pinned host memory that
-the GPU addresses directly; positions, scales and span offsets are pointers
-into small device tables, so no per-step buffers are created or copied.
+reads one 24-byte record.  The span tokens, its first position, the logit scale
+and the record live at FIXED addresses in pinned host memory that the GPU reads
+and writes directly: nothing is allocated or copied per step, and because the
+call arguments repeat, the library replays a cached launch graph per (model,
+span length) instead of launching ~170 kernels one by one.
 """
 from __future__ import annotations
 
@@ -55,37 +57,45 @@ class StitchedPair:
         self.max_ctx = max_ctx
         dev = slm.device
         self.max_rows = min(m.cfg.max_rows for m in self.models if m is not None)
-        self.pos_table = torch.arange(max_ctx + 1, dtype=torch.int32, device=dev)
+        self.stream = torch.cuda.Stream(device=dev)          # a capturable (non-default) stream
         self.slot0 = torch.zeros(1, dtype=torch.int32, device=dev)
         self.off_table = torch.tensor([[0, n] for n in range(self.max_rows + 1)], dtype=torch.int32, device=dev)
-        self.scale = scale_table.to(device=dev, dtype=torch.float32).contiguous()
-        assert self.scale.numel() >= max_ctx + 1
-        self.seq = torch.zeros(max_ctx + 1, dtype=torch.int32).pin_memory()
-        self.seq_np = self.seq.numpy()
-        self.out = torch.zeros(6, dtype=torch.int32).pin_memory()
-        self.out_i = self.out.numpy()
-        self.out_f = self.out_i.view(np.float32)
-        self._p_pos, self._p_off = self.pos_table.data_ptr(), self.off_table.data_ptr()
-        self._p_seq, self._p_scale = self.seq.data_ptr(), self.scale.data_ptr()
-        self._p_out, self._p_slot = self.out.data_ptr(), self.slot0.data_ptr()
+        self.scale_np = scale_table.to(dtype=torch.float32).cpu().numpy()
+        assert self.scale_np.size >= max_ctx + 1
+        self.seq_np = np.zeros(max_ctx + 1, dtype=np.int32)  # prompt + accepted tokens (host)
+        # fixed-address staging in pinned memory: [0:max_rows] span tokens, then pos0, then scale (as bits), then the record
+        self.stage = torch.zeros(self.max_rows + 2 + 6, dtype=torch.int32).pin_memory()
+        self.stage_i = self.stage.numpy()
+        self.stage_f = self.stage_i.view(np.float32)
+        base = self.stage.data_ptr()
+        self._p_tok = base
+        self._p_pos = base + 4 * self.max_rows
+        self._p_scale = base + 4 * (self.max_rows + 1)
+        self._p_out = base + 4 * (self.max_rows + 2)
+        self._o = self.max_rows + 2                         # index of the record inside the staging array
+        self._p_off, self._p_slot = self.off_table.data_ptr(), self.slot0.data_ptr()
+        torch.cuda.synchronize()
         self.on_invocation: Optional[Callable[[int, int, int], None]] = None   # (model, pos0, n_rows) after sync
 
-    def _forward(self, model: int, pos0: int, end: int, tau: float, stream_handle: int) -> None:
-        """Feed sequence positions pos0 .. end-1 to `model`; the record of the last chunk lands in self.out."""
+    def _forward(self, model: int, pos0: int, end: int, tau: float) -> None:
+        """Feed sequence positions pos0 .. end-1 to `model`; the record of the last chunk lands in the staging array."""
         h = self.models[model].handle
         lib = B.lib
+        sh = self.stream.cuda_stream
         p = pos0
         while p < end:
             n = min(self.max_rows, end - p)
-            # only the chunk that reaches `end` predicts position `end`
-            scale_ptr = self._p_scale + 4 * end
+            if p > pos0:
+                self.stream.synchronize()                    # the previous chunk still reads the staging buffers
+            self.stage_i[:n] = self.seq_np[p:p + n]
+            self.stage_i[self.max_rows] = p
+            self.stage_f[self.max_rows + 1] = self.scale_np[end]      # only the chunk that reaches `end` predicts position `end`
             if n == 1:
-                rc = lib.rs_decode_step(h, 1, self._p_slot, self._p_seq + 4 * p, self._p_pos + 4 * p, scale_ptr,
-                                        tau, model, self._p_out, None, stream_handle)
+                rc = lib.rs_decode_step(h, 1, self._p_slot, self._p_tok, self._p_pos, self._p_scale,
+                                        tau, model, self._p_out, None, sh)
             else:
-                rc = lib.rs_catchup_prefill(h, 1, n, self._p_slot, self._p_seq + 4 * p, self._p_off + 8 * n,
-                                            self._p_pos + 4 * p, scale_ptr, tau, model, self._p_out, None,
-                                            stream_handle)
+                rc = lib.rs_catchup_prefill(h, 1, n, self._p_slot, self._p_tok, self._p_off + 8 * n,
+                                            self._p_pos, self._p_scale, tau, model, self._p_out, None, sh)
             if rc != 0:
                 raise B.RsError(rc, B.rs_last_error())
             p += n
@@ -94,8 +104,6 @@ class StitchedPair:
                  keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None) -> StitchRun:
         """Algorithm 1 until n_tokens tokens are accepted.  single_model = SLM or LLM runs that model
         alone (every token accepted) while still reporting its entropies."""
-        stream = torch.cuda.current_stream()
-        sh = stream.cuda_stream
         n0 = len(prompt)
         if n0 + n_tokens > self.max_ctx + 1:
             raise ValueError("prompt + tokens exceed max_ctx")
@@ -104,19 +112,20 @@ class StitchedPair:
         n_kv = [0, 0]
         active = SLM if single_model is None else single_model
         run = StitchRun()
-        sync = stream.synchronize
+        sync = self.stream.synchronize
+        o = self._o
         while len(run.output) < n_tokens:
             pos0 = n_kv[active]
-            self._forward(active, pos0, length, tau, sh)
+            self._forward(active, pos0, length, tau)
             sync()
             n_kv[active] = length
-            token, flags = int(self.out_i[0]), int(self.out_i[1]) & 0xFFFFFFFF
+            token, flags = int(self.stage_i[o]), int(self.stage_i[o + 1]) & 0xFFFFFFFF
             if self.on_invocation is not None:
                 self.on_invocation(active, pos0, length - pos0)
-            if flags & (B.FLAG_BADARG | B.FLAG_NONFINITE):
+            if flags & (B.FLAG_BADARG | B.FLAG_NONFINITE | B.FLAG_ABORTED):
                 raise RuntimeError(f"router flagged the step: flags={flags} model={active} pos0={pos0}")
             if keep_trace:
-                run.trace.append(Invocation(active, pos0, length - pos0, token, float(self.out_f[3]), flags))
+                run.trace.append(Invocation(active, pos0, length - pos0, token, float(self.stage_f[o + 3]), flags))
             if single_model is None:
                 if active == SLM and (flags & B.FLAG_HI):
                     active = LLM

@@ -16,6 +16,17 @@ from parity import check_invocation
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["kernel_per_phase", "single_kernel_step"], autouse=True)
+def decode_path(request, monkeypatch):
+    """Every test runs twice: single-row steps as one kernel per phase (the default) and as one
+    persistent kernel with grid-wide waits (RSTITCH_DECODE=persistent, read when a model is created)."""
+    if request.param == "single_kernel_step":
+        monkeypatch.setenv("RSTITCH_DECODE", "persistent")
+    else:
+        monkeypatch.delenv("RSTITCH_DECODE", raising=False)
+    return request.param
+
+
 def pair_run(wl, n_tokens=None):
     """Oracle run of a stitched workload; returns weights, trace, logits per invocation, tau, scales."""
     ws, wl_ = W.make_weights(wl.slm, wl.seed, 0), W.make_weights(wl.llm, wl.seed, 1)
@@ -171,3 +182,44 @@ def test_full_size_shapes_at_full_context(name, shape, n_layers, n_ctx, spans):
         torch.cuda.synchronize()
         check_invocation(got[0], lg[0], out, tau, router.LLM, where=f"{name} span {span} at {pos}")
         pos += span
+
+
+def test_bounded_wait_gives_up_instead_of_hanging(decode_path):
+    """A spin limit of one poll makes the first grid-wide wait of the single-kernel step give up:
+    the step must end, flag its record, and the model must refuse further steps; a fresh model works."""
+    import paper_2507_17307_amd as P
+    if decode_path != "single_kernel_step":
+        pytest.skip("only the single-kernel step has grid-wide waits")
+    w = W.make_weights(W.TINY_S, 5, 0).to("cuda")
+    m = P.Model(w, max_ctx=16)
+    good = m.decode_step([3], [0], 0.5, P.RS_SLM)[0]
+    assert not good.flags & P.FLAG_ABORTED
+    P.rs_set_spin_limit(m.handle, 1)
+    r = m.decode_step([4], [1], 0.5, P.RS_SLM)[0]
+    torch.cuda.synchronize()
+    assert r.flags & P.FLAG_ABORTED and r.token == -1
+    P.rs_set_spin_limit(m.handle, 0)
+    assert m.decode_step([4], [1], 0.5, P.RS_SLM)[0].flags & P.FLAG_ABORTED      # sticky
+    m2 = P.Model(w, max_ctx=16)
+    again = m2.decode_step([3], [0], 0.5, P.RS_SLM)[0]
+    assert again.token == good.token and abs(again.h_nats - good.h_nats) < 1e-6
+
+
+def test_live_stitched_run_through_the_host_driver_matches_the_oracle_run(decode_path):
+    """Algorithm 1 run LIVE on the GPU by the package's own host driver (fixed staging buffers, so the
+    library replays launch graphs from the second step on) against the oracle's run of config 1:
+    same accepted tokens, same model per invocation, same spans, entropies within tolerance."""
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedPair
+    wl = W.WORKLOADS["cfg1_tiny_pair"]
+    weights, _, res, ref_logits, tau, scales = pair_run(wl)
+    gpu = [P.Model(w.to("cuda"), max_ctx=wl.max_ctx + 1, max_rows=64) for w in weights]
+    pair = StitchedPair(gpu[0], gpu[1], wl.max_ctx, scales)
+    run = pair.generate(W.make_prompt(wl).tolist(), tau, wl.n_decode)
+    assert run.output == res.output
+    assert [(t.model, t.pos0, t.n_rows, t.accept) for t in run.trace] == \
+           [(t.model, t.pos0, len(t.span), t.accept) for t in res.trace]
+    assert max(abs(a.h_norm - b.h_norm) for a, b in zip(run.trace, res.trace)) <= 1e-3 / math.log(1024)
+    # and again on the same pair: the caches are overwritten with identical values, graphs are replayed
+    again = pair.generate(W.make_prompt(wl).tolist(), tau, wl.n_decode)
+    assert again.output == run.output and [t.flags for t in again.trace] == [t.flags for t in run.trace]
