@@ -81,15 +81,14 @@ __global__ void __launch_bounds__(256) k_rope_kv_rows(RopeArgs a) {
 // ------------------------------------------------------------------------------------------------
 // out[m, n] = sum_k X[m, k] W[n, k] for M <= 16*NB token rows.
 // A workgroup of NW waves owns 16 output columns at a time (for gate/up: 16 gate rows and the 16
-// matching up rows of W); its waves split K in interleaved 128-element blocks, each wave feeding
-// the matrix cores with W rows as the MFMA "A" operand (loaded straight from HBM, next block
-// prefetched while the current one is multiplied) and the three bf16 planes of X as the "B"
-// operand (read through L2); the per-wave 16x16 accumulators are summed through LDS by wave 0,
-// which also runs the epilogue.
-// Lane (i = lane % 16, g = lane / 16) supplies, for both operands, the 8 consecutive k at
-// kb + 32 g + 8 s (s = 0..3) of its row: any k order is valid for a dot product as long as both
-// operands agree, and this one lets a lane read 64 contiguous bytes.  The accumulator lane holds
-// D[4 g + r][token = lane % 16], r = 0..3.
+// matching up rows of W); its waves split K in interleaved blocks of 256 elements.  Per block a
+// wave streams its 16 x 512-byte piece of W from HBM with fully coalesced 16-byte loads (a load
+// instruction covers two whole 512-byte row pieces; the next block is in flight in registers
+// while the current one is multiplied), parks it in its private LDS region, and reads it back in
+// the operand layout of v_mfma_f32_16x16x32_bf16 (lane (i = lane % 16, g = lane / 16) supplies
+// the 8 consecutive k at 32 s + 8 g of row i).  The token side comes from the three bf16 planes
+// of X through L2 in the same k layout.  The per-wave 16x16 accumulators (lane holds
+// D[4 g + r][token = lane % 16]) are summed through LDS by wave 0, which runs the epilogue.
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
     const uint16_t *W; int N, K, M;       // M = valid token rows
@@ -100,15 +99,27 @@ struct GemmArgs {
     const float *seq_scale; SoftPartial *parts; float *logits; int n_parts;   // LM head
 };
 
+constexpr int GEMM_KB = 256;                      // k elements per block
+constexpr int GEMM_ROWB = GEMM_KB * 2 + 16;       // bytes per staged row (padded against LDS bank conflicts)
+
+template <int MODE, int NB, int NW>
+__host__ __device__ constexpr size_t gemm_lds_bytes() {
+    return (size_t)NW * ((MODE == G_GATEUP) ? 2 : 1) * (16 * GEMM_ROWB + NB * 1024);
+}
+
 template <int MODE, int NB, int NW>
 __global__ void __launch_bounds__(NW * 64) k_gemm_rows(GemmArgs a) {
     constexpr int NT = (MODE == G_GATEUP) ? 2 : 1;
-    __shared__ float4 red[NW > 1 ? NW : 1][NT][NB][64];
+    extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
+    unsigned char *wlds = smem + (size_t)wave * NT * 16 * GEMM_ROWB;                       // this wave's staging area
+    float4 *red = reinterpret_cast<float4 *>(smem + (size_t)NW * NT * 16 * GEMM_ROWB);     // [NW][NT][NB][64]
     const int K = a.K;
     const int n_out = (MODE == G_GATEUP) ? a.d_ffn : a.N;                 // distinct output columns
     const int n_tiles = (n_out + 15) / 16;
+    // global-load role of this lane: load q (0..7) fetches rows 2q and 2q+1, lane covers 16 bytes of one of them
+    const int lrow = lane >> 5, lchunk = lane & 31;
 
     const uint16_t *xp[NB];
     bool xok[NB];
@@ -116,64 +127,67 @@ __global__ void __launch_bounds__(NW * 64) k_gemm_rows(GemmArgs a) {
     for (int nb = 0; nb < NB; ++nb) {
         const int m = nb * 16 + i16;
         xok[nb] = m < a.M;
-        xp[nb] = a.X + (size_t)(xok[nb] ? m : 0) * K + g * 32;
+        xp[nb] = a.X + (size_t)(xok[nb] ? m : 0) * K + g * 8;
     }
     SoftState st; st.init();
     const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
 
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int n0 = t * 16;
-        const int wrow = min(n0 + i16, n_out - 1);
-        const uint16_t *w[NT];
-        w[0] = a.W + (size_t)wrow * K + g * 32;
-        if (NT == 2) w[NT - 1] = a.W + (size_t)(a.d_ffn + wrow) * K + g * 32;
         f32x4_t acc[NT][NB];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) acc[nt][nb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-        uint4 av[NT][4];
-        int kb = wave * 128;
-        if (kb < K) {
+        // row pointers of the 8 loads per tile
+        const uint16_t *wrow[NT][8];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int r = min(n0 + 2 * q + lrow, n_out - 1) + (nt == 1 ? a.d_ffn : 0);
+                wrow[nt][q] = a.W + (size_t)r * K + lchunk * 8;
+            }
+        uint4 cur[NT][8];
+        int kb = wave * GEMM_KB;
+        auto fetch = [&](int k0, uint4 (&dst)[NT][8]) {
+            const bool ok = k0 + lchunk * 8 < K;            // K is a multiple of 128, a block may be half empty
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int s = 0; s < 4; ++s) av[nt][s] = load_stream(reinterpret_cast<const uint4 *>(w[nt] + kb + 8 * s));
-        }
-        for (; kb < K; kb += NW * 128) {
-            uint4 an[NT][4];
-            const int kn = kb + NW * 128;
-            if (kn < K) {
+                for (int q = 0; q < 8; ++q)
+                    dst[nt][q] = ok ? load_stream(reinterpret_cast<const uint4 *>(wrow[nt][q] + k0)) : make_uint4(0, 0, 0, 0);
+        };
+        if (kb < K) fetch(kb, cur);
+        for (; kb < K; kb += NW * GEMM_KB) {
+            // park the block in LDS
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    *reinterpret_cast<uint4 *>(wlds + (size_t)(nt * 16 + 2 * q + lrow) * GEMM_ROWB + lchunk * 16) = cur[nt][q];
+            const int kn = kb + NW * GEMM_KB;
+            if (kn < K) fetch(kn, cur);
+#pragma unroll
+            for (int s = 0; s < GEMM_KB / 32; ++s) {
+                if (kb + 32 * s >= K) break;
+                bf16x8_t A[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
+                    A[nt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(wlds + (size_t)(nt * 16 + i16) * GEMM_ROWB + (4 * s + g) * 16));
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) an[nt][s] = load_stream(reinterpret_cast<const uint4 *>(w[nt] + kn + 8 * s));
-            }
+                for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-                for (int pl = 2; pl >= 0; --pl) {             // smallest plane first
-                    uint4 bv[4];
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        bv[s] = xok[nb] ? *reinterpret_cast<const uint4 *>(xp[nb] + pl * a.x_plane + kb + 8 * s)
-                                        : make_uint4(0, 0, 0, 0);
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        const bf16x8_t B = __builtin_bit_cast(bf16x8_t, bv[s]);
+                    for (int pl = 2; pl >= 0; --pl) {             // smallest plane first
+                        const uint4 bv = xok[nb] ? *reinterpret_cast<const uint4 *>(xp[nb] + pl * a.x_plane + kb + 32 * s)
+                                                 : make_uint4(0, 0, 0, 0);
+                        const bf16x8_t B = __builtin_bit_cast(bf16x8_t, bv);
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt)
-                            acc[nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[nt][s]), B,
-                                                                                   acc[nt][nb], 0, 0, 0);
+                            acc[nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[nt], B, acc[nt][nb], 0, 0, 0);
                     }
                 }
-            }
-            if (kn < K) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) av[nt][s] = an[nt][s];
             }
         }
         // ---- sum the waves' accumulators (wave 0 ends up with the totals)
@@ -182,16 +196,16 @@ __global__ void __launch_bounds__(NW * 64) k_gemm_rows(GemmArgs a) {
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    red[wave][nt][nb][lane] = make_float4(acc[nt][nb][0], acc[nt][nb][1], acc[nt][nb][2], acc[nt][nb][3]);
+                    red[((wave * NT + nt) * NB + nb) * 64 + lane] = make_float4(acc[nt][nb][0], acc[nt][nb][1], acc[nt][nb][2], acc[nt][nb][3]);
             __syncthreads();
             if (wave == 0) {
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        float4 sum = red[0][nt][nb][lane];
+                        float4 sum = red[((0 * NT + nt) * NB + nb) * 64 + lane];
                         for (int wv = 1; wv < NW; ++wv) {
-                            const float4 v = red[wv][nt][nb][lane];
+                            const float4 v = red[((wv * NT + nt) * NB + nb) * 64 + lane];
                             sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
                         }
                         acc[nt][nb] = (f32x4_t){sum.x, sum.y, sum.z, sum.w};

@@ -211,16 +211,30 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, hipStream
     return RS_OK;
 }
 
+template <int MODE, int NB, int NW>
+rs_status launch_gemm_nw(GemmArgs &a, int blocks, hipStream_t st, const char *name) {
+    constexpr size_t lds = gemm_lds_bytes<MODE, NB, NW>();
+    if (lds > 64 * 1024) {
+        static bool raised = false;                       // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_gemm_rows<MODE, NB, NW>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((k_gemm_rows<MODE, NB, NW>), dim3(blocks), dim3(NW * 64), lds, st, a);
+    RS_LAUNCHED(name);
+    return RS_OK;
+}
+
 template <int MODE, int NB>
 rs_status launch_gemm_nb(GemmArgs &a, int blocks, int nw, hipStream_t st, const char *name) {
     switch (nw) {
-        case 1: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 1>), dim3(blocks), dim3(64), 0, st, a); break;
-        case 4: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 4>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 8: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 8>), dim3(blocks), dim3(512), 0, st, a); break;
-        default: hipLaunchKernelGGL((k_gemm_rows<MODE, NB, 16>), dim3(blocks), dim3(1024), 0, st, a); break;
+        case 1: return launch_gemm_nw<MODE, NB, 1>(a, blocks, st, name);
+        case 4: return launch_gemm_nw<MODE, NB, 4>(a, blocks, st, name);
+        default: return launch_gemm_nw<MODE, NB, 8>(a, blocks, st, name);
     }
-    RS_LAUNCHED(name);
-    return RS_OK;
 }
 
 // n_tiles = number of 16-column output tiles
@@ -228,12 +242,12 @@ template <int MODE>
 rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     const int nb = (a.M + 15) / 16;
     const int nt = (MODE == G_GATEUP) ? 2 : 1;
-    const int kblocks = a.K / 128;
-    // waves per workgroup: enough to put ~2000 waves on the chip, bounded by K and by the LDS
-    // used for the cross-wave sum (1 KB per wave, tile and token block)
-    int nw = n_tiles >= 512 ? 4 : (n_tiles >= 256 ? 8 : 16);
-    while (nw > 1 && (nw > kblocks || nw * nt * nb > 32)) nw >>= 1;
+    const int kblocks = (a.K + GEMM_KB - 1) / GEMM_KB;
+    // waves per workgroup (they split K): more of them where a matrix has few 16-row tiles
+    int nw = n_tiles >= 512 ? 4 : 8;
+    while (nw > 1 && nw > kblocks) nw >>= 1;
     if (nw == 2) nw = 1;
+    (void)nt;
     int blocks = n_tiles < 2048 ? n_tiles : 2048;
     if (MODE == G_LMHEAD) {
         if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;                 // one partial per workgroup
