@@ -73,10 +73,18 @@ def test_shape_arithmetic_against_the_papers_memory_table():
     # Table "Memory usage ... under BF16": per-token KV cache 0.028 / 0.055 / 0.189 / 0.253 MB and
     # weights 3036 / 15640 / 29275 / 63890 MB for the 1.5B / 7B / 14B / 32B models.  The table is
     # measured inside a serving framework, so agreement is to a few per cent, in MiB.
+    import os
     mib = 2.0 ** 20
-    for s, kv_mb, w_mb in [(W.S15, 0.028, 3036), (W.M7, 0.055, 15640), (W.M14, 0.189, 29275), (W.M32, 0.253, 63890)]:
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "memory_table.txt"))
+            if l.strip() and not l.startswith("#")]
+    table = {r[0]: [float(v) for v in r[1:]] for r in rows}
+    for s, key in [(W.S15, "1.5B"), (W.M7, "7B"), (W.M14, "14B"), (W.M32, "32B")]:
+        kv_mb, w_mb, at8k, at16k = table[key]
         assert shapes.kv_bytes_per_token(s) / mib == pytest.approx(kv_mb, rel=0.04)
         assert shapes.weight_bytes_resident(s) / mib == pytest.approx(w_mb, rel=0.08)
+        # the table's own totals are weights + context * KV per token
+        assert at16k - at8k == pytest.approx(8192 * kv_mb, rel=0.02)
+        assert (shapes.weight_bytes_resident(s) + 16384 * shapes.kv_bytes_per_token(s)) / mib == pytest.approx(at16k, rel=0.08)
     assert [shapes.kv_bytes_per_token(s) for s in (W.S15, W.M7, W.M14, W.M32)] == [28672, 57344, 196608, 262144]
     # bytes one decode step must read
     assert shapes.weight_bytes_read_per_step(W.S15) == pytest.approx(3087.7e6, rel=1e-4)
