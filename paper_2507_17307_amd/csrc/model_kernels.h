@@ -77,77 +77,57 @@ __global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// GEMV phases, one token row.  y[n] = sum_k W[n,k] x[k]: W is bf16, row-major, streamed once from
-// HBM with 16-byte non-temporal loads; x is fp32 and staged in LDS; accumulation is fp32.
-// A wave owns RT rows at a time and its lanes stride over K (KS = 1); with KS = 4 the four waves
-// of a workgroup split K of the same rows (short, wide matrices).  When K exceeds the LDS segment
-// the workgroup walks K in segments, restaging x (KS = 4 only, one tile per workgroup).
+// GEMV phases for 1..8 token rows.  y[m][n] = sum_k W[n,k] x[m][k]: W is bf16, row-major, streamed
+// once from HBM with 16-byte non-temporal loads whatever the number of rows; x is fp32 and staged in
+// LDS; accumulation is fp32.  A wave owns RT rows of W at a time and its lanes stride over K
+// (KS = 1); with KS = 4 the four waves of a workgroup split K of the same rows (short, wide
+// matrices).  MP is the number of token rows the kernel is compiled for (1, 2, 4, 8); a call with
+// fewer rows leaves the spare ones zero.  When MP * K floats exceed the LDS segment the workgroup
+// walks K in segments, restaging x (KS = 4 only).
 // Prologue and epilogue depend on the phase:
 //   G_QKV     x = RMSNorm(h);  rows come in rotary pairs (i, i + hd/2); epilogue rotates q and k,
-//             writes q (fp32) and the bf16 K/V rows of this position into the cache
+//             writes q (fp32) and the bf16 K/V rows of each token's position into the cache
 //   G_OPROJ   x = attention output;  h += y
 //   G_GATEUP  x = RMSNorm(h);  rows come in (gate i, up i) pairs; act[i] = silu(gate) * up
 //   G_DOWN    x = act;  h += y
-//   G_LMHEAD  x = RMSNorm(h);  logit = y * scale feeds the single-pass softmax state of the wave
+//   G_LMHEAD  x = RMSNorm(h[gather]);  logit = y * scale feeds the single-pass softmax state of
+//             the wave (one state per token row)
 // ------------------------------------------------------------------------------------------------
 enum { G_QKV = 0, G_OPROJ = 1, G_GATEUP = 2, G_DOWN = 3, G_LMHEAD = 4 };
 
-constexpr int GEMV_KSEG = 32768;     // fp32 elements of x held in LDS at a time (128 KB of the CU's 160 KB)
+constexpr int GEMV_LDS_FLOATS = 38912;   // fp32 elements of x held in LDS at a time (152 KB of the CU's 160 KB)
 
 struct GemvArgs {
     const uint16_t *W; int N, K;
-    const float *h_in; const uint16_t *gain; float eps;   // RMSNorm input (norm phases)
-    const float *x_in;                                    // ready fp32 vector (other phases)
-    float *h_out;                                         // residual stream (O-proj, down)
-    float *act;                                           // SwiGLU output (gate/up)
-    float *qbuf; uint16_t *kcache, *vcache;               // QKV outputs
+    int m_rows;                                           // token rows in this call (<= MP)
+    const float *h_in; int ld_h; const uint16_t *gain; float eps;   // RMSNorm input rows (norm phases), row stride ld_h
+    const int *gather;                                    // LM head: h row of output row m, or null (= m)
+    const float *x_in;                                    // ready fp32 rows [m][K] (other phases)
+    float *h_out;                                         // residual stream rows, stride ld_h (O-proj, down)
+    float *act;                                           // SwiGLU output rows [m][d_ffn] (gate/up)
+    float *qbuf; uint16_t *kcache, *vcache;               // QKV outputs (q rows [m][n_q*hd])
     const float *rope_cos, *rope_sin;                     // [max_ctx, head_dim/2]
     int n_q, n_kv, head_dim, max_ctx, max_seqs, layer, d_ffn;
     const int *row_pos, *row_slot, *row_bad;
-    const float *seq_scale; SoftPartial *parts; float *logits;   // LM head
+    const float *seq_scale; SoftPartial *parts; int n_parts; float *logits;   // LM head
 };
 
-// 8 bf16 weights times 8 fp32 activations
-__device__ __forceinline__ float dot8f(const uint4 &w, const float4 &xa, const float4 &xb, float acc) {
-    acc = fmaf(bf16_lo(w.x), xa.x, acc); acc = fmaf(bf16_hi(w.x), xa.y, acc);
-    acc = fmaf(bf16_lo(w.y), xa.z, acc); acc = fmaf(bf16_hi(w.y), xa.w, acc);
-    acc = fmaf(bf16_lo(w.z), xb.x, acc); acc = fmaf(bf16_hi(w.z), xb.y, acc);
-    acc = fmaf(bf16_lo(w.w), xb.z, acc); acc = fmaf(bf16_hi(w.w), xb.w, acc);
-    return acc;
-}
+// elements of K one LDS segment holds for MP rows
+template <int MP>
+__host__ __device__ constexpr int gemv_seg(int K) { return K * MP <= GEMV_LDS_FLOATS ? K : (GEMV_LDS_FLOATS / MP) / 2048 * 2048; }
+template <int MP>
+__host__ __device__ constexpr size_t gemv_lds_bytes(int K) { return (size_t)gemv_seg<MP>(K) * MP * 4 + 4096; }
 
-// accumulate chunks [c_begin, c_end) of the rows; xs holds the segment starting at chunk seg_c0 as
-// two float4 planes (first and second half of every 8-element chunk) of plane_len chunks each
-template <int RT, int UNR>
-__device__ __forceinline__ void gemv_accumulate(const uint4 *const (&wp)[RT], const float4 *__restrict__ xs, int plane_len,
-                                                int seg_c0, int c_begin, int c_end, int cstride, float (&acc)[RT]) {
-#pragma unroll UNR
-    for (int c = c_begin; c < c_end; c += cstride) {
-        uint4 wv[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
-        const float4 xa = xs[c - seg_c0], xb = xs[plane_len + c - seg_c0];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) acc[r] = dot8f(wv[r], xa, xb, acc[r]);
-    }
-}
-
-// LDS needed by gemv_phase for a matrix with K columns
-__host__ __device__ constexpr size_t gemv_lds_bytes(int K) { return (size_t)(K < GEMV_KSEG ? K : GEMV_KSEG) * 4 + 512; }
-
-// wg / nwg: index of this workgroup among the workgroups that share the phase.
-// PF > 0: the first PF 16-byte loads per row of the wave's first tile are issued before the
-// prologue (they do not depend on x), so the weight stream starts at kernel entry.
-template <int MODE, int RT, int KS, int UNR = 2, int PF = 0>
+template <int MODE, int RT, int KS, int UNR, int MP>
 __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *smem, int wg, int nwg) {
     float4 *xs = reinterpret_cast<float4 *>(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int K = a.K;
-    const int seg = K < GEMV_KSEG ? K : GEMV_KSEG;       // elements per LDS segment
-    float *red = reinterpret_cast<float *>(smem + (size_t)seg * 4);    // [2][4][RT]
-    float *red_ss = red + 2 * 4 * RT;                                    // [4]
-    const int plane_len = seg >> 3;
-    const bool resident = K <= GEMV_KSEG;
+    const int K = a.K, M = a.m_rows;
+    const int seg = gemv_seg<MP>(K);                      // elements of K per LDS segment
+    const int plane_len = seg >> 3;                       // float4 per plane; row m uses planes 2m and 2m+1
+    float *red = reinterpret_cast<float *>(smem + (size_t)seg * MP * 4);   // [2][4][RT*MP]
+    float *red_ss = red + 2 * 4 * RT * MP;                                  // [4][MP]
+    const bool resident = seg == K;
     constexpr bool NORM = (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD);
 
     // ---- tiles
@@ -191,204 +171,251 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
     };
 
     // row position / slot (QKV only), read once up front so that no epilogue waits on it
-    int row_bad = 0, row_pos = 0, row_slot = 0;
-    if (MODE == G_QKV) { row_bad = a.row_bad[0]; row_pos = a.row_pos[0]; row_slot = a.row_slot[0]; }
-
-    // ---- early weight loads of the first tile
-    constexpr int NPF = PF > 0 ? PF : 1;
-    uint4 pre[RT][NPF];
-    if (PF > 0 && unit0 < t_hi) {
-        int rows[RT]; int hd_, p0_; bool rot_;
-        tile_rows(unit0, rows, hd_, p0_, rot_);
+    int row_bad[MP], row_pos[MP], row_slot[MP];
 #pragma unroll
-        for (int j = 0; j < NPF; ++j) {
-            const int c = c0 + j * cstride;
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                pre[r][j] = make_uint4(0, 0, 0, 0);
-                if (c < (K >> 3)) pre[r][j] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K) + c);
-            }
-        }
+    for (int m = 0; m < MP; ++m) {
+        row_bad[m] = 1; row_pos[m] = 0; row_slot[m] = 0;
+        if (MODE == G_QKV && m < M) { row_bad[m] = a.row_bad[m]; row_pos[m] = a.row_pos[m]; row_slot[m] = a.row_slot[m]; }
     }
 
-    // ---- prologue: x (fp32) into LDS
-    float inv = 1.f;
-    constexpr int HCACHE = 6;                 // float4 per thread kept between the two passes over h (K <= 6144)
-    float4 hreg[HCACHE];
-    uint2 greg[HCACHE];
+    // ---- prologue: x (fp32) into LDS.  Norm phases: K = d_model fits one segment for every MP.
+    float inv[MP];
+    constexpr int HCACHE = (MP == 1) ? 6 : 0;            // float4 per thread kept between the two passes over h
+    float4 hreg[HCACHE > 0 ? HCACHE : 1];
+    uint2 greg[HCACHE > 0 ? HCACHE : 1];
     if (NORM) {
-        const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in);
         const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain);
-        float ss = 0.f;
 #pragma unroll
-        for (int j = 0; j < HCACHE; ++j) {
-            const int i = tid + j * 256;
-            hreg[j] = make_float4(0.f, 0.f, 0.f, 0.f); greg[j] = make_uint2(0, 0);
-            if (i < (K >> 2)) { hreg[j] = h4[i]; greg[j] = g2[i]; }
-        }
+        for (int m = 0; m < MP; ++m) {
+            float ss = 0.f;
+            if (m < M) {
+                const int src = (MODE == G_LMHEAD && a.gather) ? a.gather[m] : m;
+                const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in + (size_t)src * a.ld_h);
+                if (HCACHE > 0) {
 #pragma unroll
-        for (int j = 0; j < HCACHE; ++j) {
-            ss = fmaf(hreg[j].x, hreg[j].x, ss); ss = fmaf(hreg[j].y, hreg[j].y, ss);
-            ss = fmaf(hreg[j].z, hreg[j].z, ss); ss = fmaf(hreg[j].w, hreg[j].w, ss);
-        }
-        for (int i = tid + HCACHE * 256; i < (K >> 2); i += 256) {
-            const float4 v = h4[i];
-            ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
-        }
-        ss = wave_sum(ss);
-        if (lane == 0) red_ss[wave] = ss;
-        __syncthreads();
-        inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)K + a.eps);
-    }
-    // stage the K-range [k0, k0+len) of x: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
-    auto stage = [&](int k0, int len) {
-        if (NORM) {                       // k0 == 0 and len == K in the norm phases (K fits one segment)
-            const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in + k0);
-            const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain + k0);
+                    for (int j = 0; j < HCACHE; ++j) {
+                        const int i = tid + j * 256;
+                        hreg[j] = make_float4(0.f, 0.f, 0.f, 0.f); greg[j] = make_uint2(0, 0);
+                        if (i < (K >> 2)) { hreg[j] = h4[i]; greg[j] = g2[i]; }
+                    }
 #pragma unroll
-            for (int j = 0; j < HCACHE; ++j) {
-                const int i = tid + j * 256;
-                if (i < (len >> 2)) {
-                    float4 v = hreg[j]; const uint2 g = greg[j];
-                    v.x *= inv * bf16_lo(g.x); v.y *= inv * bf16_hi(g.x); v.z *= inv * bf16_lo(g.y); v.w *= inv * bf16_hi(g.y);
-                    xs[(i & 1) * plane_len + (i >> 1)] = v;
+                    for (int j = 0; j < HCACHE; ++j) {
+                        ss = fmaf(hreg[j].x, hreg[j].x, ss); ss = fmaf(hreg[j].y, hreg[j].y, ss);
+                        ss = fmaf(hreg[j].z, hreg[j].z, ss); ss = fmaf(hreg[j].w, hreg[j].w, ss);
+                    }
+                }
+                for (int i = tid + HCACHE * 256; i < (K >> 2); i += 256) {
+                    const float4 v = h4[i];
+                    ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
                 }
             }
-            for (int i = tid + HCACHE * 256; i < (len >> 2); i += 256) {
-                float4 v = h4[i]; const uint2 g = g2[i];
-                v.x *= inv * bf16_lo(g.x); v.y *= inv * bf16_hi(g.x); v.z *= inv * bf16_lo(g.y); v.w *= inv * bf16_hi(g.y);
-                xs[(i & 1) * plane_len + (i >> 1)] = v;
+            ss = wave_sum(ss);
+            if (lane == 0) red_ss[wave * MP + m] = ss;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < MP; ++m)
+            inv[m] = 1.0f / sqrtf((red_ss[0 * MP + m] + red_ss[1 * MP + m] + red_ss[2 * MP + m] + red_ss[3 * MP + m]) / (float)K + a.eps);
+    }
+    // stage the K-range [k0, k0+len) of every row: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
+    auto stage = [&](int k0, int len) {
+#pragma unroll
+        for (int m = 0; m < MP; ++m) {
+            float4 *xm = xs + (size_t)2 * m * plane_len;
+            if (m >= M) {
+                for (int i = tid; i < (len >> 2); i += 256) xm[(i & 1) * plane_len + (i >> 1)] = make_float4(0.f, 0.f, 0.f, 0.f);
+            } else if (NORM) {
+                const int src = (MODE == G_LMHEAD && a.gather) ? a.gather[m] : m;
+                const float4 *h4 = reinterpret_cast<const float4 *>(a.h_in + (size_t)src * a.ld_h + k0);
+                const uint2 *g2 = reinterpret_cast<const uint2 *>(a.gain + k0);
+                const float iv = inv[m];
+                if (HCACHE > 0) {
+#pragma unroll
+                    for (int j = 0; j < HCACHE; ++j) {
+                        const int i = tid + j * 256;
+                        if (i < (len >> 2)) {
+                            float4 v = hreg[j]; const uint2 g = greg[j];
+                            v.x *= iv * bf16_lo(g.x); v.y *= iv * bf16_hi(g.x); v.z *= iv * bf16_lo(g.y); v.w *= iv * bf16_hi(g.y);
+                            xm[(i & 1) * plane_len + (i >> 1)] = v;
+                        }
+                    }
+                }
+                for (int i = tid + HCACHE * 256; i < (len >> 2); i += 256) {
+                    float4 v = h4[i]; const uint2 g = g2[i];
+                    v.x *= iv * bf16_lo(g.x); v.y *= iv * bf16_hi(g.x); v.z *= iv * bf16_lo(g.y); v.w *= iv * bf16_hi(g.y);
+                    xm[(i & 1) * plane_len + (i >> 1)] = v;
+                }
+            } else {
+                const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in + (size_t)m * K + k0);
+                for (int i = tid; i < (len >> 2); i += 256) xm[(i & 1) * plane_len + (i >> 1)] = x4[i];
             }
-        } else {
-            const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in + k0);
-            for (int i = tid; i < (len >> 2); i += 256) xs[(i & 1) * plane_len + (i >> 1)] = x4[i];
         }
     };
     if (resident) { stage(0, K); __syncthreads(); }
 
-    SoftState st; st.init();
-    const float lm_scale = (MODE == G_LMHEAD) ? a.seq_scale[0] : 1.f;
+    SoftState st[MP];
+    float lm_scale[MP];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) { st[m].init(); lm_scale[m] = (MODE == G_LMHEAD && m < M) ? a.seq_scale[m] : 1.f; }
     int parity = 0;
+
+    // accumulate chunks [c_begin, c_end) of the tile; the LDS segment starts at chunk seg_c0
+    auto accumulate = [&](const uint4 *const (&wp)[RT], int seg_c0, int c_begin, int c_end, float (&acc)[RT][MP]) {
+#pragma unroll UNR
+        for (int c = c_begin; c < c_end; c += cstride) {
+            uint4 wv[RT];
+#pragma unroll
+            for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
+            float4 xa[MP], xb[MP];
+#pragma unroll
+            for (int m = 0; m < MP; ++m) { xa[m] = xs[(2 * m) * plane_len + c - seg_c0]; xb[m] = xs[(2 * m + 1) * plane_len + c - seg_c0]; }
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const float w0 = bf16_lo(wv[r].x), w1 = bf16_hi(wv[r].x), w2 = bf16_lo(wv[r].y), w3 = bf16_hi(wv[r].y);
+                const float w4 = bf16_lo(wv[r].z), w5 = bf16_hi(wv[r].z), w6 = bf16_lo(wv[r].w), w7 = bf16_hi(wv[r].w);
+#pragma unroll
+                for (int m = 0; m < MP; ++m) {
+                    float v = acc[r][m];
+                    v = fmaf(w0, xa[m].x, v); v = fmaf(w1, xa[m].y, v); v = fmaf(w2, xa[m].z, v); v = fmaf(w3, xa[m].w, v);
+                    v = fmaf(w4, xb[m].x, v); v = fmaf(w5, xb[m].y, v); v = fmaf(w6, xb[m].z, v); v = fmaf(w7, xb[m].w, v);
+                    acc[r][m] = v;
+                }
+            }
+        }
+    };
 
     for (int t = unit0; t < t_hi; t += ustride) {
         int rows[RT];
         int head, pair0; bool rot;
         tile_rows(t, rows, head, pair0, rot);
         const uint4 *wp[RT];
-        float acc[RT];
+        float acc[RT][MP];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K); acc[r] = 0.f; }
+        for (int r = 0; r < RT; ++r) {
+            wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K);
+#pragma unroll
+            for (int m = 0; m < MP; ++m) acc[r][m] = 0.f;
+        }
         // what the epilogue will need from memory is requested now, ahead of the weight stream
-        float epi[RT];
+        float epi[RT][MP];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) epi[r] = 0.f;
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int m = 0; m < MP; ++m) epi[r][m] = 0.f;
         if (MODE == G_QKV) {
-            if (rot && !row_bad) {
+            if (rot) {
 #pragma unroll
-                for (int j = 0; j < P; ++j) {
-                    epi[2 * j] = a.rope_cos[(size_t)row_pos * half + pair0 + j];
-                    epi[2 * j + 1] = a.rope_sin[(size_t)row_pos * half + pair0 + j];
+                for (int m = 0; m < MP; ++m) if (!row_bad[m]) {
+#pragma unroll
+                    for (int j = 0; j < P; ++j) {
+                        epi[2 * j][m] = a.rope_cos[(size_t)row_pos[m] * half + pair0 + j];
+                        epi[2 * j + 1][m] = a.rope_sin[(size_t)row_pos[m] * half + pair0 + j];
+                    }
                 }
             }
         } else if (MODE == G_OPROJ || MODE == G_DOWN) {
 #pragma unroll
-            for (int r = 0; r < RT; ++r) epi[r] = a.h_out[rows[r]];
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int m = 0; m < MP; ++m) if (m < M) epi[r][m] = a.h_out[(size_t)m * a.ld_h + rows[r]];
         }
         if (resident) {
-            int c_start = c0;
-            if (PF > 0 && t == unit0) {
-#pragma unroll
-                for (int j = 0; j < NPF; ++j) {
-                    const int c = c0 + j * cstride;
-                    if (c < (K >> 3)) {
-                        const float4 xa = xs[c], xb = xs[plane_len + c];
-#pragma unroll
-                        for (int r = 0; r < RT; ++r) acc[r] = dot8f(pre[r][j], xa, xb, acc[r]);
-                    }
-                }
-                c_start = c0 + NPF * cstride;
-            }
-            gemv_accumulate<RT, UNR>(wp, xs, plane_len, 0, c_start, K >> 3, cstride, acc);
+            accumulate(wp, 0, c0, K >> 3, acc);
         } else {
-            for (int k0 = 0; k0 < K; k0 += GEMV_KSEG) {        // KS == 4 only: the tile loop is workgroup-uniform
-                const int len = min(GEMV_KSEG, K - k0);
+            for (int k0 = 0; k0 < K; k0 += seg) {              // KS == 4 only: the tile loop is workgroup-uniform
+                const int len = min(seg, K - k0);
                 __syncthreads();
                 stage(k0, len);
                 __syncthreads();
-                gemv_accumulate<RT, UNR>(wp, xs, plane_len, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, cstride, acc);
+                accumulate(wp, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, acc);
             }
         }
 #pragma unroll
-        for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int m = 0; m < MP; ++m) acc[r][m] = wave_sum(acc[r][m]);
         if (KS > 1) {
             if (lane == 0) {
 #pragma unroll
-                for (int r = 0; r < RT; ++r) red[(parity * 4 + wave) * RT + r] = acc[r];
+                for (int r = 0; r < RT; ++r)
+#pragma unroll
+                    for (int m = 0; m < MP; ++m) red[(parity * 4 + wave) * RT * MP + r * MP + m] = acc[r][m];
             }
             __syncthreads();
 #pragma unroll
             for (int r = 0; r < RT; ++r)
-                acc[r] = red[(parity * 4 + 0) * RT + r] + red[(parity * 4 + 1) * RT + r] + red[(parity * 4 + 2) * RT + r] +
-                         red[(parity * 4 + 3) * RT + r];
+#pragma unroll
+                for (int m = 0; m < MP; ++m)
+                    acc[r][m] = red[(parity * 4 + 0) * RT * MP + r * MP + m] + red[(parity * 4 + 1) * RT * MP + r * MP + m] +
+                                red[(parity * 4 + 2) * RT * MP + r * MP + m] + red[(parity * 4 + 3) * RT * MP + r * MP + m];
             parity ^= 1;
         }
         const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
         if (!writer) continue;
 
         // ---- epilogue (one lane)
-        if (MODE == G_QKV) {
-            if (row_bad) continue;
-            const int pos = row_pos, slot = row_slot;
-            if (rot) {
 #pragma unroll
-                for (int j = 0; j < P; ++j) {
-                    const int i = pair0 + j;
-                    const float c = epi[2 * j], s = epi[2 * j + 1], x0 = acc[2 * j], x1 = acc[2 * j + 1];
-                    const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
-                    if (head < a.n_q) {
-                        a.qbuf[head * a.head_dim + i] = y0; a.qbuf[head * a.head_dim + i + half] = y1;
-                    } else {
-                        const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + pos) * a.head_dim;
-                        a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
+        for (int m = 0; m < MP; ++m) {
+            if (m >= M) continue;
+            if (MODE == G_QKV) {
+                if (row_bad[m]) continue;
+                const int pos = row_pos[m], slot = row_slot[m];
+                if (rot) {
+#pragma unroll
+                    for (int j = 0; j < P; ++j) {
+                        const int i = pair0 + j;
+                        const float c = epi[2 * j][m], s = epi[2 * j + 1][m], x0 = acc[2 * j][m], x1 = acc[2 * j + 1][m];
+                        const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
+                        if (head < a.n_q) {
+                            float *q = a.qbuf + (size_t)m * a.n_q * a.head_dim + head * a.head_dim;
+                            q[i] = y0; q[i + half] = y1;
+                        } else {
+                            const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + pos) * a.head_dim;
+                            a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < RT; ++j) {
+                        const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
+                        const int vh = vr / a.head_dim, e = vr % a.head_dim;
+                        const size_t base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * (size_t)a.max_ctx * a.head_dim;
+                        a.vcache[base + (size_t)e * a.max_ctx + pos] = f32_to_bf16(acc[j][m]);     // V is stored [hd][position]
                     }
                 }
-            } else {
+            } else if (MODE == G_GATEUP) {
 #pragma unroll
-                for (int j = 0; j < RT; ++j) {
-                    const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
-                    const int vh = vr / a.head_dim, e = vr % a.head_dim;
-                    const size_t base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * (size_t)a.max_ctx * a.head_dim;
-                    a.vcache[base + (size_t)e * a.max_ctx + pos] = f32_to_bf16(acc[j]);     // V is stored [hd][position]
+                for (int j = 0; j < P; ++j) {
+                    const float g = acc[2 * j][m], u = acc[2 * j + 1][m];
+                    a.act[(size_t)m * a.d_ffn + t * P + j] = g / (1.0f + expf(-g)) * u;
                 }
-            }
-        } else if (MODE == G_GATEUP) {
+            } else if (MODE == G_OPROJ || MODE == G_DOWN) {
 #pragma unroll
-            for (int j = 0; j < P; ++j) {
-                const float g = acc[2 * j], u = acc[2 * j + 1];
-                a.act[t * P + j] = g / (1.0f + expf(-g)) * u;
-            }
-        } else if (MODE == G_OPROJ || MODE == G_DOWN) {
+                for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[(size_t)m * a.ld_h + t * RT + j] = epi[j][m] + acc[j][m];
+            } else {   // G_LMHEAD
 #pragma unroll
-            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[t * RT + j] = epi[j] + acc[j];
-        } else {   // G_LMHEAD
-#pragma unroll
-            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
-                const float lg = acc[j] * lm_scale;
-                st.push(lg, t * RT + j);
-                if (a.logits) a.logits[t * RT + j] = lg;
+                for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
+                    const float lg = acc[j][m] * lm_scale[m];
+                    st[m].push(lg, t * RT + j);
+                    if (a.logits) a.logits[(size_t)m * a.N + t * RT + j] = lg;
+                }
             }
         }
     }
     if (MODE == G_LMHEAD) {
         const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
-        if (writer) a.parts[(KS == 1) ? wg * 4 + wave : wg] = to_partial(st);
+        if (writer) {
+#pragma unroll
+            for (int m = 0; m < MP; ++m)
+                if (m < M) a.parts[(size_t)m * a.n_parts + ((KS == 1) ? wg * 4 + wave : wg)] = to_partial(st[m]);
+        }
     }
 }
 
-template <int MODE, int RT, int KS, int UNR = 2, int PF = 0>
+template <int MODE, int RT, int KS, int UNR, int MP>
 __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    gemv_phase<MODE, RT, KS, UNR, PF>(a, smem, blockIdx.x, gridDim.x);
+    gemv_phase<MODE, RT, KS, UNR, MP>(a, smem, blockIdx.x, gridDim.x);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(256) k_decode_persistent(PersistArgs p) {
         g.layer = l; at.layer = l;
         // QKV (+ RMSNorm, RoPE, KV write)
         g.W = lp.w_qkv; g.N = p.qkv_rows; g.K = d; g.h_in = h; g.gain = lp.attn_norm; g.x_in = nullptr;
-        if (p.qkv_rt == 2) gemv_phase<G_QKV, 2, 1>(g, smem, wg, nwg); else gemv_phase<G_QKV, 4, 1>(g, smem, wg, nwg);
+        gemv_phase<G_QKV, 2, 1, 2, 1>(g, smem, wg, nwg);
         RS_BARRIER();
         // attention: (slice, kv head) units, then one merge unit per query head
         for (int u = wg; u < p.n_splits * at.n_kv; u += nwg) {
@@ -120,22 +120,23 @@ __global__ void __launch_bounds__(256) k_decode_persistent(PersistArgs p) {
         RS_BARRIER();
         // O projection + residual
         g.W = lp.w_o; g.N = d; g.K = p.qdim; g.h_in = nullptr; g.gain = nullptr; g.x_in = at.out;
-        if (p.o_rt == 2) gemv_phase<G_OPROJ, 2, 1>(g, smem, wg, nwg); else gemv_phase<G_OPROJ, 4, 1>(g, smem, wg, nwg);
+        gemv_phase<G_OPROJ, 2, 1, 2, 1>(g, smem, wg, nwg);
         RS_BARRIER();
         // gate/up (+ RMSNorm, SwiGLU)
         g.W = lp.w_gate_up; g.N = 2 * g.d_ffn; g.K = d; g.h_in = h; g.gain = lp.mlp_norm; g.x_in = nullptr;
-        gemv_phase<G_GATEUP, 4, 1>(g, smem, wg, nwg);
+        gemv_phase<G_GATEUP, 4, 1, 4, 1>(g, smem, wg, nwg);
         RS_BARRIER();
         // down + residual
         g.W = lp.w_down; g.N = d; g.K = g.d_ffn; g.h_in = nullptr; g.gain = nullptr; g.x_in = g.act;
-        if (p.down_rt == 2) gemv_phase<G_DOWN, 2, 4>(g, smem, wg, nwg);
-        else if (p.down_rt == 4) gemv_phase<G_DOWN, 4, 4>(g, smem, wg, nwg);
-        else gemv_phase<G_DOWN, 8, 4>(g, smem, wg, nwg);
+        if (p.down_rt == 2) gemv_phase<G_DOWN, 2, 4, 2, 1>(g, smem, wg, nwg);
+        else if (p.down_rt == 4) gemv_phase<G_DOWN, 4, 4, 2, 1>(g, smem, wg, nwg);
+        else gemv_phase<G_DOWN, 8, 4, 1, 1>(g, smem, wg, nwg);
         RS_BARRIER();
     }
     // LM head + single-pass softmax statistics, one partial per wave
     g.W = p.lm_head; g.N = p.vocab; g.K = d; g.h_in = h; g.gain = p.final_norm; g.x_in = nullptr;
-    gemv_phase<G_LMHEAD, 8, 1>(g, smem, wg, nwg);
+    g.n_parts = nwg * 4;
+    gemv_phase<G_LMHEAD, 8, 1, 2, 1>(g, smem, wg, nwg);
     RS_BARRIER();
     if (wg == 0) route_merge_row(g.parts, nwg * 4, p.vocab, p.tau, p.active, p.seq_bad, p.out, 0, reinterpret_cast<SoftPartial *>(smem));
 #undef RS_BARRIER

@@ -60,7 +60,7 @@ const char *check_config(const rs_config *c) {
     if (c->max_seqs < 1 || c->max_seqs > 8) return "max_seqs must be in 1..8";
     if (c->max_rows < 1 || c->max_rows > 64) return "max_rows must be in 1..64";
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return "rms_eps must be > 0 and rope_theta > 1";
-    if (c->d_model > rs::GEMV_KSEG || c->n_q_heads * c->head_dim > rs::GEMV_KSEG)
+    if (c->d_model > 12288 || c->n_q_heads * c->head_dim > 12288)
         return "d_model and n_q_heads*head_dim must not exceed 12288";
     return nullptr;
 }
@@ -158,23 +158,34 @@ int clamp_blocks(int want, int n_tiles_per_wg_unit) {
 }
 
 // `blocks` workgroups share the phase; every workgroup takes a contiguous range of tiles
-template <int MODE, int RT, int KS, int UNR>
-rs_status launch_gemv(const rs_model *m, GemvArgs &a, int blocks, hipStream_t st, const char *name) {
-    const size_t lds = gemv_lds_bytes(a.K);
+template <int MODE, int RT, int KS, int UNR, int MP>
+rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *name) {
+    const size_t lds = gemv_lds_bytes<MP>(a.K);
     if (lds > 64 * 1024) {
         static bool raised = false;                       // per instantiation
         if (!raised) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_gemv<MODE, RT, KS, UNR, 0>,
+            hipError_t e = hipFuncSetAttribute((const void *)k_gemv<MODE, RT, KS, UNR, MP>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
             if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
             raised = true;
         }
     }
-    if (a.K > GEMV_KSEG && KS != 4) return fail(RS_EINVAL, "internal: segmented K needs the split-K launch");
-    (void)m;
-    hipLaunchKernelGGL((k_gemv<MODE, RT, KS, UNR, 0>), dim3(blocks), dim3(256), lds, st, a);
+    if (gemv_seg<MP>(a.K) != a.K && KS != 4) return fail(RS_EINVAL, "internal: segmented K needs the split-K launch");
+    hipLaunchKernelGGL((k_gemv<MODE, RT, KS, UNR, MP>), dim3(blocks), dim3(256), lds, st, a);
     RS_LAUNCHED(name);
     return RS_OK;
+}
+
+// mp = 1, 2, 4 or 8 token rows compiled in (a.m_rows <= mp)
+template <int MODE, int RT, int KS, int UNR>
+rs_status launch_gemv(const rs_model *m, GemvArgs &a, int mp, int blocks, hipStream_t st, const char *name) {
+    (void)m;
+    switch (mp) {
+        case 1: return launch_gemv_mp<MODE, RT, KS, UNR, 1>(a, blocks, st, name);
+        case 2: return launch_gemv_mp<MODE, RT, KS, UNR, 2>(a, blocks, st, name);
+        case 4: return launch_gemv_mp<MODE, RT, KS, UNR, 4>(a, blocks, st, name);
+        default: return launch_gemv_mp<MODE, RT, KS, UNR, 8>(a, blocks, st, name);
+    }
 }
 
 // Launch shapes from sweeps on MI355X: about three workgroups per CU for matrices under ~128 MB,
@@ -272,8 +283,8 @@ const void *persistent_kernel(int hd) {
 }
 
 size_t persistent_lds(const rs_config &c) {
-    size_t need = gemv_lds_bytes(c.d_model);
-    const size_t cand[] = {gemv_lds_bytes(c.n_q_heads * c.head_dim), gemv_lds_bytes(c.d_ffn),
+    size_t need = gemv_lds_bytes<1>(c.d_model);
+    const size_t cand[] = {gemv_lds_bytes<1>(c.n_q_heads * c.head_dim), gemv_lds_bytes<1>(c.d_ffn),
                            c.head_dim == 32 ? attn_lds_bytes<32>() : (c.head_dim == 64 ? attn_lds_bytes<64>() : attn_lds_bytes<128>()),
                            attn_combine_lds_bytes<32>()};
     for (size_t v : cand) if (v > need) need = v;
@@ -304,6 +315,7 @@ rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_to
     p.prep.h = m->at<float>(L.h);
 
     GemvArgs &g = p.gemv;
+    g.m_rows = 1; g.ld_h = c.d_model; g.gather = nullptr;
     g.eps = c.rms_eps; g.n_q = c.n_q_heads; g.n_kv = c.n_kv_heads; g.head_dim = hd; g.max_ctx = c.max_ctx;
     g.max_seqs = c.max_seqs; g.d_ffn = c.d_ffn;
     g.row_pos = p.prep.row_pos; g.row_slot = p.prep.row_slot; g.row_bad = p.prep.row_bad;
@@ -360,7 +372,11 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
     // attention launch shape
     const int n_splits = attn_splits(c, L, n_rows);
 
-    const bool single = (n_rows == 1);
+    // up to 4 rows go through the FMA GEMV kernels (weights streamed once, x rows in LDS: measured
+    // faster than the matrix-core path up to there); more rows, or rows that do not fit the LDS next
+    // to each other, go through the MFMA kernels
+    const int mp = n_rows <= 1 ? 1 : (n_rows <= 2 ? 2 : (n_rows <= 4 ? 4 : 8));
+    const bool single = n_rows <= 4 && (size_t)c.d_model * mp <= (size_t)GEMV_LDS_FLOATS && (size_t)qdim * mp <= (size_t)GEMV_LDS_FLOATS;
     rs_status rc;
     // optional event pair around one chosen kernel (rs_set_phase_timer)
     auto tic = [&](int phase, int layer) {
@@ -381,6 +397,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
 
         if (single) {
             GemvArgs g{};
+            g.m_rows = n_rows; g.ld_h = c.d_model;
             g.eps = c.rms_eps; g.n_q = c.n_q_heads; g.n_kv = c.n_kv_heads; g.head_dim = hd; g.max_ctx = c.max_ctx;
             g.max_seqs = c.max_seqs; g.layer = l; g.d_ffn = c.d_ffn;
             g.row_pos = row_pos; g.row_slot = row_slot; g.row_bad = row_bad;
@@ -392,15 +409,15 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             // QKV (+ RMSNorm, RoPE, KV write)
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_QKV, l);
-            rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, pl.qkv_blocks, st, "gemv_qkv");
+            rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
             toc(RS_PHASE_QKV, l);
             if (rc) return rc;
             // attention
             tic(RS_PHASE_ATTN, l);
             switch (hd) {
-                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, 1, st); break;
-                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, 1, st); break;
-                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, 1, st); break;
+                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
+                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
+                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
             }
             toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
@@ -408,13 +425,13 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.attn_out);
             tic(RS_PHASE_OPROJ, l);
-            rc = launch_gemv<G_OPROJ, 2, 1, 2>(m, g, pl.o_blocks, st, "gemv_oproj");
+            rc = launch_gemv<G_OPROJ, 2, 1, 2>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
             toc(RS_PHASE_OPROJ, l);
             if (rc) return rc;
             // gate/up (+ RMSNorm, SwiGLU)
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_GATEUP, l);
-            rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, pl.gu_blocks, st, "gemv_gateup");
+            rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
             toc(RS_PHASE_GATEUP, l);
             if (rc) return rc;
             // down + residual
@@ -422,12 +439,12 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.x_in = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
             switch (pl.down_rt) {
-                case 2: rc = launch_gemv<G_DOWN, 2, 4, 2>(m, g, pl.down_blocks, st, "gemv_down"); break;
-                case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, pl.down_blocks, st, "gemv_down"); break;
-                case 5: rc = launch_gemv<G_DOWN, 5, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
-                case 7: rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
-                case 8: rc = launch_gemv<G_DOWN, 8, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
-                default: rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, pl.down_blocks, st, "gemv_down"); break;
+                case 2: rc = launch_gemv<G_DOWN, 2, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                case 5: rc = launch_gemv<G_DOWN, 5, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                case 7: rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                case 8: rc = launch_gemv<G_DOWN, 8, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                default: rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
             }
             toc(RS_PHASE_DOWN, l);
             if (rc) return rc;
@@ -487,12 +504,14 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
     int n_parts;
     if (single) {
         GemvArgs g{};
+        g.m_rows = n_seqs; g.ld_h = c.d_model; g.gather = m->at<int>(L.out_row);
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
+        n_parts = m->plan.lm_blocks * 4; g.n_parts = n_parts;
+        const int mp_lm = n_seqs <= 1 ? 1 : (n_seqs <= 2 ? 2 : (n_seqs <= 4 ? 4 : 8));
         tic(RS_PHASE_LMHEAD, 0);
-        if ((rc = launch_gemv<G_LMHEAD, 8, 1, 2>(m, g, m->plan.lm_blocks, st, "gemv_lmhead"))) return rc;
+        if ((rc = launch_gemv<G_LMHEAD, 8, 1, 2>(m, g, mp_lm, m->plan.lm_blocks, st, "gemv_lmhead"))) return rc;
         toc(RS_PHASE_LMHEAD, 0);
-        n_parts = m->plan.lm_blocks * 4;
     } else {
         uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
         const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
