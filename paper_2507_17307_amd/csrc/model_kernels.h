@@ -434,7 +434,7 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 //                                                           accumulator registers (the token <-> k
 //                                                           slot assignment is free as long as both
 //                                                           operands agree)
-// A wave handles 64 tokens per pass with an online softmax; the four waves are merged through LDS
+// A wave handles 16 tokens per pass with an online softmax; the four waves are merged through LDS
 // and the workgroup writes one partial record per query head: [m, l, 0, 0, acc[HD]] fp32.
 //
 // k_attn_combine: grid (n_q_heads, n_rows), block 256: merges the slices of one head.
@@ -454,27 +454,20 @@ struct AttnArgs {
 };
 
 constexpr int ATT_GMAX = 8;       // query heads per kv head, at most
-constexpr int ATT_SMAX = 64;      // context slices, at most
-constexpr int ATT_WT = 64;        // tokens per wave and pass
-constexpr int ATT_BT = 256;       // tokens per workgroup and pass
+constexpr int ATT_SMAX = 128;     // context slices, at most
+constexpr int ATT_WT = 16;        // tokens per wave and pass
+constexpr int ATT_BT = 64;        // tokens per workgroup and pass
 
 // split 8 fp32 values into three bf16x8 planes whose sum is exact
 __device__ __forceinline__ void split3(const float (&x)[8], bf16x8_t (&pl)[3]) {
     uint32_t w0[4], w1[4], w2[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        uint16_t a[2], b[2], c[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float v = x[2 * i + h];
-            a[h] = f32_to_bf16(v);
-            const float r1 = v - bf16_to_f32(a[h]);
-            b[h] = f32_to_bf16(r1);
-            c[h] = f32_to_bf16(r1 - bf16_to_f32(b[h]));
-        }
-        w0[i] = (uint32_t)a[0] | ((uint32_t)a[1] << 16);
-        w1[i] = (uint32_t)b[0] | ((uint32_t)b[1] << 16);
-        w2[i] = (uint32_t)c[0] | ((uint32_t)c[1] << 16);
+        const float a = x[2 * i], b = x[2 * i + 1];
+        w0[i] = pack_bf16x2(a, b);
+        const float ra = a - bf16_lo(w0[i]), rb = b - bf16_hi(w0[i]);
+        w1[i] = pack_bf16x2(ra, rb);
+        w2[i] = pack_bf16x2(ra - bf16_lo(w1[i]), rb - bf16_hi(w1[i]));
     }
     pl[0] = __builtin_bit_cast(bf16x8_t, make_uint4(w0[0], w0[1], w0[2], w0[3]));
     pl[1] = __builtin_bit_cast(bf16x8_t, make_uint4(w1[0], w1[1], w1[2], w1[3]));
@@ -484,6 +477,40 @@ __device__ __forceinline__ void split3(const float (&x)[8], bf16x8_t (&pl)[3]) {
 template <int HD>
 __host__ __device__ constexpr size_t attn_lds_bytes() { return (size_t)(4 * 16 * (HD + 4) + 2 * 4 * 16) * 4; }
 
+#ifdef RS_ATT_TRACE
+__device__ long long g_att_trace[4096 * 8];
+#define ATT_T(k) do { if (threadIdx.x == 0) g_att_trace[((kvh * S + split) * 8) + (k)] = wall_clock64(); } while (0)
+#else
+#define ATT_T(k) do { } while (0)
+#endif
+
+// Cache operands of one wave pass (ATT_WT = 16 tokens from t0): K rows as the A operand of the score
+// contraction, V^T rows as the A operand of the output contraction.  The loads are unconditional:
+// positions are clamped into the cache row (max_ctx is a multiple of 8, so a group of 4 positions
+// that starts at or before max_ctx - 4 ends inside it) and a clamped lane just fetches a duplicate.
+// Which tokens count is decided later by masks, once the row's context length has arrived; without
+// branches around them the compiler issues all loads back to back and waits once.
+template <int HD>
+struct AttnTile {
+    uint4 k[HD / 32];
+    uint2 v[HD / 16];
+    __device__ __forceinline__ void load(const uint16_t *Kp, const uint16_t *Vp, int t0, int max_ctx, int j, int kg) {
+        const int tok = min(t0 + j, max_ctx - 1);
+#pragma unroll
+        for (int ds = 0; ds < HD / 32; ++ds)
+            k[ds] = *reinterpret_cast<const uint4 *>(Kp + (size_t)tok * HD + 32 * ds + 8 * kg);
+        const int tv = min(t0 + 4 * kg, max_ctx - 4);
+#pragma unroll
+        for (int db = 0; db < HD / 16; ++db)
+            v[db] = *reinterpret_cast<const uint2 *>(Vp + (size_t)(16 * db + j) * max_ctx + tv);
+    }
+};
+
+// One (context slice, kv head, token row) unit.  Slice s covers positions [s*C, (s+1)*C) with C fixed
+// by max_ctx and the slice count, NOT by the row's context length: the addresses of the first pass
+// are known at launch, so the row table, q, K and V are all requested at once and the unit pays one
+// memory round trip instead of three dependent ones.  Slices at or past the context length write
+// empty partials (L = 0).
 template <int HD>
 __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned char *smem, int split, int S, int kvh, int row) {
     constexpr int NDS = HD / 32;       // 32-wide d steps of the score contraction
@@ -497,82 +524,86 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     float (*m_lds)[16] = reinterpret_cast<float (*)[16]>(smem + (size_t)4 * 16 * (HD + 4) * 4);   // [4][16]
     float (*l_lds)[16] = m_lds + 4;
 
-    const int bad = a.row_bad[row];
-    const int ctx = bad ? 0 : a.row_pos[row] + 1;
-    const int slot = bad ? 0 : a.row_slot[row];
-    int C = (ctx + S - 1) / S;
-    C = ((C + ATT_WT - 1) / ATT_WT) * ATT_WT;
+    ATT_T(0);
+    int C = (a.max_ctx + S - 1) / S;
+    C = ((C + ATT_BT - 1) / ATT_BT) * ATT_BT;
     const int t_begin = split * C;
-    const int t_end = min(ctx, t_begin + C);
+    // with one cache slot the slot index needs no load; otherwise clamp it so that a row the
+    // validation rejected (its slot is then stored as 0 anyway) can never address outside the cache
+    int slot = 0;
+    if (a.max_seqs > 1) slot = min(max(a.row_slot[row], 0), a.max_seqs - 1);
+    const int bad = a.row_bad[row];
+    const int pos = a.row_pos[row];
     const size_t kv_base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + kvh) * (size_t)a.max_ctx * HD;
     const uint16_t *Kp = a.kcache + kv_base;      // [position][hd]
     const uint16_t *Vp = a.vcache + kv_base;      // [hd][position]
     const float scale = 1.0f / sqrtf((float)HD);
 
+    // lanes j >= G have no head: they fetch head G-1 again and are cleared after the wait
+    float4 qraw[NDS][2];
+    {
+        const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + min(j, G - 1)) * HD + 8 * kg);
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) { qraw[ds][0] = qp[8 * ds]; qraw[ds][1] = qp[8 * ds + 1]; }
+    }
+    AttnTile<HD> cur;
+    cur.load(Kp, Vp, t_begin + wave * ATT_WT, a.max_ctx, j, kg);
+    __builtin_amdgcn_sched_barrier(0);             // every request is in flight before anything waits
+
+    const int ctx = bad ? 0 : pos + 1;
+    const int t_end = min(ctx, t_begin + C);
+    if (t_begin >= t_end) {                        // nothing of this slice is in the context
+        for (int i = tid; i < G * HD; i += 256) {
+            const int g = i / HD, d = i - g * HD;
+            float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
+            p[4 + d] = 0.f;
+            if (d == 0) { p[0] = 0.f; p[1] = 0.f; }
+        }
+        return;
+    }
+
     // q of head j as the B operand of the score contraction: three exact bf16 planes per d step
     bf16x8_t qB[NDS][3];
 #pragma unroll
     for (int ds = 0; ds < NDS; ++ds) {
-        float qv[8];
+        const float4 x0 = qraw[ds][0], x1 = qraw[ds][1];
+        float qv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+        if (j >= G) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qv[e] = 0.f;
-        if (j < G) {
-            const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)row * a.n_q + kvh * G + j) * HD + 32 * ds + 8 * kg);
-            const float4 x0 = qp[0], x1 = qp[1];
-            qv[0] = x0.x; qv[1] = x0.y; qv[2] = x0.z; qv[3] = x0.w; qv[4] = x1.x; qv[5] = x1.y; qv[6] = x1.z; qv[7] = x1.w;
+            for (int e = 0; e < 8; ++e) qv[e] = 0.f;
         }
         split3(qv, qB[ds]);
     }
 
+    ATT_T(1);
     float m_run = -INFINITY, l_run = 0.f;          // head j (replicated over the four kg groups)
     f32x4_t acc[NDB];                              // out[d = 16 db + 4 kg + r][head j]
 #pragma unroll
     for (int db = 0; db < NDB; ++db) acc[db] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     for (int t0 = t_begin + wave * ATT_WT; t0 < t_end; t0 += ATT_BT) {
-        // ---- scores of 4 blocks of 16 tokens
-        f32x4_t sc[4];
+        AttnTile<HD> nxt;
+        const bool more = t0 + ATT_BT < t_end;
+        if (more) nxt.load(Kp, Vp, t0 + ATT_BT, a.max_ctx, j, kg);
+        // ---- scores of 16 tokens; lane holds tokens t0 + 4 kg + r of head j.
+        // Positions at or past t_end may hold anything (a rejected step's rows, never-written memory):
+        // their scores are replaced, not scaled.
+        f32x4_t sc = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
-            sc[tb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-            const int tok = t0 + tb * 16 + j;                          // A row of this lane
-            uint4 kv[NDS];
+        for (int ds = 0; ds < NDS; ++ds) {
+            const bf16x8_t A = __builtin_bit_cast(bf16x8_t, cur.k[ds]);
 #pragma unroll
-            for (int ds = 0; ds < NDS; ++ds) {
-                kv[ds] = make_uint4(0, 0, 0, 0);
-                if (tok < t_end) kv[ds] = *reinterpret_cast<const uint4 *>(Kp + (size_t)tok * HD + 32 * ds + 8 * kg);
-            }
-#pragma unroll
-            for (int ds = 0; ds < NDS; ++ds) {
-                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, kv[ds]);
-#pragma unroll
-                for (int pl = 2; pl >= 0; --pl) sc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc[tb], 0, 0, 0);
-            }
+            for (int pl = 2; pl >= 0; --pl) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc, 0, 0, 0);
         }
-        // ---- V^T operand loads: lane (d = 16 db + j, kg) reads tokens t0 + 32 ks + {4 kg .. +4} and + 16
-        uint2 vv[2][NDB][2];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
-                    const int tok = t0 + 32 * ks + 16 * hf + 4 * kg;
-                    vv[ks][db][hf] = make_uint2(0, 0);
-                    if (tok < t_end)      // t_end <= max_ctx (multiple of 8): the 4 tokens are inside the row
-                        vv[ks][db][hf] = *reinterpret_cast<const uint2 *>(Vp + (size_t)(16 * db + j) * a.max_ctx + tok);
-                }
-        // ---- online softmax over this pass: lane holds tokens t0 + 16 tb + 4 kg + r of head j
         float mx = -INFINITY;
+        const int tok_lo = t0 + 4 * kg;
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int tok = t0 + tb * 16 + 4 * kg + r;
-                const float v = tok < t_end ? sc[tb][r] * scale : -INFINITY;
-                sc[tb][r] = v;
-                mx = fmaxf(mx, v);
-            }
+        for (int r = 0; r < 4; ++r) {
+            const float v = tok_lo + r < t_end ? sc[r] * scale : -INFINITY;
+            sc[r] = v;
+            mx = fmaxf(mx, v);
+        }
+        ATT_T(2);
         mx = fmaxf(mx, __shfl_xor(mx, 16, RS_WAVE));
         mx = fmaxf(mx, __shfl_xor(mx, 32, RS_WAVE));
         const float m_new = fmaxf(m_run, mx);                         // finite: the pass has at least one valid token
@@ -581,43 +612,33 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
         l_run *= alpha;
 #pragma unroll
         for (int db = 0; db < NDB; ++db) { acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha; }
-        // ---- P V: k slot (kg, e = 4 hf + r) of k-step ks is token t0 + 32 ks + 16 hf + 4 kg + r
+        ATT_T(3);
+        // ---- P V: k slot (kg, r) is token t0 + 4 kg + r; slots (kg, 4..7) are unused (zero on both sides)
+        float pv[8];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            float pv[8];
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float s_ = sc[2 * ks + hf][r];
-                    const float p = (s_ == -INFINITY) ? 0.f : expf(s_ - m_new);
-                    pv[4 * hf + r] = p;
-                    l_run += p;
-                }
-            bf16x8_t pB[3];
-            split3(pv, pB);
-#pragma unroll
-            for (int db = 0; db < NDB; ++db) {
-                // tokens past t_end may hold anything (even NaN patterns): they were loaded as zeros above,
-                // but a partially valid group of 4 needs its tail cleared as well
-                uint2 lo = vv[ks][db][0], hi = vv[ks][db][1];
-                const int tok_lo = t0 + 32 * ks + 4 * kg, tok_hi = tok_lo + 16;
-                if (tok_lo + 3 >= t_end) {
-                    if (tok_lo + 1 >= t_end) lo.x &= 0x0000ffffu;
-                    if (tok_lo + 2 >= t_end) lo.y = 0; else if (tok_lo + 3 >= t_end) lo.y &= 0x0000ffffu;
-                    if (tok_lo >= t_end) lo.x = 0;
-                }
-                if (tok_hi + 3 >= t_end) {
-                    if (tok_hi + 1 >= t_end) hi.x &= 0x0000ffffu;
-                    if (tok_hi + 2 >= t_end) hi.y = 0; else if (tok_hi + 3 >= t_end) hi.y &= 0x0000ffffu;
-                    if (tok_hi >= t_end) hi.x = 0;
-                }
-                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, make_uint4(lo.x, lo.y, hi.x, hi.y));
-#pragma unroll
-                for (int pl = 2; pl >= 0; --pl) acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, pB[pl], acc[db], 0, 0, 0);
-            }
+        for (int r = 0; r < 4; ++r) {
+            const float p = (sc[r] == -INFINITY) ? 0.f : expf(sc[r] - m_new);
+            pv[r] = p; pv[4 + r] = 0.f;
+            l_run += p;
         }
+        bf16x8_t pB[3];
+        split3(pv, pB);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+            // clear the V columns of positions at or past t_end (0 * NaN would poison the sum)
+            uint2 lo = cur.v[db];
+            if (tok_lo + 3 >= t_end) {
+                if (tok_lo + 1 >= t_end) lo.x &= 0x0000ffffu;
+                if (tok_lo + 2 >= t_end) lo.y = 0; else if (tok_lo + 3 >= t_end) lo.y &= 0x0000ffffu;
+                if (tok_lo >= t_end) lo.x = 0;
+            }
+            const bf16x8_t A = __builtin_bit_cast(bf16x8_t, make_uint4(lo.x, lo.y, 0u, 0u));
+#pragma unroll
+            for (int pl = 2; pl >= 0; --pl) acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, pB[pl], acc[db], 0, 0, 0);
+        }
+        if (more) cur = nxt;
     }
+    ATT_T(4);
     // l_run so far covers this lane's own tokens: add the other three kg groups
     l_run += __shfl_xor(l_run, 16, RS_WAVE);
     l_run += __shfl_xor(l_run, 32, RS_WAVE);
@@ -643,6 +664,7 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
         p[4 + d] = O;
         if (d == 0) { p[0] = M; p[1] = L; }
     }
+    ATT_T(5);
 }
 
 template <int HD>
@@ -673,15 +695,22 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
         if (s < S) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + 4 * qd);
     }
     if (wave == 0) {
-        float ms = -INFINITY, ls = 0.f;
-        if (lane < S) {
-            const float2 ml = *reinterpret_cast<const float2 *>(pbase + (size_t)lane * PS);
-            ls = ml.y; ms = ls > 0.f ? ml.x : -INFINITY;
+        static_assert(ATT_SMAX <= 128, "two slices per lane");
+        float ms[2], ls[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int s = lane + 64 * k;
+            ms[k] = -INFINITY; ls[k] = 0.f;
+            if (s < S) {
+                const float2 ml = *reinterpret_cast<const float2 *>(pbase + (size_t)s * PS);
+                ls[k] = ml.y; ms[k] = ls[k] > 0.f ? ml.x : -INFINITY;
+            }
         }
-        const float M = wave_max(ms);
-        const float w = ls > 0.f ? expf(ms - M) : 0.f;
-        const float L = wave_sum(ls * w);
-        w_sh[lane] = L > 0.f ? w / L : 0.f;
+        const float M = wave_max(fmaxf(ms[0], ms[1]));
+        const float w0 = ls[0] > 0.f ? expf(ms[0] - M) : 0.f, w1 = ls[1] > 0.f ? expf(ms[1] - M) : 0.f;
+        const float L = wave_sum(ls[0] * w0 + ls[1] * w1);
+        w_sh[lane] = L > 0.f ? w0 / L : 0.f;
+        w_sh[lane + 64] = L > 0.f ? w1 / L : 0.f;
     }
     __syncthreads();
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);

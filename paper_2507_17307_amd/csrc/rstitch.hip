@@ -76,7 +76,7 @@ struct GemvPlan {
     int qkv_rt, qkv_blocks, o_rt, o_blocks, gu_blocks, down_rt, down_blocks, lm_blocks;
 };
 
-int attn_pairs_cap(const rs_config &c) { return c.max_rows > 256 ? c.max_rows : 256; }
+int attn_pairs_cap(const rs_config &c) { return c.max_rows > 512 ? c.max_rows : 512; }
 
 constexpr int LM_PARTS_CAP = 4096;
 
@@ -292,7 +292,7 @@ size_t persistent_lds(const rs_config &c) {
 }
 
 int attn_splits(const rs_config &c, const Layout &L, int n_rows) {
-    const int att_ts = 128;                                // tokens per context slice at full context
+    const int att_ts = ATT_BT;                             // tokens per context slice: one pass of a workgroup
     int n_splits = (c.max_ctx + att_ts - 1) / att_ts;
     if (n_splits > ATT_SMAX) n_splits = ATT_SMAX;
     if (n_splits * n_rows > L.attn_rows_x_splits) n_splits = L.attn_rows_x_splits / n_rows;
