@@ -44,15 +44,31 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
 }
 
 // ---------------------------------------------------------------- wave64 reductions
+// Cross-lane steps as DPP operands of the add / max itself (no LDS round trip per step): two
+// quad permutes and two mirrors leave every lane with the total of its row of 16; row_bcast15
+// and row_bcast31 then carry the row totals upward so that lane 63 holds the wave's total, which
+// a readlane broadcasts.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float old, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, RS_WAVE);
-    return v;
+    v += dpp_f32<0xB1, 0xf>(0.f, v);      // quad_perm [1,0,3,2]
+    v += dpp_f32<0x4E, 0xf>(0.f, v);      // quad_perm [2,3,0,1]
+    v += dpp_f32<0x141, 0xf>(0.f, v);     // row_half_mirror
+    v += dpp_f32<0x140, 0xf>(0.f, v);     // row_mirror
+    v += dpp_f32<0x142, 0xa>(0.f, v);     // row_bcast15 into rows 1 and 3
+    v += dpp_f32<0x143, 0xc>(0.f, v);     // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, RS_WAVE));
-    return v;
+    v = fmaxf(v, dpp_f32<0xB1, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x4E, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x141, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x140, 0xf>(v, v));
+    v = fmaxf(v, dpp_f32<0x142, 0xa>(v, v));
+    v = fmaxf(v, dpp_f32<0x143, 0xc>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // ---------------------------------------------------------------- softmax / entropy / argmax in one pass

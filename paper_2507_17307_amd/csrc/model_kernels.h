@@ -25,54 +25,67 @@ struct PrepArgs {
     float *h;
 };
 
-__device__ __forceinline__ void prepare_row(const PrepArgs &a, int r, int *sh /* 4 ints of LDS */) {
+constexpr int PREP_LDS_INTS = 128;
+
+// sh: PREP_LDS_INTS ints of LDS.  The control values may live in pinned host memory, where every
+// dependent read costs a bus round trip: each one is requested by its own thread, all at once,
+// and the validation then runs out of LDS.
+__device__ __forceinline__ void prepare_row(const PrepArgs &a, int r, int *sh) {
     const int tid = threadIdx.x;
+    int *s_off = sh + 4, *s_slot = sh + 16, *s_pos = sh + 24, *s_tok = sh + 40;     // [9], [8], [8], [64]
+    float *s_scale = reinterpret_cast<float *>(sh + 32);                             // [8]
+    const int ns = min(a.n_seqs, 8), nr = min(a.n_rows, 64);                         // the host enforces both bounds
+    if (a.span_off != nullptr && tid <= ns) s_off[tid] = a.span_off[tid];
+    if (tid >= 64 && tid < 64 + ns) {
+        const int i = tid - 64;
+        s_slot[i] = a.seq_slot[i]; s_pos[i] = a.pos0[i]; s_scale[i] = a.scale ? a.scale[i] : 1.f;
+    }
+    if (tid >= 128 && tid < 128 + nr) s_tok[tid - 128] = a.tokens[tid - 128];
+    __syncthreads();
     if (tid == 0) {
         int b = -1, lo = 0, hi = 0, bad = 0;
         if (a.span_off == nullptr) { b = r; lo = r; hi = r + 1; }
         else {
-            if (a.span_off[0] != 0 || a.span_off[a.n_seqs] != a.n_rows) bad = 1;
-            for (int i = 0; i < a.n_seqs; ++i) {
-                int o0 = a.span_off[i], o1 = a.span_off[i + 1];
+            if (s_off[0] != 0 || s_off[ns] != a.n_rows) bad = 1;
+            for (int i = 0; i < ns; ++i) {
+                const int o0 = s_off[i], o1 = s_off[i + 1];
                 if (o1 <= o0 || o0 < 0 || o1 > a.n_rows) bad = 1;        // empty or malformed span
                 if (r >= o0 && r < o1 && b < 0) { b = i; lo = o0; hi = o1; }
             }
             if (b < 0) bad = 1;
         }
         if (!bad) {
-            int slot = a.seq_slot[b], p0 = a.pos0[b];
+            const int slot = s_slot[b], p0 = s_pos[b];
             if (slot < 0 || slot >= a.max_seqs || p0 < 0 || p0 > a.max_ctx - (hi - lo)) bad = 1;
-            for (int i = 0; i < a.n_seqs && !bad; ++i)                   // slots must be distinct
-                if (i != b && a.seq_slot[i] == slot) bad = 1;
+            for (int i = 0; i < ns && !bad; ++i)                         // slots must be distinct
+                if (i != b && s_slot[i] == slot) bad = 1;
             for (int i = lo; i < hi && !bad; ++i) {
-                int t = a.tokens[i];
+                const int t = s_tok[i];
                 if (t < 0 || t >= a.vocab) bad = 1;
             }
         }
         sh[0] = b; sh[1] = lo; sh[2] = hi; sh[3] = bad;
-    }
-    __syncthreads();
-    const int b = sh[0], lo = sh[1], hi = sh[2], bad = sh[3];
-    if (tid == 0) {
         a.row_bad[r] = bad;
-        a.row_slot[r] = bad ? 0 : a.seq_slot[b];
-        a.row_pos[r] = bad ? 0 : a.pos0[b] + (r - lo);
-        if (b >= 0 && r == hi - 1 && b < a.n_seqs) {
+        a.row_slot[r] = bad ? 0 : s_slot[b];
+        a.row_pos[r] = bad ? 0 : s_pos[b] + (r - lo);
+        if (b >= 0 && r == hi - 1 && b < ns) {
             a.out_row[b] = r; a.seq_bad[b] = bad;
-            a.seq_scale[b] = a.scale ? a.scale[b] : 1.f;
+            a.seq_scale[b] = s_scale[b];
         }
         // a malformed offset table can leave sequences without any row: flag them all
         if (bad && a.span_off != nullptr && r == 0)
-            for (int i = 0; i < a.n_seqs; ++i) { a.seq_bad[i] = 1; a.out_row[i] = 0; a.seq_scale[i] = 1.f; }
+            for (int i = 0; i < ns; ++i) { a.seq_bad[i] = 1; a.out_row[i] = 0; a.seq_scale[i] = 1.f; }
     }
+    __syncthreads();
+    const int bad = sh[3];
     float *h = a.h + (size_t)r * a.d_model;
     if (bad) { for (int i = tid; i < a.d_model; i += 256) h[i] = 0.f; return; }
-    const uint16_t *e = a.embed + (size_t)a.tokens[r] * a.d_model;
+    const uint16_t *e = a.embed + (size_t)s_tok[r] * a.d_model;
     for (int i = tid; i < a.d_model; i += 256) h[i] = bf16_to_f32(e[i]);
 }
 
 __global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
-    __shared__ int sh[4];     // b, first row, last row (exclusive), bad
+    __shared__ int sh[PREP_LDS_INTS];
     prepare_row(a, blockIdx.x, sh);
 }
 
@@ -118,8 +131,17 @@ __host__ __device__ constexpr int gemv_seg(int K) { return K * MP <= GEMV_LDS_FL
 template <int MP>
 __host__ __device__ constexpr size_t gemv_lds_bytes(int K) { return (size_t)gemv_seg<MP>(K) * MP * 4 + 4096; }
 
-template <int MODE, int RT, int KS, int UNR, int MP>
+#ifdef RS_GEMV_TRACE
+__device__ long long g_gemv_trace[4096 * 8];
+#define GEMV_T(k) do { if (threadIdx.x == 0 && wg < 4096) g_gemv_trace[wg * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define GEMV_T(k) do { } while (0)
+#endif
+
+template <int MODE, int RT, int KS, int UNR, int MP, int PRE = 0>
 __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *smem, int wg, int nwg) {
+    static_assert(PRE == 0 || MP == 1, "the early weight request exists for single-row calls only");
+    GEMV_T(0);
     float4 *xs = reinterpret_cast<float4 *>(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int K = a.K, M = a.m_rows;
@@ -144,7 +166,8 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
     }
     // each workgroup owns a contiguous range of tiles (a contiguous stretch of W); with KS == 1 its
     // four waves interleave inside that range
-    const int t_lo = (int)(((long long)n_tiles * wg) / nwg), t_hi = (int)(((long long)n_tiles * (wg + 1)) / nwg);
+    // n_tiles * nwg stays far below 2^31 (at most ~2e4 tiles, a few thousand workgroups)
+    const int t_lo = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)nwg), t_hi = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)nwg);
     const int unit0 = (KS == 1) ? t_lo + wave : t_lo;
     const int ustride = (KS == 1) ? 4 : 1;
     const int c0 = (KS == 1) ? lane : wave * 64 + lane;
@@ -169,6 +192,24 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
             for (int j = 0; j < RT; ++j) rows[j] = min(t * RT + j, a.N - 1);
         }
     };
+
+    // PRE > 0: the first PRE chunks of this wave's first tile are requested before the prologue
+    // touches x, so the weight stream's first round trip overlaps the prologue's instead of
+    // following it.  It costs PRE * RT * 4 registers, so it is compiled in only where the sweep
+    // showed a gain.  Chunk indices are clamped, not guarded; a clamped chunk is cancelled later by
+    // zeroing its x operand.
+    uint4 pre[PRE > 0 ? PRE : 1][RT];
+    const bool have0 = PRE > 0 && resident && unit0 < t_hi;
+    if (have0) {
+        int rows0[RT], head0, pair00; bool rot0;
+        tile_rows(unit0, rows0, head0, pair00, rot0);
+#pragma unroll
+        for (int u = 0; u < PRE; ++u) {
+            const int c = min(c0 + u * cstride, (K >> 3) - 1);
+#pragma unroll
+            for (int r = 0; r < RT; ++r) pre[u][r] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)rows0[r] * K) + c);
+        }
+    }
 
     // row position / slot (QKV only), read once up front so that no epilogue waits on it
     int row_bad[MP], row_pos[MP], row_slot[MP];
@@ -213,6 +254,7 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
             if (lane == 0) red_ss[wave * MP + m] = ss;
         }
         __syncthreads();
+        GEMV_T(1);
 #pragma unroll
         for (int m = 0; m < MP; ++m)
             inv[m] = 1.0f / sqrtf((red_ss[0 * MP + m] + red_ss[1 * MP + m] + red_ss[2 * MP + m] + red_ss[3 * MP + m]) / (float)K + a.eps);
@@ -246,12 +288,25 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                     xm[(i & 1) * plane_len + (i >> 1)] = v;
                 }
             } else {
+                // batches of SB loads per thread, all requested before the first is stored
                 const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in + (size_t)m * K + k0);
-                for (int i = tid; i < (len >> 2); i += 256) xm[(i & 1) * plane_len + (i >> 1)] = x4[i];
+                constexpr int SB = 10;
+                const int n4 = len >> 2;
+                for (int i0 = tid; i0 < n4; i0 += 256 * SB) {
+                    float4 v[SB];
+#pragma unroll
+                    for (int j = 0; j < SB; ++j) v[j] = x4[min(i0 + j * 256, n4 - 1)];
+#pragma unroll
+                    for (int j = 0; j < SB; ++j) {
+                        const int i = i0 + j * 256;
+                        if (i < n4) xm[(i & 1) * plane_len + (i >> 1)] = v[j];
+                    }
+                }
             }
         }
     };
     if (resident) { stage(0, K); __syncthreads(); }
+    GEMV_T(2);
 
     SoftState st[MP];
     float lm_scale[MP];
@@ -320,7 +375,27 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 for (int m = 0; m < MP; ++m) if (m < M) epi[r][m] = a.h_out[(size_t)m * a.ld_h + rows[r]];
         }
         if (resident) {
-            accumulate(wp, 0, c0, K >> 3, acc);
+            int cb = c0;
+            if (PRE > 0 && t == unit0) {
+#pragma unroll
+                for (int u = 0; u < PRE; ++u) {
+                    const int c = c0 + u * cstride;
+                    const bool valid = c < (K >> 3);
+                    const int cc = valid ? c : 0;
+                    float4 xa = xs[cc], xb = xs[plane_len + cc];
+                    if (!valid) { xa = make_float4(0.f, 0.f, 0.f, 0.f); xb = xa; }
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) {
+                        const uint4 w = pre[u][r];
+                        float v = acc[r][0];
+                        v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
+                        v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
+                        acc[r][0] = v;
+                    }
+                }
+                cb = c0 + PRE * cstride;
+            }
+            accumulate(wp, 0, cb, K >> 3, acc);
         } else {
             for (int k0 = 0; k0 < K; k0 += seg) {              // KS == 4 only: the tile loop is workgroup-uniform
                 const int len = min(seg, K - k0);
@@ -330,10 +405,12 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 accumulate(wp, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, acc);
             }
         }
+        if (t == unit0) GEMV_T(3);
 #pragma unroll
         for (int r = 0; r < RT; ++r)
 #pragma unroll
             for (int m = 0; m < MP; ++m) acc[r][m] = wave_sum(acc[r][m]);
+        if (t == unit0) GEMV_T(4);
         if (KS > 1) {
             if (lane == 0) {
 #pragma unroll
@@ -350,6 +427,7 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                                 red[(parity * 4 + 2) * RT * MP + r * MP + m] + red[(parity * 4 + 3) * RT * MP + r * MP + m];
             parity ^= 1;
         }
+        if (t == unit0) GEMV_T(5);
         const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
         if (!writer) continue;
 
@@ -402,20 +480,33 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
             }
         }
     }
+    GEMV_T(6);
     if (MODE == G_LMHEAD) {
-        const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
-        if (writer) {
+        // one partial per workgroup and token row: the four waves' states meet in LDS
+        SoftPartial *sp = reinterpret_cast<SoftPartial *>(red);           // [4][MP], inside the 4 KB tail of the segment
+        if (KS == 1) {
+            if (lane == 0) {
+#pragma unroll
+                for (int m = 0; m < MP; ++m) sp[wave * MP + m] = to_partial(st[m]);
+            }
+            __syncthreads();
+            if (tid < MP && tid < M) {
+                SoftState s0 = from_partial(sp[tid]);
+                for (int w = 1; w < 4; ++w) s0.merge(from_partial(sp[w * MP + tid]));
+                a.parts[(size_t)tid * a.n_parts + wg] = to_partial(s0);
+            }
+        } else if (tid == 0) {
 #pragma unroll
             for (int m = 0; m < MP; ++m)
-                if (m < M) a.parts[(size_t)m * a.n_parts + ((KS == 1) ? wg * 4 + wave : wg)] = to_partial(st[m]);
+                if (m < M) a.parts[(size_t)m * a.n_parts + wg] = to_partial(st[m]);
         }
     }
 }
 
-template <int MODE, int RT, int KS, int UNR, int MP>
+template <int MODE, int RT, int KS, int UNR, int MP, int PRE = 0>
 __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    gemv_phase<MODE, RT, KS, UNR, MP>(a, smem, blockIdx.x, gridDim.x);
+    gemv_phase<MODE, RT, KS, UNR, MP, PRE>(a, smem, blockIdx.x, gridDim.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -510,7 +601,7 @@ struct AttnTile {
 // by max_ctx and the slice count, NOT by the row's context length: the addresses of the first pass
 // are known at launch, so the row table, q, K and V are all requested at once and the unit pays one
 // memory round trip instead of three dependent ones.  Slices at or past the context length write
-// empty partials (L = 0).
+// nothing; attn_combine_unit derives the same slice length and reads only the slices before it.
 template <int HD>
 __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned char *smem, int split, int S, int kvh, int row) {
     constexpr int NDS = HD / 32;       // 32-wide d steps of the score contraction
@@ -552,15 +643,7 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
 
     const int ctx = bad ? 0 : pos + 1;
     const int t_end = min(ctx, t_begin + C);
-    if (t_begin >= t_end) {                        // nothing of this slice is in the context
-        for (int i = tid; i < G * HD; i += 256) {
-            const int g = i / HD, d = i - g * HD;
-            float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
-            p[4 + d] = 0.f;
-            if (d == 0) { p[0] = 0.f; p[1] = 0.f; }
-        }
-        return;
-    }
+    if (t_begin >= t_end) return;                  // nothing of this slice is in the context: the merge skips it too
 
     // q of head j as the B operand of the score contraction: three exact bf16 planes per d step
     bf16x8_t qB[NDS][3];
@@ -687,12 +770,16 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
     float (*red)[HD] = reinterpret_cast<float (*)[HD]>(w_sh + ATT_SMAX);         // [NSG][HD]
     const float *pbase = a.partials + ((size_t)row * a.n_q + head) * S * PS;
     const int qd = tid % NQ, sg = tid / NQ;
+    // slices that hold context: same slice length as attn_partial_unit
+    int C = (a.max_ctx + S - 1) / S;
+    C = ((C + ATT_BT - 1) / ATT_BT) * ATT_BT;
+    const int S_act = a.row_bad[row] ? 0 : min(S, a.row_pos[row] / C + 1);
     float4 buf[NLD];
 #pragma unroll
     for (int k = 0; k < NLD; ++k) {
         const int s = sg + k * NSG;
         buf[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (s < S) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + 4 * qd);
+        if (s < S_act) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + 4 * qd);
     }
     if (wave == 0) {
         static_assert(ATT_SMAX <= 128, "two slices per lane");
@@ -701,7 +788,7 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
         for (int k = 0; k < 2; ++k) {
             const int s = lane + 64 * k;
             ms[k] = -INFINITY; ls[k] = 0.f;
-            if (s < S) {
+            if (s < S_act) {
                 const float2 ml = *reinterpret_cast<const float2 *>(pbase + (size_t)s * PS);
                 ls[k] = ml.y; ms[k] = ls[k] > 0.f ? ml.x : -INFINITY;
             }
@@ -717,7 +804,7 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
 #pragma unroll
     for (int k = 0; k < NLD; ++k) {
         const int s = sg + k * NSG;
-        const float w = s < S ? w_sh[s] : 0.f;
+        const float w = s < S_act ? w_sh[s] : 0.f;
         sum.x = fmaf(w, buf[k].x, sum.x); sum.y = fmaf(w, buf[k].y, sum.y); sum.z = fmaf(w, buf[k].z, sum.z); sum.w = fmaf(w, buf[k].w, sum.w);
     }
     *reinterpret_cast<float4 *>(&red[sg][4 * qd]) = sum;

@@ -133,12 +133,12 @@ __global__ void __launch_bounds__(256) k_decode_persistent(PersistArgs p) {
         else gemv_phase<G_DOWN, 8, 4, 1, 1>(g, smem, wg, nwg);
         RS_BARRIER();
     }
-    // LM head + single-pass softmax statistics, one partial per wave
+    // LM head + single-pass softmax statistics, one partial per workgroup
     g.W = p.lm_head; g.N = p.vocab; g.K = d; g.h_in = h; g.gain = p.final_norm; g.x_in = nullptr;
-    g.n_parts = nwg * 4;
+    g.n_parts = nwg;
     gemv_phase<G_LMHEAD, 8, 1, 2, 1>(g, smem, wg, nwg);
     RS_BARRIER();
-    if (wg == 0) route_merge_row(g.parts, nwg * 4, p.vocab, p.tau, p.active, p.seq_bad, p.out, 0, reinterpret_cast<SoftPartial *>(smem));
+    if (wg == 0) route_merge_row(g.parts, nwg, p.vocab, p.tau, p.active, p.seq_bad, p.out, 0, reinterpret_cast<SoftPartial *>(smem));
 #undef RS_BARRIER
 }
 

@@ -74,6 +74,7 @@ struct Layout {
 
 struct GemvPlan {
     int qkv_rt, qkv_blocks, o_rt, o_blocks, gu_blocks, down_rt, down_blocks, lm_blocks;
+    bool gu_early;      // gate/up single-row kernel with the early weight request
 };
 
 int attn_pairs_cap(const rs_config &c) { return c.max_rows > 512 ? c.max_rows : 512; }
@@ -158,30 +159,30 @@ int clamp_blocks(int want, int n_tiles_per_wg_unit) {
 }
 
 // `blocks` workgroups share the phase; every workgroup takes a contiguous range of tiles
-template <int MODE, int RT, int KS, int UNR, int MP>
+template <int MODE, int RT, int KS, int UNR, int MP, int PRE = 0>
 rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *name) {
     const size_t lds = gemv_lds_bytes<MP>(a.K);
     if (lds > 64 * 1024) {
         static bool raised = false;                       // per instantiation
         if (!raised) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_gemv<MODE, RT, KS, UNR, MP>,
+            hipError_t e = hipFuncSetAttribute((const void *)k_gemv<MODE, RT, KS, UNR, MP, PRE>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
             if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
             raised = true;
         }
     }
     if (gemv_seg<MP>(a.K) != a.K && KS != 4) return fail(RS_EINVAL, "internal: segmented K needs the split-K launch");
-    hipLaunchKernelGGL((k_gemv<MODE, RT, KS, UNR, MP>), dim3(blocks), dim3(256), lds, st, a);
+    hipLaunchKernelGGL((k_gemv<MODE, RT, KS, UNR, MP, PRE>), dim3(blocks), dim3(256), lds, st, a);
     RS_LAUNCHED(name);
     return RS_OK;
 }
 
-// mp = 1, 2, 4 or 8 token rows compiled in (a.m_rows <= mp)
-template <int MODE, int RT, int KS, int UNR>
+// mp = 1, 2, 4 or 8 token rows compiled in (a.m_rows <= mp); PRE: early weight request of the single-row kernel
+template <int MODE, int RT, int KS, int UNR, int PRE = 0>
 rs_status launch_gemv(const rs_model *m, GemvArgs &a, int mp, int blocks, hipStream_t st, const char *name) {
     (void)m;
     switch (mp) {
-        case 1: return launch_gemv_mp<MODE, RT, KS, UNR, 1>(a, blocks, st, name);
+        case 1: return launch_gemv_mp<MODE, RT, KS, UNR, 1, PRE>(a, blocks, st, name);
         case 2: return launch_gemv_mp<MODE, RT, KS, UNR, 2>(a, blocks, st, name);
         case 4: return launch_gemv_mp<MODE, RT, KS, UNR, 4>(a, blocks, st, name);
         default: return launch_gemv_mp<MODE, RT, KS, UNR, 8>(a, blocks, st, name);
@@ -200,6 +201,7 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
     p.o_rt = 2;
     p.o_blocks = clamp_blocks(pick((size_t)c.d_model * c.n_q_heads * hd * 2), ((c.d_model + 1) / 2 + 3) / 4);
     p.gu_blocks = clamp_blocks(pick((size_t)2 * c.d_ffn * c.d_model * 2), (c.d_ffn / 2 + 3) / 4);
+    p.gu_early = (size_t)2 * c.d_ffn * c.d_model * 2 >= ((size_t)128 << 20);
     // down: split-K workgroups, rows per workgroup chosen so that ~2 workgroups per CU have one tile each
     const int want = (c.d_model + 2 * n_cu - 1) / (2 * n_cu);
     const int opts[] = {2, 4, 5, 7, 8, 10};
@@ -208,7 +210,7 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
     if (c.d_model <= 2048) p.down_rt = 2;
     p.down_blocks = clamp_blocks(3 * n_cu, (c.d_model + p.down_rt - 1) / p.down_rt);
     p.lm_blocks = clamp_blocks(4 * n_cu, ((c.vocab + 7) / 8 + 3) / 4);
-    if (p.lm_blocks * 4 > LM_PARTS_CAP) p.lm_blocks = LM_PARTS_CAP / 4;
+    if (p.lm_blocks > LM_PARTS_CAP) p.lm_blocks = LM_PARTS_CAP;
     return p;
 }
 
@@ -425,13 +427,15 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.attn_out);
             tic(RS_PHASE_OPROJ, l);
-            rc = launch_gemv<G_OPROJ, 2, 1, 2>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
+            rc = launch_gemv<G_OPROJ, 2, 1, 2, 4>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
             toc(RS_PHASE_OPROJ, l);
             if (rc) return rc;
             // gate/up (+ RMSNorm, SwiGLU)
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_GATEUP, l);
-            rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
+            // large matrices run two workgroups per CU, which leaves registers for the early weight request
+            if (pl.gu_early && mp == 1) rc = launch_gemv<G_GATEUP, 4, 1, 4, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
+            else rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
             toc(RS_PHASE_GATEUP, l);
             if (rc) return rc;
             // down + residual
@@ -507,7 +511,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         g.m_rows = n_seqs; g.ld_h = c.d_model; g.gather = m->at<int>(L.out_row);
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
-        n_parts = m->plan.lm_blocks * 4; g.n_parts = n_parts;
+        n_parts = m->plan.lm_blocks; g.n_parts = n_parts;
         const int mp_lm = n_seqs <= 1 ? 1 : (n_seqs <= 2 ? 2 : (n_seqs <= 4 ? 4 : 8));
         tic(RS_PHASE_LMHEAD, 0);
         if ((rc = launch_gemv<G_LMHEAD, 8, 1, 2>(m, g, mp_lm, m->plan.lm_blocks, st, "gemv_lmhead"))) return rc;
