@@ -8,6 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "rstitch.hip")
 LIB = os.path.join(HERE, "librstitch.so")
+PROBE_SRC = os.path.join(HERE, "csrc", "traffic_probe.hip")
+PROBE = os.path.join(HERE, "traffic_probe")
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
@@ -16,9 +18,7 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [SRC, "-o", LIB]
+def _run(cmd, verbose: bool) -> None:
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -28,6 +28,14 @@ def build(verbose: bool = True) -> str:
         print(err, file=sys.stderr)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
+
+
+def build(verbose: bool = True) -> str:
+    """The library, then the counter-run driver that links against it (found through $ORIGIN)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + FLAGS + [SRC, "-o", LIB], verbose)
+    probe_flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    _run([hipcc] + probe_flags + [PROBE_SRC, "-o", PROBE, "-L" + HERE, "-lrstitch", "-Wl,-rpath,$ORIGIN"], verbose)
     return LIB
 
 

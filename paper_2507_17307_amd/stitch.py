@@ -138,3 +138,123 @@ class StitchedPair:
             if stop_after is not None and stop_after(len(run.output)):
                 break
         return run
+
+
+class StitchedBatch:
+    """Algorithm 1 for several independent sequences that share the two models, with per-sequence
+    routing (the batch-8 setting of the paper's batch-size study).
+
+    Every sequence keeps its own state (tokens, cached length per model, active model) and its own
+    KV slot in both models.  A round advances, with as few library calls as possible, first every
+    sequence whose active model is the small one, then every sequence on the large one: the unseen
+    suffixes of a group are packed back to back into one ragged rs_catchup_prefill call (or one
+    rs_decode_step when every suffix is a single token), chunked when they exceed max_rows.  A
+    sequence the small model gives up on in the first half of a round is picked up by the large
+    model in the second half.  Because sequences never interact, each one's outcome equals the
+    single-sequence loop's.
+    """
+
+    def __init__(self, slm: B.Model, llm: B.Model, max_ctx: int, scale_tables: Sequence[torch.Tensor]):
+        self.models = [slm, llm]
+        self.max_ctx = max_ctx
+        self.n_slots = min(slm.cfg.max_seqs, llm.cfg.max_seqs)
+        if len(scale_tables) > self.n_slots:
+            raise ValueError("more sequences than KV slots")
+        self.max_rows = min(slm.cfg.max_rows, llm.cfg.max_rows)
+        self.stream = torch.cuda.Stream(device=slm.device)
+        self.scale_np = [t.to(dtype=torch.float32).cpu().numpy() for t in scale_tables]
+        ns, mr = self.n_slots, self.max_rows
+        # fixed-address pinned staging: slots[ns] tokens[mr] offsets[ns+1] pos0[ns] scales[ns] records[6*ns]
+        self.stage = torch.zeros(ns + mr + (ns + 1) + ns + ns + 6 * ns, dtype=torch.int32).pin_memory()
+        self.stage_i = self.stage.numpy()
+        self.stage_f = self.stage_i.view(np.float32)
+        self._o_slot, self._o_tok = 0, ns
+        self._o_off = ns + mr
+        self._o_pos = self._o_off + ns + 1
+        self._o_scale = self._o_pos + ns
+        self._o_rec = self._o_scale + ns
+        self._base = self.stage.data_ptr()
+        torch.cuda.synchronize()
+
+    def _ptr(self, index: int) -> int:
+        return self._base + 4 * index
+
+    def _call(self, model: int, entries, tau: float, lengths) -> None:
+        """entries: (sequence, first position, row count), at most n_slots of them and max_rows rows in all."""
+        si, sf = self.stage_i, self.stage_f
+        row = 0
+        for i, (b, p0, n) in enumerate(entries):
+            si[self._o_slot + i] = b
+            si[self._o_tok + row:self._o_tok + row + n] = self.seqs[b][p0:p0 + n]
+            si[self._o_off + i] = row
+            si[self._o_pos + i] = p0
+            sf[self._o_scale + i] = self.scale_np[b][lengths[b]]
+            row += n
+        si[self._o_off + len(entries)] = row
+        h, lib, sh = self.models[model].handle, B.lib, self.stream.cuda_stream
+        if row == len(entries):
+            rc = lib.rs_decode_step(h, len(entries), self._ptr(self._o_slot), self._ptr(self._o_tok), self._ptr(self._o_pos),
+                                    self._ptr(self._o_scale), tau, model, self._ptr(self._o_rec), None, sh)
+        else:
+            rc = lib.rs_catchup_prefill(h, len(entries), row, self._ptr(self._o_slot), self._ptr(self._o_tok),
+                                        self._ptr(self._o_off), self._ptr(self._o_pos), self._ptr(self._o_scale),
+                                        tau, model, self._ptr(self._o_rec), None, sh)
+        if rc != 0:
+            raise B.RsError(rc, B.rs_last_error())
+        self.stream.synchronize()
+        self.calls += 1
+
+    def generate(self, prompts: Sequence[Sequence[int]], tau: float, n_tokens: int,
+                 single_model: Optional[int] = None) -> List[StitchRun]:
+        nb = len(prompts)
+        if nb > len(self.scale_np):
+            raise ValueError("more prompts than scale tables")
+        self.seqs = [np.zeros(self.max_ctx + 1, dtype=np.int32) for _ in range(nb)]
+        lengths = []
+        for b, p in enumerate(prompts):
+            if len(p) + n_tokens > self.max_ctx + 1:
+                raise ValueError("prompt + tokens exceed max_ctx")
+            self.seqs[b][:len(p)] = np.asarray(p, dtype=np.int32)
+            lengths.append(len(p))
+        n_kv = [[0] * nb, [0] * nb]
+        active = [SLM if single_model is None else single_model] * nb
+        runs = [StitchRun() for _ in range(nb)]
+        self.calls = 0
+        live = set(range(nb))
+        while live:
+            for model in (SLM, LLM):
+                group = [b for b in sorted(live) if active[b] == model]
+                fed = {b: n_kv[model][b] for b in group}
+                while group:
+                    entries, rows = [], 0
+                    for b in group:
+                        if rows >= self.max_rows or len(entries) >= self.n_slots:
+                            break
+                        n = min(lengths[b] - fed[b], self.max_rows - rows)
+                        entries.append((b, fed[b], n))
+                        rows += n
+                    self._call(model, entries, tau, lengths)
+                    for i, (b, p0, n) in enumerate(entries):
+                        fed[b] += n
+                        if fed[b] < lengths[b]:
+                            continue                       # more of this suffix to feed: the record is not the final one
+                        o = self._o_rec + 6 * i
+                        token, flags = int(self.stage_i[o]), int(self.stage_i[o + 1]) & 0xFFFFFFFF
+                        if flags & (B.FLAG_BADARG | B.FLAG_NONFINITE | B.FLAG_ABORTED):
+                            raise RuntimeError(f"router flagged the step: flags={flags} model={model} sequence={b}")
+                        runs[b].trace.append(Invocation(model, n_kv[model][b], lengths[b] - n_kv[model][b], token,
+                                                        float(self.stage_f[o + 3]), flags))
+                        n_kv[model][b] = lengths[b]
+                        group.remove(b)
+                        if single_model is None:
+                            if model == SLM and (flags & B.FLAG_HI):
+                                active[b] = LLM            # rejected: the large model redoes this position
+                                continue
+                            if model == LLM and not (flags & B.FLAG_HI):
+                                active[b] = SLM
+                        self.seqs[b][lengths[b]] = token
+                        lengths[b] += 1
+                        runs[b].output.append(token)
+                        if len(runs[b].output) >= n_tokens:
+                            live.discard(b)
+        return runs

@@ -223,3 +223,39 @@ def test_live_stitched_run_through_the_host_driver_matches_the_oracle_run(decode
     # and again on the same pair: the caches are overwritten with identical values, graphs are replayed
     again = pair.generate(W.make_prompt(wl).tolist(), tau, wl.n_decode)
     assert again.output == run.output and [t.flags for t in again.trace] == [t.flags for t in run.trace]
+
+
+def test_batched_stitched_run_with_per_sequence_routing_matches_per_sequence_oracle_runs(decode_path):
+    """Four sequences with different prompt lengths share the two tiny models (one KV slot each) and are
+    routed independently by the batched host driver; each must reproduce the oracle's single-sequence
+    Algorithm 1 run on its own prompt and logit-scale schedule: same tokens, same model / first position /
+    span / acceptance per invocation, entropies within tolerance."""
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedBatch
+    wl = W.WORKLOADS["cfg1_tiny_pair"]
+    ws, wl_ = W.make_weights(wl.slm, wl.seed, 0), W.make_weights(wl.llm, wl.seed, 1)
+    lens, n_tok = [20, 32, 7, 45], 24
+    max_ctx = max(lens) + n_tok + 3
+    prompts = [W.make_prompt(wl, seq=b, length=n).tolist() for b, n in enumerate(lens)]
+    scales = [W.logit_scale(wl, 0, max_ctx + 1, seq=b) for b in range(len(lens))]
+    mk = lambda: [decoder.OracleModel(ws, max_ctx + 1), decoder.OracleModel(wl_, max_ctx + 1)]  # noqa: E731
+    hs = []
+    for b in range(len(lens)):
+        sc = lambda p, b=b: float(scales[b][p])  # noqa: E731
+        hs += [t.h_norm for t in stitch.generate(prompts[b], stitch.decoder_forward(mk(), sc), 2.0, n_tok).trace]
+    tau = W.pick_tau(hs, 60.0, 4e-3 / math.log(wl.slm.vocab))
+    ref = []
+    for b in range(len(lens)):
+        sc = lambda p, b=b: float(scales[b][p])  # noqa: E731
+        ref.append(stitch.generate(prompts[b], stitch.decoder_forward(mk(), sc), tau, n_tok))
+    gpu = [P.Model(w.to("cuda"), max_ctx=max_ctx + 1, max_seqs=4, max_rows=64) for w in (ws, wl_)]
+    batch = StitchedBatch(gpu[0], gpu[1], max_ctx, scales)
+    runs = batch.generate(prompts, tau, n_tok)
+    assert any(t.model == 1 for r in ref for t in r.trace) and any(not t.accept for r in ref for t in r.trace)
+    for b, (run, res) in enumerate(zip(runs, ref)):
+        assert run.output == res.output, f"sequence {b}"
+        assert [(t.model, t.pos0, t.n_rows, t.accept) for t in run.trace] == \
+               [(t.model, t.pos0, len(t.span), t.accept) for t in res.trace], f"sequence {b}"
+        assert max(abs(x.h_norm - y.h_norm) for x, y in zip(run.trace, res.trace)) <= 1e-3 / math.log(1024)
+    # fewer library calls than the four sequences would need one by one
+    assert batch.calls < sum(len(r.trace) for r in ref)
