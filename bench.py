@@ -60,6 +60,111 @@ class HipEvents:
         return ms.value if rc == 0 else float("nan")
 
 
+def bench_single_model(args, wl) -> int:
+    """Workload without a large model: the small model decodes alone after its prompt (no routing)."""
+    import torch
+    import workloads as W
+    from workloads import shapes as S
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedPair, SLM
+
+    w_s = W.make_weights(wl.slm, wl.seed, 0, device="cuda")
+    max_ctx = wl.max_ctx
+    slm = P.Model(w_s, max_ctx=max_ctx, max_rows=64)
+    pair = StitchedPair(slm, None, max_ctx, W.logit_scale(wl, 0, max_ctx + 1))
+    prompt = W.make_prompt(wl).tolist()
+    marks = {}
+
+    def stop_after(n_acc):
+        if n_acc == args.warmup:
+            torch.cuda.synchronize()
+            marks["t0"] = time.perf_counter()
+        return False
+
+    if args.warmup == 0:
+        torch.cuda.synchronize()
+        marks["t0"] = time.perf_counter()
+    pair.generate(prompt, 2.0, args.warmup + args.steps, single_model=SLM, keep_trace=False, stop_after=stop_after)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - marks["t0"]
+    ctx_mid = len(prompt) + args.warmup + args.steps // 2
+    ideal = S.step_bytes(wl.slm, [ctx_mid]) / HBM_PEAK
+    print(json.dumps({
+        "metric": f"decode tokens/s at batch 1 ({wl.slm.name} shape alone)", "value": round(args.steps / elapsed, 2),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",
+        "config": {"workload": args.workload, "slm": wl.slm.name, "batch": 1, "prompt_len": len(prompt), "max_ctx": max_ctx},
+        "roofline": None, "cpu_baseline": None,
+        "per_model": {"slm": {"shape": wl.slm.name, "ctx": ctx_mid, "ms_per_token_wall": round(elapsed / args.steps * 1e3, 4),
+                              "roofline_ms": round(ideal * 1e3, 4), "roofline_frac": round(ideal / (elapsed / args.steps), 4)}},
+    }), flush=True)
+    return 0
+
+
+def bench_batched(args, wl) -> int:
+    """Several sequences with per-sequence routing on one pair of models (the batch-8 workload)."""
+    import torch
+    import workloads as W
+    from workloads import shapes as S
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedBatch, SLM, LLM
+
+    nb = wl.n_seqs
+    t0 = time.time()
+    w_s = W.make_weights(wl.slm, wl.seed, 0, device="cuda")
+    w_l = W.make_weights(wl.llm, wl.seed, 1, device="cuda")
+    torch.cuda.synchronize()
+    log(f"[bench] weights generated on the GPU in {time.time() - t0:.1f}s")
+    prompts = [W.make_prompt(wl, seq=b).tolist() for b in range(nb)]
+    n_total = args.warmup + args.steps
+    max_ctx = max(len(p) for p in prompts) + max(n_total, args.tau_steps or 0) + 8
+    slm = P.Model(w_s, max_ctx=max_ctx, max_seqs=nb, max_rows=64)
+    llm = P.Model(w_l, max_ctx=max_ctx, max_seqs=nb, max_rows=64)
+    batch = StitchedBatch(slm, llm, max_ctx, [W.logit_scale(wl, 0, max_ctx + 1, seq=b) for b in range(nb)])
+    ln_v = math.log(wl.slm.vocab)
+    n_tau = args.tau_steps or 128
+    solo = batch.generate(prompts, 2.0, n_tau, single_model=SLM)
+    tau = W.pick_tau([t.h_norm for r in solo for t in r.trace], wl.tau_percentile, 4e-3 / ln_v)
+    log(f"[bench] small-model-only run of {n_tau} tokens per sequence; tau = {tau:.6f}")
+    marks = {}
+
+    def progress(accepted_total):
+        if "t0" not in marks and accepted_total >= args.warmup * nb:
+            torch.cuda.synchronize()
+            marks["t0"] = time.perf_counter()
+            marks["acc0"] = accepted_total
+            marks["calls0"] = batch.calls
+
+    batch.on_call = progress
+    runs = batch.generate(prompts, tau, n_total)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - marks["t0"]
+    accepted = sum(len(r.output) for r in runs) - marks["acc0"]
+    calls = batch.calls - marks["calls0"]
+    llm_tok = sum(1 for r in runs for t in r.trace if t.model == LLM and t.accept)
+    all_tok = sum(len(r.output) for r in runs)
+    # roofline of one round in which every sequence takes a small-model step and the routed share a large-model step
+    ctx = [len(p) + n_total // 2 for p in prompts]
+    frac = llm_tok / max(all_tok, 1)
+    ideal_round = (S.step_bytes(wl.slm, ctx) + frac * S.step_bytes(wl.llm, ctx)) / HBM_PEAK
+    print(json.dumps({
+        "metric": f"stitched decode tokens/s over {nb} sequences ({wl.llm.name}+{wl.slm.name} shapes)",
+        "value": round(accepted / elapsed, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / max(accepted, 1) * nb * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",
+        "config": {"workload": args.workload, "slm": wl.slm.name, "llm": wl.llm.name, "batch": nb,
+                   "prompt_lens": [len(p) for p in prompts], "tau": round(tau, 6), "tau_percentile": wl.tau_percentile,
+                   "max_ctx": max_ctx},
+        "roofline": None, "cpu_baseline": None,
+        "stitched": {"accepted_tokens": accepted, "library_calls": calls, "llm_token_frac": round(frac, 4),
+                     "ms_per_call": round(elapsed / max(calls, 1) * 1e3, 4),
+                     "rejected_slm_steps": sum(1 for r in runs for t in r.trace if not t.accept),
+                     "roofline_ms_per_round_estimate": round(ideal_round * 1e3, 4)},
+    }), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,7 +189,10 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = W.WORKLOADS[args.workload]
-    assert wl.n_seqs == 1 and wl.llm is not None, "bench.py times the batch-1 stitched workloads"
+    if wl.llm is None:
+        return bench_single_model(args, wl)
+    if wl.n_seqs > 1:
+        return bench_batched(args, wl)
     if args.warmup + args.steps > wl.n_decode:
         print(f"bench.py: warmup + steps must not exceed {wl.n_decode}", file=sys.stderr)
         return 2
@@ -246,7 +354,8 @@ def main() -> int:
                "s_per_invocation": {k: round(v, 2) for k, v in t_inv.items()}}
 
     line = {
-        "metric": "stitched decode tokens/s at batch 1 (7B+1.5B shapes)",
+        "metric": ("stitched decode tokens/s at batch 1 (7B+1.5B shapes)" if args.workload == "cfg3_s15_m7"
+                   else f"stitched decode tokens/s at batch 1 ({wl.llm.name}+{wl.slm.name} shapes)"),
         "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",

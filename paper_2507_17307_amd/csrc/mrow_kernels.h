@@ -80,15 +80,21 @@ __global__ void __launch_bounds__(256) k_rope_kv_rows(RopeArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // out[m, n] = sum_k X[m, k] W[n, k] for M <= 16*NB token rows.
-// A workgroup of NW waves owns 16 output columns at a time (for gate/up: 16 gate rows and the 16
-// matching up rows of W); its waves split K in interleaved blocks of 256 elements.  Per block a
-// wave streams its 16 x 512-byte piece of W from HBM with fully coalesced 16-byte loads (a load
-// instruction covers two whole 512-byte row pieces; the next block is in flight in registers
-// while the current one is multiplied), parks it in its private LDS region, and reads it back in
-// the operand layout of v_mfma_f32_16x16x32_bf16 (lane (i = lane % 16, g = lane / 16) supplies
-// the 8 consecutive k at 32 s + 8 g of row i).  The token side comes from the three bf16 planes
-// of X through L2 in the same k layout.  The per-wave 16x16 accumulators (lane holds
-// D[4 g + r][token = lane % 16]) are summed through LDS by wave 0, which runs the epilogue.
+// A workgroup of GEMM_NW waves owns R consecutive tiles of 16 output columns (for gate/up a tile is 16
+// gate rows plus the 16 matching up rows of W) and ALL of K; wave w takes the k windows w, w+GEMM_NW,
+// ... of 64 elements (more waves where a matrix has few tiles, so that enough requests are in flight).  Per window a wave requests
+//   * its piece of X once: three bf16 planes, 16 tokens x 64 k per 16-token block, each lane
+//     straight in the B-operand layout of v_mfma_f32_16x16x32_bf16 (lane (i = lane % 16, g = lane / 16)
+//     supplies the 8 consecutive k at 32 s + 8 g of token i); the piece serves all R tiles, so X
+//     costs 3/R of the W bytes in L2 traffic;
+//   * the 16 x 64 piece of W of every tile it owns with coalesced 16-byte loads, eight lanes per
+//     128-byte row piece (whole cache lines: on this chip 64-byte pieces, which the operand layout
+//     would give directly, stream at 4.5 TB/s, 128-byte pieces at 6.2), parked in the wave's private
+//     LDS area and read back in the A-operand layout.
+// The requests of the next window are in flight while the current one is multiplied.  The per-wave
+// 16x16 accumulators (lane holds D[4 g + r][token = lane % 16]) of a group meet in LDS; wave p sums
+// and finishes tile-and-token-block pair p.  The launch makes every group resident at once, with the
+// groups spread evenly over the CUs, because a CU draws at most ~30 GB/s (see launch_gemm).
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
     const uint16_t *W; int N, K, M;       // M = valid token rows
@@ -99,28 +105,36 @@ struct GemmArgs {
     const float *seq_scale; SoftPartial *parts; float *logits; int n_parts;   // LM head
 };
 
-constexpr int GEMM_KB = 256;                      // k elements per block
-constexpr int GEMM_ROWB = GEMM_KB * 2 + 16;       // bytes per staged row (padded against LDS bank conflicts)
+constexpr int GEMM_KW = 64;                       // k elements per window: K must be a multiple
+constexpr int GEMM_PITCH = GEMM_KW * 2 + 16;      // bytes per parked row (padded against LDS bank conflicts)
 
-template <int MODE, int NB, int NW>
+template <int MODE, int NB, int R, int GEMM_NW>
 __host__ __device__ constexpr size_t gemm_lds_bytes() {
-    return (size_t)NW * ((MODE == G_GATEUP) ? 2 : 1) * (16 * GEMM_ROWB + NB * 1024);
+    constexpr size_t nt = (MODE == G_GATEUP) ? 2 : 1;
+    constexpr size_t park = (size_t)GEMM_NW * R * nt * 16 * GEMM_PITCH, meet = (size_t)GEMM_NW * R * nt * NB * 1024;
+    return park > meet ? (park > 2048 ? park : 2048) : (meet > 2048 ? meet : 2048);   // 2 KB: the LM head's state exchange
 }
 
-template <int MODE, int NB, int NW>
-__global__ void __launch_bounds__(NW * 64) k_gemm_rows(GemmArgs a) {
+template <int MODE, int NB, int R, int GEMM_NW>
+__global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
+    constexpr bool TWO_IN_FLIGHT = NB == 1;                               // larger token blocks have no registers to spare
     constexpr int NT = (MODE == G_GATEUP) ? 2 : 1;
+    constexpr int NS = GEMM_KW / 32;
+    constexpr int NQ = (16 * GEMM_KW * 2) / 1024;                         // load instructions per 16-row piece (2)
+    constexpr int SLOTS = R * NT * NB;
+    static_assert(MODE != G_LMHEAD || NB == 1, "the router state of a lane follows one token");
     extern __shared__ __align__(16) unsigned char smem[];
+    float4 *red = reinterpret_cast<float4 *>(smem);                       // [GEMM_NW][SLOTS][64], after the last window
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
-    unsigned char *wlds = smem + (size_t)wave * NT * 16 * GEMM_ROWB;                       // this wave's staging area
-    float4 *red = reinterpret_cast<float4 *>(smem + (size_t)NW * NT * 16 * GEMM_ROWB);     // [NW][NT][NB][64]
+    unsigned char *park = smem + (size_t)wave * R * NT * 16 * GEMM_PITCH;   // this wave's [R*NT][16 rows][GEMM_PITCH]
+    const int lrow = lane >> 3, lchunk = lane & 7;                        // load role: row 8 q + lrow, bytes 16 lchunk ..
     const int K = a.K;
     const int n_out = (MODE == G_GATEUP) ? a.d_ffn : a.N;                 // distinct output columns
-    const int n_tiles = (n_out + 15) / 16;
-    // global-load role of this lane: load q (0..7) fetches rows 2q and 2q+1, lane covers 16 bytes of one of them
-    const int lrow = lane >> 5, lchunk = lane & 31;
+    const int n_tiles = (n_out + 15) / 16, n_groups = (n_tiles + R - 1) / R;
+    const int n_win = K / GEMM_KW;
 
+    // token side: rows past M read row 0 and are cleared after the load
     const uint16_t *xp[NB];
     bool xok[NB];
 #pragma unroll
@@ -132,119 +146,160 @@ __global__ void __launch_bounds__(NW * 64) k_gemm_rows(GemmArgs a) {
     SoftState st; st.init();
     const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
 
-    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const int n0 = t * 16;
-        f32x4_t acc[NT][NB];
+    for (int grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+        f32x4_t acc[R][NT][NB];
+        const uint16_t *wp[R][NT][NQ];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) acc[nt][nb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-
-        // row pointers of the 8 loads per tile
-        const uint16_t *wrow[NT][8];
+            for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+                for (int q = 0; q < NQ; ++q) {
+                    const int row = min((grp * R + r) * 16 + 8 * q + lrow, n_out - 1) + (nt == 1 ? a.d_ffn : 0);
+                    wp[r][nt][q] = a.W + (size_t)row * K + lchunk * 8;
+                }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int r = min(n0 + 2 * q + lrow, n_out - 1) + (nt == 1 ? a.d_ffn : 0);
-                wrow[nt][q] = a.W + (size_t)r * K + lchunk * 8;
+                for (int nb = 0; nb < NB; ++nb) acc[r][nt][nb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
             }
-        uint4 cur[NT][8];
-        int kb = wave * GEMM_KB;
-        auto fetch = [&](int k0, uint4 (&dst)[NT][8]) {
-            const bool ok = k0 + lchunk * 8 < K;            // K is a multiple of 128, a block may be half empty
+        // two windows in flight per wave: the requests of the next window are issued before the
+        // products of the current one.  Requests are unconditional (the window index is clamped;
+        // a duplicate is fetched but never multiplied) so that the compiler can count them and wait
+        // for exactly the older set.
+        auto request = [&](int win, uint4 (&xb)[NB][NS][3], uint4 (&wr)[R][NT][NQ]) {
+            const int k0 = min(win, n_win - 1) * GEMM_KW;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    dst[nt][q] = ok ? load_stream(reinterpret_cast<const uint4 *>(wrow[nt][q] + k0)) : make_uint4(0, 0, 0, 0);
-        };
-        if (kb < K) fetch(kb, cur);
-        for (; kb < K; kb += NW * GEMM_KB) {
-            // park the block in LDS
+                for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+                    for (int pl = 0; pl < 3; ++pl)
+                        xb[nb][s][pl] = *reinterpret_cast<const uint4 *>(xp[nb] + pl * a.x_plane + k0 + 32 * s);
 #pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    *reinterpret_cast<uint4 *>(wlds + (size_t)(nt * 16 + 2 * q + lrow) * GEMM_ROWB + lchunk * 16) = cur[nt][q];
-            const int kn = kb + NW * GEMM_KB;
-            if (kn < K) fetch(kn, cur);
-#pragma unroll
-            for (int s = 0; s < GEMM_KB / 32; ++s) {
-                if (kb + 32 * s >= K) break;
-                bf16x8_t A[NT];
+            for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    A[nt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(wlds + (size_t)(nt * 16 + i16) * GEMM_ROWB + (4 * s + g) * 16));
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
+                    for (int q = 0; q < NQ; ++q)
+                        wr[r][nt][q] = load_stream(reinterpret_cast<const uint4 *>(wp[r][nt][q] + k0));
+        };
+        auto multiply = [&](uint4 (&xb)[NB][NS][3], const uint4 (&wr)[R][NT][NQ]) {
 #pragma unroll
-                    for (int pl = 2; pl >= 0; --pl) {             // smallest plane first
-                        const uint4 bv = xok[nb] ? *reinterpret_cast<const uint4 *>(xp[nb] + pl * a.x_plane + kb + 32 * s)
-                                                 : make_uint4(0, 0, 0, 0);
-                        const bf16x8_t B = __builtin_bit_cast(bf16x8_t, bv);
+            for (int nb = 0; nb < NB; ++nb)
+                if (!xok[nb]) {
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            acc[nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[nt], B, acc[nt][nb], 0, 0, 0);
+                    for (int s = 0; s < NS; ++s)
+#pragma unroll
+                        for (int pl = 0; pl < 3; ++pl) xb[nb][s][pl] = make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    unsigned char *pk = park + (size_t)(r * NT + nt) * 16 * GEMM_PITCH;
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q)
+                        *reinterpret_cast<uint4 *>(pk + (size_t)(8 * q + lrow) * GEMM_PITCH + lchunk * 16) = wr[r][nt][q];
+                }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const unsigned char *pk = park + (size_t)(r * NT + nt) * 16 * GEMM_PITCH;
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(pk + (size_t)i16 * GEMM_PITCH + (4 * s + g) * 16));
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                            for (int pl = 2; pl >= 0; --pl)           // smallest plane first
+                                acc[r][nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    A, __builtin_bit_cast(bf16x8_t, xb[nb][s][pl]), acc[r][nt][nb], 0, 0, 0);
                     }
                 }
+        };
+        if constexpr (TWO_IN_FLIGHT) {
+            uint4 xb0[NB][NS][3], xb1[NB][NS][3], wr0[R][NT][NQ], wr1[R][NT][NQ];
+            int win = wave;
+            if (win < n_win) {
+                request(win, xb0, wr0);
+                while (true) {
+                    request(win + GEMM_NW, xb1, wr1);
+                    multiply(xb0, wr0);
+                    win += GEMM_NW;
+                    if (win >= n_win) break;
+                    request(win + GEMM_NW, xb0, wr0);
+                    multiply(xb1, wr1);
+                    win += GEMM_NW;
+                    if (win >= n_win) break;
+                }
+            }
+        } else {
+            uint4 xb0[NB][NS][3], wr0[R][NT][NQ];
+            for (int win = wave; win < n_win; win += GEMM_NW) {
+                request(win, xb0, wr0);
+                multiply(xb0, wr0);
             }
         }
-        // ---- sum the waves' accumulators (wave 0 ends up with the totals)
-        if (NW > 1) {
+        __syncthreads();      // every wave is done with its parking area, which the accumulators now overwrite
+        // ---- the waves' accumulators meet in LDS
+#pragma unroll
+        for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    red[((wave * NT + nt) * NB + nb) * 64 + lane] = make_float4(acc[nt][nb][0], acc[nt][nb][1], acc[nt][nb][2], acc[nt][nb][3]);
-            __syncthreads();
-            if (wave == 0) {
+                    red[(wave * SLOTS + (r * NT + nt) * NB + nb) * 64 + lane] =
+                        make_float4(acc[r][nt][nb][0], acc[r][nt][nb][1], acc[r][nt][nb][2], acc[r][nt][nb][3]);
+        __syncthreads();
+        // ---- wave p finishes pair p = (tile r, token block nb): this lane holds output columns
+        // n0 + 4 g + rr (rr = 0..3) of token nb*16 + i16
+        for (int p = wave; p < R * NB; p += GEMM_NW) {
+            const int r = p / NB, nb = p - r * NB;
+            const int tile = grp * R + r, n0 = tile * 16, m = nb * 16 + i16;
+            float4 v[NT];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
+            for (int nt = 0; nt < NT; ++nt) {
+                v[nt] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        float4 sum = red[((0 * NT + nt) * NB + nb) * 64 + lane];
-                        for (int wv = 1; wv < NW; ++wv) {
-                            const float4 v = red[((wv * NT + nt) * NB + nb) * 64 + lane];
-                            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
-                        }
-                        acc[nt][nb] = (f32x4_t){sum.x, sum.y, sum.z, sum.w};
-                    }
+                for (int w = 0; w < GEMM_NW; ++w) {
+                    const float4 u = red[(w * SLOTS + (r * NT + nt) * NB + nb) * 64 + lane];
+                    v[nt].x += u.x; v[nt].y += u.y; v[nt].z += u.z; v[nt].w += u.w;
+                }
             }
-        }
-        // ---- epilogue (wave 0): this lane holds output columns n0 + 4 g + r (r = 0..3) of token nb*16 + i16
-        if (wave == 0) {
+            if (tile >= n_tiles || m >= a.M) continue;
+            const float o0[4] = {v[0].x, v[0].y, v[0].z, v[0].w};
+            const float o1[4] = {v[NT - 1].x, v[NT - 1].y, v[NT - 1].z, v[NT - 1].w};
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int m = nb * 16 + i16;
-                if (m >= a.M) continue;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int n = n0 + 4 * g + r;
-                    if (n >= n_out) continue;
-                    const float v = acc[0][nb][r];
-                    if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = v;
-                    else if (MODE == G_OPROJ || MODE == G_DOWN) a.h_out[(size_t)m * a.ld_h + n] += v;
-                    else if (MODE == G_GATEUP) {
-                        const float up = acc[NT - 1][nb][r];
-                        split_store(v / (1.0f + expf(-v)) * up, a.act, a.act_plane, (size_t)m * a.d_ffn + n);
-                    } else {
-                        const float lg = v * lm_scale;
-                        st.push(lg, n);
-                        if (a.logits) a.logits[(size_t)m * a.N + n] = lg;
-                    }
+            for (int rr = 0; rr < 4; ++rr) {
+                const int n = n0 + 4 * g + rr;
+                if (n >= n_out) continue;
+                const float val = o0[rr];
+                if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = val;
+                else if (MODE == G_OPROJ || MODE == G_DOWN) a.h_out[(size_t)m * a.ld_h + n] += val;
+                else if (MODE == G_GATEUP) split_store(val / (1.0f + expf(-val)) * o1[rr], a.act, a.act_plane, (size_t)m * a.d_ffn + n);
+                else {
+                    const float lg = val * lm_scale;
+                    st.push(lg, n);
+                    if (a.logits) a.logits[(size_t)m * a.N + n] = lg;
                 }
             }
         }
-        if (NW > 1) __syncthreads();      // red[] is reused by the next tile
+        __syncthreads();      // red[] is reused by the next group
     }
-    if (MODE == G_LMHEAD && wave == 0) {
-        // merge the four row groups of the wave: lanes 0..15 end up with the state of token i16
+    if (MODE == G_LMHEAD) {
+        // merge the four row groups of each wave (lanes 0..15 end up with the state of token i16), then the waves
         for (int o = 32; o >= 16; o >>= 1) {
             SoftState b = shfl_xor_state(st, o);
             if ((lane & o) == 0) st.merge(b); else { b.merge(st); st = b; }
         }
-        if (g == 0 && i16 < a.M) a.parts[(size_t)i16 * a.n_parts + blockIdx.x] = to_partial(st);
+        SoftPartial *sp = reinterpret_cast<SoftPartial *>(smem);          // [GEMM_NW][16]
+        if (g == 0) sp[wave * 16 + i16] = to_partial(st);
+        __syncthreads();
+        if (wave == 0 && g == 0 && i16 < a.M) {
+            SoftState s0 = from_partial(sp[i16]);
+            for (int w = 1; w < GEMM_NW; ++w) s0.merge(from_partial(sp[w * 16 + i16]));
+            a.parts[(size_t)i16 * a.n_parts + blockIdx.x] = to_partial(s0);
+        }
     }
 }
 

@@ -224,55 +224,44 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, hipStream
     return RS_OK;
 }
 
-template <int MODE, int NB, int NW>
-rs_status launch_gemm_nw(GemmArgs &a, int blocks, hipStream_t st, const char *name) {
-    constexpr size_t lds = gemm_lds_bytes<MODE, NB, NW>();
-    if (lds > 64 * 1024) {
-        static bool raised = false;                       // per instantiation
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_gemm_rows<MODE, NB, NW>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
-            raised = true;
-        }
-    }
-    hipLaunchKernelGGL((k_gemm_rows<MODE, NB, NW>), dim3(blocks), dim3(NW * 64), lds, st, a);
+template <int MODE, int NB, int R, int NW>
+rs_status launch_gemm_r(GemmArgs &a, int blocks, hipStream_t st, const char *name) {
+    constexpr size_t lds = gemm_lds_bytes<MODE, NB, R, NW>();
+    static_assert(lds <= 64 * 1024, "two workgroups per CU must fit");
+    hipLaunchKernelGGL((k_gemm_rows<MODE, NB, R, NW>), dim3(blocks), dim3(NW * 64), lds, st, a);
     RS_LAUNCHED(name);
     return RS_OK;
 }
 
+// Launch shape.  Measured on MI355X: a CU draws at most ~30 GB/s and the weight stream needs well over
+// two thousand waves in flight (1184 waves reach 3.4 TB/s, 2368 reach 6.1), all groups resident at once.
+// So R (output tiles per workgroup; a larger R re-reads less of X) is 2 only while that leaves two
+// workgroups per CU.  More waves per workgroup (a finer split of K) were measured and bring nothing:
+// with one tile per workgroup the X pieces, not the weights, fill the CU's load path.
 template <int MODE, int NB>
-rs_status launch_gemm_nb(GemmArgs &a, int blocks, int nw, hipStream_t st, const char *name) {
-    switch (nw) {
-        case 1: return launch_gemm_nw<MODE, NB, 1>(a, blocks, st, name);
-        case 4: return launch_gemm_nw<MODE, NB, 4>(a, blocks, st, name);
-        default: return launch_gemm_nw<MODE, NB, 8>(a, blocks, st, name);
-    }
-}
-
-// n_tiles = number of 16-column output tiles
-template <int MODE>
-rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
-    const int nb = (a.M + 15) / 16;
-    const int nt = (MODE == G_GATEUP) ? 2 : 1;
-    const int kblocks = (a.K + GEMM_KB - 1) / GEMM_KB;
-    // waves per workgroup (they split K): more of them where a matrix has few 16-row tiles
-    int nw = n_tiles >= 512 ? 4 : 8;
-    while (nw > 1 && nw > kblocks) nw >>= 1;
-    if (nw == 2) nw = 1;
-    (void)nt;
-    int blocks = n_tiles < 2048 ? n_tiles : 2048;
+rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
+    const int r = (NB <= 2 && (n_tiles + 1) / 2 >= 2 * m->n_cu) ? 2 : 1;
+    int blocks = (n_tiles + r - 1) / r;
     if (MODE == G_LMHEAD) {
         if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;                 // one partial per workgroup
         a.n_parts = blocks;
     }
-    (void)m;
-    if (MODE == G_LMHEAD) return launch_gemm_nb<MODE, 1>(a, blocks, nw, st, name);
-    switch (nb) {
-        case 1: return launch_gemm_nb<MODE, 1>(a, blocks, nw, st, name);
-        case 2: return launch_gemm_nb<MODE, 2>(a, blocks, nw, st, name);
-        case 3: return launch_gemm_nb<MODE, 3>(a, blocks, nw, st, name);
-        default: return launch_gemm_nb<MODE, 4>(a, blocks, nw, st, name);
+    if constexpr (NB <= 2) {
+        if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
+    }
+    return launch_gemm_r<MODE, NB, 1, 4>(a, blocks, st, name);
+}
+
+// n_tiles = number of 16-column output tiles; 16 * NB token rows compiled in (NB = 1, 2 or 4)
+template <int MODE>
+rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
+    if (a.K % GEMM_KW) return fail(RS_EINVAL, "internal: K = %d is not a multiple of %d", a.K, GEMM_KW);
+    if constexpr (MODE == G_LMHEAD) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
+    else {
+        const int nb = (a.M + 15) / 16;
+        if (nb <= 1) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
+        if (nb == 2) return launch_gemm_nb<MODE, 2>(m, a, n_tiles, st, name);
+        return launch_gemm_nb<MODE, 4>(m, a, n_tiles, st, name);
     }
 }
 

@@ -174,6 +174,8 @@ class StitchedBatch:
         self._o_scale = self._o_pos + ns
         self._o_rec = self._o_scale + ns
         self._base = self.stage.data_ptr()
+        self.calls = 0
+        self.on_call: Optional[Callable[[int], None]] = None     # (accepted tokens so far, all sequences) after each call
         torch.cuda.synchronize()
 
     def _ptr(self, index: int) -> int:
@@ -219,7 +221,6 @@ class StitchedBatch:
         n_kv = [[0] * nb, [0] * nb]
         active = [SLM if single_model is None else single_model] * nb
         runs = [StitchRun() for _ in range(nb)]
-        self.calls = 0
         live = set(range(nb))
         while live:
             for model in (SLM, LLM):
@@ -257,4 +258,6 @@ class StitchedBatch:
                         runs[b].output.append(token)
                         if len(runs[b].output) >= n_tokens:
                             live.discard(b)
+                    if self.on_call is not None:
+                        self.on_call(sum(len(r.output) for r in runs))
         return runs
