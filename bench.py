@@ -277,8 +277,7 @@ def main() -> int:
             continue
         pair._forward(LLM, p0, p0 + n, tau)
         pair.stream.synchronize()
-        name = (f"k_gemv<GATEUP,rows<={1 if n == 1 else (2 if n == 2 else 4)}>" if n <= 4
-                else f"k_gemm_rows<GATEUP,NB={(n + 15) // 16}>")
+        name = "k_gemv<GATEUP,rows<=1>" if n == 1 else f"k_gemm_rows<GATEUP,NB={1 if n <= 16 else (2 if n <= 32 else 4)}>"
         k = kern.setdefault(name, [0, 0.0])
         k[0] += 1
         k[1] += ev.elapsed_ms(e0, e1)

@@ -542,6 +542,7 @@ struct AttnArgs {
     uint16_t *out_planes; size_t out_plane;   // optional three-plane bf16 split of the same values, or null
     const int *row_pos, *row_slot, *row_bad;
     int n_q, n_kv, max_ctx, max_seqs, layer, n_slices;
+    int n_rows;                    // token rows in the call (k_attn_partial_rows)
 };
 
 constexpr int ATT_GMAX = 8;       // query heads per kv head, at most
@@ -754,6 +755,159 @@ template <int HD>
 __global__ void __launch_bounds__(256) k_attn_partial(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     attn_partial_unit<HD>(a, smem, blockIdx.x, gridDim.x, blockIdx.y, blockIdx.z);
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_attn_partial_rows: the same partial records for a call with several token rows (catch-up spans).
+// grid (n_slices, n_kv_heads, ceil(n_rows / (4 RP))), block 256, no LDS.  The 16 columns of the
+// matrix-core tiles carry RP = 16 / G token rows at once (G = query heads per KV head): column
+// rr * G + gh is head gh of the rr-th row of the wave's row slot, so one K/V tile serves RP rows.
+// A wave owns one row slot (RP consecutive rows) and one context slice, walks the slice in passes of
+// 64 positions with an online softmax per column, and writes its columns' records itself; the four
+// waves of a workgroup hold neighbouring row slots of the SAME slice, so their K/V requests meet in
+// the CU's cache and HBM is read once per slice.  Rows of one slot that belong to different
+// sequences (different cache slots) are taken in separate turns.  Causality is per column: row r
+// attends to positions 0..pos[r].
+// ------------------------------------------------------------------------------------------------
+template <int HD>
+__global__ void __launch_bounds__(256) k_attn_partial_rows(AttnArgs a) {
+    constexpr int NDS = HD / 32, NDB = HD / 16, PS = HD + 4;
+    const int split = blockIdx.x, S = gridDim.x, kvh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    const int G = a.n_q / a.n_kv, RP = 16 / G;
+    const int rr = j / G, gh = j - rr * G;                    // this lane's column: row rr of the slot, head gh
+    int C = (a.max_ctx + S - 1) / S;
+    C = ((C + 63) / 64) * 64;
+    const int t_begin = split * C;
+    const float scale = 1.0f / sqrtf((float)HD);
+    const int slot_first = (blockIdx.z * 4 + wave) * RP, slot_end = min(slot_first + RP, a.n_rows);
+
+    for (int r0 = slot_first; r0 < slot_end;) {
+        // a turn: the rows r0 .. r1-1 of the slot that share r0's cache slot (and are valid)
+        if (a.row_bad[r0]) { ++r0; continue; }
+        const int kv_slot = min(max(a.row_slot[r0], 0), a.max_seqs - 1);
+        int r1 = r0 + 1;
+        while (r1 < slot_end && !a.row_bad[r1] && a.row_slot[r1] == a.row_slot[r0]) ++r1;
+        const int my_row = r0 + rr;                            // valid column iff rr < RP, my_row < r1
+        const bool col_ok = rr < RP && my_row < r1;
+        const int ctx_col = col_ok ? a.row_pos[my_row] + 1 : 0;
+        const int ctx_max = a.row_pos[r1 - 1] + 1;             // positions grow with the row inside a span
+        const int t_end = min(ctx_max, t_begin + C), t_end_col = min(ctx_col, t_begin + C);
+        if (t_begin < t_end) {
+            const size_t kv_base = (((size_t)a.layer * a.max_seqs + kv_slot) * a.n_kv + kvh) * (size_t)a.max_ctx * HD;
+            const uint16_t *Kp = a.kcache + kv_base, *Vp = a.vcache + kv_base;
+            bf16x8_t qB[NDS][3];
+            {
+                const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)(col_ok ? my_row : r0) * a.n_q + kvh * G + (col_ok ? gh : 0)) * HD + 8 * kg);
+#pragma unroll
+                for (int ds = 0; ds < NDS; ++ds) {
+                    const float4 x0 = qp[8 * ds], x1 = qp[8 * ds + 1];
+                    float qv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                    if (!col_ok) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) qv[e] = 0.f;
+                    }
+                    split3(qv, qB[ds]);
+                }
+            }
+            float m_run = -INFINITY, l_run = 0.f;
+            f32x4_t acc[NDB];
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) acc[db] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            for (int t0 = t_begin; t0 < t_end; t0 += 64) {
+                // K rows (A operand of the scores) and V^T rows (A operand of the output); positions clamped into the cache row
+                uint4 kk[4][NDS];
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb) {
+                    const int tok = min(t0 + 16 * tb + j, a.max_ctx - 1);
+#pragma unroll
+                    for (int ds = 0; ds < NDS; ++ds) kk[tb][ds] = *reinterpret_cast<const uint4 *>(Kp + (size_t)tok * HD + 32 * ds + 8 * kg);
+                }
+                uint2 vv[2][NDB][2];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                        for (int hf = 0; hf < 2; ++hf) {
+                            const int tv = min(t0 + 32 * ks + 16 * hf + 4 * kg, a.max_ctx - 4);
+                            vv[ks][db][hf] = *reinterpret_cast<const uint2 *>(Vp + (size_t)(16 * db + j) * a.max_ctx + tv);
+                        }
+                // scores: lane holds positions t0 + 16 tb + 4 kg + r of its column
+                f32x4_t sc[4];
+                float mx = -INFINITY;
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb) {
+                    sc[tb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ds = 0; ds < NDS; ++ds) {
+                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, kk[tb][ds]);
+#pragma unroll
+                        for (int pl = 2; pl >= 0; --pl) sc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc[tb], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float v = (t0 + 16 * tb + 4 * kg + r) < t_end_col ? sc[tb][r] * scale : -INFINITY;
+                        sc[tb][r] = v;
+                        mx = fmaxf(mx, v);
+                    }
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 16, RS_WAVE));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, RS_WAVE));
+                const float m_new = fmaxf(m_run, mx);              // may stay -inf for a column without positions here
+                const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) { acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha; }
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    float pv[8];
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float s_ = sc[2 * ks + hf][r];
+                            const float p = (s_ == -INFINITY) ? 0.f : expf(s_ - m_new);
+                            pv[4 * hf + r] = p;
+                            l_run += p;
+                        }
+                    bf16x8_t pB[3];
+                    split3(pv, pB);
+                    const int tok_lo = t0 + 32 * ks + 4 * kg, tok_hi = tok_lo + 16;
+#pragma unroll
+                    for (int db = 0; db < NDB; ++db) {
+                        // positions at or past the turn's longest context may hold anything: clear their V columns
+                        uint2 lo = vv[ks][db][0], hi = vv[ks][db][1];
+                        if (tok_lo + 3 >= t_end) {
+                            if (tok_lo + 1 >= t_end) lo.x &= 0x0000ffffu;
+                            if (tok_lo + 2 >= t_end) lo.y = 0; else if (tok_lo + 3 >= t_end) lo.y &= 0x0000ffffu;
+                            if (tok_lo >= t_end) lo.x = 0;
+                        }
+                        if (tok_hi + 3 >= t_end) {
+                            if (tok_hi + 1 >= t_end) hi.x &= 0x0000ffffu;
+                            if (tok_hi + 2 >= t_end) hi.y = 0; else if (tok_hi + 3 >= t_end) hi.y &= 0x0000ffffu;
+                            if (tok_hi >= t_end) hi.x = 0;
+                        }
+                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, make_uint4(lo.x, lo.y, hi.x, hi.y));
+#pragma unroll
+                        for (int pl = 2; pl >= 0; --pl) acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, pB[pl], acc[db], 0, 0, 0);
+                    }
+                }
+            }
+            l_run += __shfl_xor(l_run, 16, RS_WAVE);
+            l_run += __shfl_xor(l_run, 32, RS_WAVE);
+            if (col_ok && t_begin < t_end_col) {
+                float *p = a.partials + (((size_t)my_row * a.n_q + kvh * G + gh) * S + split) * PS;
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+                    *reinterpret_cast<float4 *>(p + 4 + 16 * db + 4 * kg) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+                if (kg == 0) { p[0] = m_run; p[1] = l_run; }
+            }
+        }
+        r0 = r1;
+    }
 }
 
 // merge the context slices of one (row, query head): 256 threads = (HD/4 float4 columns) x slice groups.

@@ -21,60 +21,132 @@ __device__ __forceinline__ void split_store(float v, uint16_t *p, size_t plane, 
     p[i] = a; p[plane + i] = b; p[2 * plane + i] = f32_to_bf16(r1 - bf16_to_f32(b));
 }
 
-// RMSNorm of whole rows into three bf16 planes: grid n_out, block 256.
-// src row = gather ? gather[blockIdx.x] : blockIdx.x
-__global__ void __launch_bounds__(256)
-k_rmsnorm_rows(const float *__restrict__ h, const uint16_t *__restrict__ gain, float eps, int d,
-               const int *__restrict__ gather, uint16_t *__restrict__ out, size_t plane) {
+constexpr int ROWK_THREADS = 1024;     // one workgroup per token row in the two row kernels below
+constexpr int KSPLIT_MAX = 8;
+
+// x[i] (+ the other split-K partial sums of it): all requests are issued together, unconditionally
+// (the split index is clamped, a duplicate is dropped by a select), so a row costs one round trip.
+__device__ __forceinline__ float4 sum_splits4(const float *base, size_t i, int ksplit, size_t part_stride, float4 first) {
+    float4 v[KSPLIT_MAX];
+#pragma unroll
+    for (int ks = 1; ks < KSPLIT_MAX; ++ks)
+        v[ks] = *reinterpret_cast<const float4 *>(base + (size_t)min(ks, ksplit - 1) * part_stride + i);
+#pragma unroll
+    for (int ks = 1; ks < KSPLIT_MAX; ++ks)
+        if (ks < ksplit) { first.x += v[ks].x; first.y += v[ks].y; first.z += v[ks].z; first.w += v[ks].w; }
+    return first;
+}
+
+// RMSNorm of whole rows into three bf16 planes: grid n_out, block ROWK_THREADS; d a multiple of 4, at
+// most 12 * ROWK_THREADS.  src row = gather ? gather[blockIdx.x] : blockIdx.x
+// part != null: the projection before this norm left its result as `ksplit` partial sums
+// part[ks][row][d] (split over K across workgroups); they are added to the residual row here, in a
+// fixed order, and the row is written back before it is normalised.
+__global__ void __launch_bounds__(ROWK_THREADS)
+k_rmsnorm_rows(float *__restrict__ h, const uint16_t *__restrict__ gain, float eps, int d,
+               const int *__restrict__ gather, uint16_t *__restrict__ out, size_t plane,
+               const float *__restrict__ part, int ksplit, size_t part_stride) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int src = gather ? gather[blockIdx.x] : blockIdx.x;
-    const float *hr = h + (size_t)src * d;
-    __shared__ float red_ss[4];
+    float *hr = h + (size_t)src * d;
+    __shared__ float red_ss[ROWK_THREADS / 64];
+    const int n4 = d >> 2;
+    constexpr int NV = 3;
+    float4 v[NV];
+    uint2 gv[NV];
     float ss = 0.f;
-    for (int i = tid; i < d; i += 256) { const float v = hr[i]; ss = fmaf(v, v, ss); }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int i4 = tid + k * ROWK_THREADS;
+        v[k] = make_float4(0.f, 0.f, 0.f, 0.f); gv[k] = make_uint2(0, 0);
+        if (i4 < n4) {
+            v[k] = *reinterpret_cast<const float4 *>(hr + 4 * i4);
+            gv[k] = *reinterpret_cast<const uint2 *>(gain + 4 * i4);
+            if (part) {
+                const float4 p0 = *reinterpret_cast<const float4 *>(part + (size_t)src * d + 4 * i4);
+                float4 t = sum_splits4(part, (size_t)src * d + 4 * i4, ksplit, part_stride, p0);
+                v[k].x += t.x; v[k].y += t.y; v[k].z += t.z; v[k].w += t.w;
+                *reinterpret_cast<float4 *>(hr + 4 * i4) = v[k];
+            }
+        }
+        ss = fmaf(v[k].x, v[k].x, ss); ss = fmaf(v[k].y, v[k].y, ss); ss = fmaf(v[k].z, v[k].z, ss); ss = fmaf(v[k].w, v[k].w, ss);
+    }
     ss = wave_sum(ss);
     if (lane == 0) red_ss[wave] = ss;
     __syncthreads();
-    const float inv = 1.0f / sqrtf((red_ss[0] + red_ss[1] + red_ss[2] + red_ss[3]) / (float)d + eps);
-    for (int i = tid; i < d; i += 256)
-        split_store(hr[i] * (inv * bf16_to_f32(gain[i])), out, plane, (size_t)blockIdx.x * d + i);
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < ROWK_THREADS / 64; ++w) tot += red_ss[w];
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int i4 = tid + k * ROWK_THREADS;
+        if (i4 >= n4) continue;
+        const float x[4] = {v[k].x * (inv * bf16_lo(gv[k].x)), v[k].y * (inv * bf16_hi(gv[k].x)),
+                            v[k].z * (inv * bf16_lo(gv[k].y)), v[k].w * (inv * bf16_hi(gv[k].y))};
+        // three planes, four values each: packed 8-byte stores
+        uint32_t w0[2], w1[2], w2[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const float a0 = x[2 * q], b0 = x[2 * q + 1];
+            w0[q] = pack_bf16x2(a0, b0);
+            const float ra = a0 - bf16_lo(w0[q]), rb = b0 - bf16_hi(w0[q]);
+            w1[q] = pack_bf16x2(ra, rb);
+            w2[q] = pack_bf16x2(ra - bf16_lo(w1[q]), rb - bf16_hi(w1[q]));
+        }
+        const size_t o = (size_t)blockIdx.x * d + 4 * i4;
+        *reinterpret_cast<uint2 *>(out + o) = make_uint2(w0[0], w0[1]);
+        *reinterpret_cast<uint2 *>(out + plane + o) = make_uint2(w1[0], w1[1]);
+        *reinterpret_cast<uint2 *>(out + 2 * plane + o) = make_uint2(w2[0], w2[1]);
+    }
 }
 
-// Rotary embedding of q and k, KV-cache write, for every row: grid n_rows, block 256.
+// Rotary embedding of q and k, KV-cache write, for every row: grid n_rows, block ROWK_THREADS.
 struct RopeArgs {
-    const float *qkv;              // [rows, (n_q+2 n_kv) hd] fp32
+    const float *qkv;              // [rows, (n_q+2 n_kv) hd] fp32, or `ksplit` partial sums of it, part_stride elements apart
+    int ksplit; size_t part_stride;
     float *qbuf; uint16_t *kcache, *vcache;
     const float *rope_cos, *rope_sin;
     const int *row_pos, *row_slot, *row_bad;
     int n_q, n_kv, head_dim, max_ctx, max_seqs, layer;
 };
 
-__global__ void __launch_bounds__(256) k_rope_kv_rows(RopeArgs a) {
+__global__ void __launch_bounds__(ROWK_THREADS) k_rope_kv_rows(RopeArgs a) {
     const int r = blockIdx.x, tid = threadIdx.x;
     if (a.row_bad[r]) {
-        for (int i = tid; i < a.n_q * a.head_dim; i += 256) a.qbuf[(size_t)r * a.n_q * a.head_dim + i] = 0.f;
+        for (int i = tid; i < a.n_q * a.head_dim; i += ROWK_THREADS) a.qbuf[(size_t)r * a.n_q * a.head_dim + i] = 0.f;
         return;
     }
     const int hd = a.head_dim, half = hd >> 1, pos = a.row_pos[r], slot = a.row_slot[r];
     const int n_qkv = (a.n_q + 2 * a.n_kv) * hd;
-    const float *x = a.qkv + (size_t)r * n_qkv;
+    const size_t xo = (size_t)r * n_qkv;
+    const int ks_n = a.ksplit > 1 ? a.ksplit : 1;
     const float *cs = a.rope_cos + (size_t)pos * half, *sn = a.rope_sin + (size_t)pos * half;
-    for (int p = tid; p < (a.n_q + a.n_kv) * half; p += 256) {
-        const int head = p / half, i = p - head * half;
-        const float x0 = x[head * hd + i], x1 = x[head * hd + i + half], c = cs[i], s = sn[i];
-        const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
+    // four consecutive rotary pairs per thread (head_dim / 2 is a multiple of 4)
+    for (int p4 = tid; p4 < (a.n_q + a.n_kv) * (half >> 2); p4 += ROWK_THREADS) {
+        const int head = p4 / (half >> 2), i = (p4 - head * (half >> 2)) * 4;
+        const size_t e0 = xo + head * hd + i;
+        const float4 x0 = sum_splits4(a.qkv, e0, ks_n, a.part_stride, *reinterpret_cast<const float4 *>(a.qkv + e0));
+        const float4 x1 = sum_splits4(a.qkv, e0 + half, ks_n, a.part_stride, *reinterpret_cast<const float4 *>(a.qkv + e0 + half));
+        const float4 c = *reinterpret_cast<const float4 *>(cs + i), s = *reinterpret_cast<const float4 *>(sn + i);
+        const float4 y0 = make_float4(x0.x * c.x - x1.x * s.x, x0.y * c.y - x1.y * s.y, x0.z * c.z - x1.z * s.z, x0.w * c.w - x1.w * s.w);
+        const float4 y1 = make_float4(x1.x * c.x + x0.x * s.x, x1.y * c.y + x0.y * s.y, x1.z * c.z + x0.z * s.z, x1.w * c.w + x0.w * s.w);
         if (head < a.n_q) {
             float *q = a.qbuf + ((size_t)r * a.n_q + head) * hd;
-            q[i] = y0; q[i + half] = y1;
+            *reinterpret_cast<float4 *>(q + i) = y0; *reinterpret_cast<float4 *>(q + i + half) = y1;
         } else {
             const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + pos) * hd;
-            a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
+            *reinterpret_cast<uint2 *>(a.kcache + base + i) = make_uint2(pack_bf16x2(y0.x, y0.y), pack_bf16x2(y0.z, y0.w));
+            *reinterpret_cast<uint2 *>(a.kcache + base + i + half) = make_uint2(pack_bf16x2(y1.x, y1.y), pack_bf16x2(y1.z, y1.w));
         }
     }
-    for (int p = tid; p < a.n_kv * hd; p += 256) {
-        const int vh = p / hd, e = p - vh * hd;
+    for (int p4 = tid; p4 < (a.n_kv * hd) >> 2; p4 += ROWK_THREADS) {
+        const int p = p4 * 4, vh = p / hd, e = p - vh * hd;
+        const size_t e0 = xo + (a.n_q + a.n_kv) * hd + p;
+        const float4 x = sum_splits4(a.qkv, e0, ks_n, a.part_stride, *reinterpret_cast<const float4 *>(a.qkv + e0));
         const size_t base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * (size_t)a.max_ctx * hd;
-        a.vcache[base + (size_t)e * a.max_ctx + pos] = f32_to_bf16(x[(a.n_q + a.n_kv) * hd + p]);   // V is stored [hd][position]
+        uint16_t *vp = a.vcache + base + (size_t)e * a.max_ctx + pos;          // V is stored [hd][position]
+        vp[0] = f32_to_bf16(x.x); vp[a.max_ctx] = f32_to_bf16(x.y); vp[2 * (size_t)a.max_ctx] = f32_to_bf16(x.z); vp[3 * (size_t)a.max_ctx] = f32_to_bf16(x.w);
     }
 }
 
@@ -100,6 +172,8 @@ struct GemmArgs {
     const uint16_t *W; int N, K, M;       // M = valid token rows
     const uint16_t *X; size_t x_plane;    // three [.., K] bf16 planes, x_plane elements apart
     float *out_f32; int ld_out;           // raw fp32 output [M, ld_out] (QKV)
+    int ksplit; size_t part_stride;       // > 1: K is split over workgroups too; split ks writes its partial sums to
+    float *part;                          //      part[ks * part_stride + m * N + n] (QKV, O-proj, down) and the consumer adds them up
     float *h_out; int ld_h;               // residual accumulate
     uint16_t *act; size_t act_plane; int d_ffn;   // gate/up output planes
     const float *seq_scale; SoftPartial *parts; float *logits; int n_parts;   // LM head
@@ -133,6 +207,7 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     const int n_out = (MODE == G_GATEUP) ? a.d_ffn : a.N;                 // distinct output columns
     const int n_tiles = (n_out + 15) / 16, n_groups = (n_tiles + R - 1) / R;
     const int n_win = K / GEMM_KW;
+    const int KSP = a.ksplit > 1 ? a.ksplit : 1;
 
     // token side: rows past M read row 0 and are cleared after the load
     const uint16_t *xp[NB];
@@ -146,7 +221,9 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     SoftState st; st.init();
     const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
 
-    for (int grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    for (int unit = blockIdx.x; unit < n_groups * KSP; unit += gridDim.x) {
+        const int grp = unit / KSP, ksp = unit - grp * KSP;
+        const int w_lo = (int)(((long long)n_win * ksp) / KSP), w_hi = (int)(((long long)n_win * (ksp + 1)) / KSP);
         f32x4_t acc[R][NT][NB];
         const uint16_t *wp[R][NT][NQ];
 #pragma unroll
@@ -166,7 +243,7 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
         // a duplicate is fetched but never multiplied) so that the compiler can count them and wait
         // for exactly the older set.
         auto request = [&](int win, uint4 (&xb)[NB][NS][3], uint4 (&wr)[R][NT][NQ]) {
-            const int k0 = min(win, n_win - 1) * GEMM_KW;
+            const int k0 = min(win, w_hi - 1) * GEMM_KW;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -219,23 +296,23 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
         };
         if constexpr (TWO_IN_FLIGHT) {
             uint4 xb0[NB][NS][3], xb1[NB][NS][3], wr0[R][NT][NQ], wr1[R][NT][NQ];
-            int win = wave;
-            if (win < n_win) {
+            int win = w_lo + wave;
+            if (win < w_hi) {
                 request(win, xb0, wr0);
                 while (true) {
                     request(win + GEMM_NW, xb1, wr1);
                     multiply(xb0, wr0);
                     win += GEMM_NW;
-                    if (win >= n_win) break;
+                    if (win >= w_hi) break;
                     request(win + GEMM_NW, xb0, wr0);
                     multiply(xb1, wr1);
                     win += GEMM_NW;
-                    if (win >= n_win) break;
+                    if (win >= w_hi) break;
                 }
             }
         } else {
             uint4 xb0[NB][NS][3], wr0[R][NT][NQ];
-            for (int win = wave; win < n_win; win += GEMM_NW) {
+            for (int win = w_lo + wave; win < w_hi; win += GEMM_NW) {
                 request(win, xb0, wr0);
                 multiply(xb0, wr0);
             }
@@ -274,7 +351,8 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
                 const int n = n0 + 4 * g + rr;
                 if (n >= n_out) continue;
                 const float val = o0[rr];
-                if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = val;
+                if ((MODE == G_QKV || MODE == G_OPROJ || MODE == G_DOWN) && KSP > 1) a.part[ksp * a.part_stride + (size_t)m * n_out + n] = val;
+                else if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = val;
                 else if (MODE == G_OPROJ || MODE == G_DOWN) a.h_out[(size_t)m * a.ld_h + n] += val;
                 else if (MODE == G_GATEUP) split_store(val / (1.0f + expf(-val)) * o1[rr], a.act, a.act_plane, (size_t)m * a.d_ffn + n);
                 else {

@@ -67,7 +67,7 @@ const char *check_config(const rs_config *c) {
 
 struct Layout {
     size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, h, xn, qkv_raw, qbuf,
-        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, total;
+        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, gemm_part, total;
     int attn_rows_x_splits;   // capacity of attn_part in (row, split) pairs
     int lm_parts_cap;         // partial states per sequence
 };
@@ -77,9 +77,18 @@ struct GemvPlan {
     bool gu_early;      // gate/up single-row kernel with the early weight request
 };
 
-int attn_pairs_cap(const rs_config &c) { return c.max_rows > 512 ? c.max_rows : 512; }
+// (row, context slice) pairs the attention partial buffer holds: every row of a full call may use
+// slices of one 64-position pass, up to 72 of them (short dependent chains matter more than the
+// buffer: 528 bytes per pair and query head)
+int attn_pairs_cap(const rs_config &c) {
+    int slices = (c.max_ctx + 63) / 64;
+    if (slices > 72) slices = 72;
+    const int want = c.max_rows * slices;
+    return want > 512 ? want : 512;
+}
 
 constexpr int LM_PARTS_CAP = 4096;
+constexpr int GEMM_KSPLIT_MAX = rs::KSPLIT_MAX;     // workgroup-level K splits of the multi-row projections, at most
 
 Layout make_layout(const rs_config &c) {
     Layout L{};
@@ -109,6 +118,7 @@ Layout make_layout(const rs_config &c) {
     L.lm_pl = take((size_t)3 * c.max_seqs * c.d_model * 2);
     L.lm_parts_cap = LM_PARTS_CAP;
     L.lm_parts = take((size_t)c.max_seqs * L.lm_parts_cap * sizeof(rs::SoftPartial));
+    L.gemm_part = take((size_t)GEMM_KSPLIT_MAX * c.max_rows * (qkv > (size_t)c.d_model ? qkv : (size_t)c.d_model) * 4);
     L.sync = take(sizeof(rs::SyncState));
     L.layer_ptrs = take((size_t)c.n_layers * sizeof(rs::LayerPtrs));
     L.total = o;
@@ -177,16 +187,14 @@ rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *na
     return RS_OK;
 }
 
-// mp = 1, 2, 4 or 8 token rows compiled in (a.m_rows <= mp); PRE: early weight request of the single-row kernel
+// Single-row launches.  (gemv_phase can be compiled for 2, 4 or 8 token rows as well; on this chip the
+// matrix-core path overtakes those variants already at two rows, so only the one-row form is built.)
+// PRE: early weight request.
 template <int MODE, int RT, int KS, int UNR, int PRE = 0>
 rs_status launch_gemv(const rs_model *m, GemvArgs &a, int mp, int blocks, hipStream_t st, const char *name) {
     (void)m;
-    switch (mp) {
-        case 1: return launch_gemv_mp<MODE, RT, KS, UNR, 1, PRE>(a, blocks, st, name);
-        case 2: return launch_gemv_mp<MODE, RT, KS, UNR, 2>(a, blocks, st, name);
-        case 4: return launch_gemv_mp<MODE, RT, KS, UNR, 4>(a, blocks, st, name);
-        default: return launch_gemv_mp<MODE, RT, KS, UNR, 8>(a, blocks, st, name);
-    }
+    if (mp != 1) return fail(RS_EINVAL, "internal: %s launched for %d rows", name, mp);
+    return launch_gemv_mp<MODE, RT, KS, UNR, 1, PRE>(a, blocks, st, name);
 }
 
 // Launch shapes from sweeps on MI355X: about three workgroups per CU for matrices under ~128 MB,
@@ -215,10 +223,18 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
 }
 
 template <int HD>
-rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, hipStream_t st) {
+rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool spans, hipStream_t st) {
     a.n_slices = n_splits;
-    hipLaunchKernelGGL((k_attn_partial<HD>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(), st, a);
-    RS_LAUNCHED("attn_partial");
+    a.n_rows = n_rows;
+    if (spans) {
+        // several rows per sequence: rows share K/V tiles through the columns of the matrix-core tiles
+        const int rp = 16 / (a.n_q / n_kv);
+        hipLaunchKernelGGL((k_attn_partial_rows<HD>), dim3(n_splits, n_kv, (n_rows + 4 * rp - 1) / (4 * rp)), dim3(256), 0, st, a);
+        RS_LAUNCHED("attn_partial_rows");
+    } else {
+        hipLaunchKernelGGL((k_attn_partial<HD>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(), st, a);
+        RS_LAUNCHED("attn_partial");
+    }
     hipLaunchKernelGGL((k_attn_combine<HD>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
     RS_LAUNCHED("attn_combine");
     return RS_OK;
@@ -234,22 +250,43 @@ rs_status launch_gemm_r(GemmArgs &a, int blocks, hipStream_t st, const char *nam
 }
 
 // Launch shape.  Measured on MI355X: a CU draws at most ~30 GB/s and the weight stream needs well over
-// two thousand waves in flight (1184 waves reach 3.4 TB/s, 2368 reach 6.1), all groups resident at once.
-// So R (output tiles per workgroup; a larger R re-reads less of X) is 2 only while that leaves two
-// workgroups per CU.  More waves per workgroup (a finer split of K) were measured and bring nothing:
-// with one tile per workgroup the X pieces, not the weights, fill the CU's load path.
+// two thousand waves in flight (1184 waves reach 3.4 TB/s, 2368 reach 6.1), all groups resident at once;
+// and with one tile per workgroup the X pieces (three planes), not the weights, fill the CU's load path.
+// So a workgroup takes R >= 2 tiles (one X piece serves them all), and where a matrix then has too few
+// groups (QKV, O-proj, down: few output rows) K is split over workgroups as well: split ks leaves partial
+// sums in a buffer that the next kernel (rotary / RMSNorm) adds up in a fixed order.  Gate/up needs whole
+// sums for its activation and has tiles to spare.
 template <int MODE, int NB>
 rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
-    const int r = (NB <= 2 && (n_tiles + 1) / 2 >= 2 * m->n_cu) ? 2 : 1;
-    int blocks = (n_tiles + r - 1) / r;
-    if (MODE == G_LMHEAD) {
-        if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;                 // one partial per workgroup
-        a.n_parts = blocks;
-    }
-    if constexpr (NB <= 2) {
+    constexpr bool SPLITS = MODE == G_QKV || MODE == G_OPROJ || MODE == G_DOWN;
+    const int target = 2 * m->n_cu, n_win = a.K / GEMM_KW;
+    a.ksplit = 1; a.part = nullptr; a.part_stride = 0;
+    if constexpr (SPLITS) {
+        constexpr int R = (NB == 1) ? 4 : 2;
+        const int r = (NB == 1 && n_win < 128) ? 2 : R;             // short rows: smaller groups rather than thin K slices
+        const int groups = (n_tiles + r - 1) / r;
+        int ks = 1;
+        while (ks < GEMM_KSPLIT_MAX && groups * ks < target && n_win / (2 * ks) >= 4) ks *= 2;
+        if (ks > 1) {
+            a.ksplit = ks; a.part = m->at<float>(m->lay.gemm_part);
+            a.part_stride = (size_t)m->cfg.max_rows * (size_t)a.N;
+        }
+        const int blocks = groups * ks;
         if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
+        if constexpr (NB == 1) return launch_gemm_r<MODE, NB, 4, 4>(a, blocks, st, name);
+        else return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
+    } else {
+        const int r = (NB <= 2 && (n_tiles + 1) / 2 >= target) ? 2 : 1;
+        int blocks = (n_tiles + r - 1) / r;
+        if (MODE == G_LMHEAD) {
+            if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;             // one partial per workgroup
+            a.n_parts = blocks;
+        }
+        if constexpr (NB <= 2) {
+            if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
+        }
+        return launch_gemm_r<MODE, NB, 1, 4>(a, blocks, st, name);
     }
-    return launch_gemm_r<MODE, NB, 1, 4>(a, blocks, st, name);
 }
 
 // n_tiles = number of 16-column output tiles; 16 * NB token rows compiled in (NB = 1, 2 or 4)
@@ -360,15 +397,16 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
     hipLaunchKernelGGL(k_prepare, dim3(n_rows), dim3(256), 0, st, pa);
     RS_LAUNCHED("prepare");
 
-    // attention launch shape
+    // attention launch shape; calls in which some sequence brings several rows share K/V tiles between rows
     const int n_splits = attn_splits(c, L, n_rows);
+    const bool spans = n_rows > n_seqs;
 
-    // up to 4 rows go through the FMA GEMV kernels (weights streamed once, x rows in LDS: measured
-    // faster than the matrix-core path up to there); more rows, or rows that do not fit the LDS next
-    // to each other, go through the MFMA kernels
-    const int mp = n_rows <= 1 ? 1 : (n_rows <= 2 ? 2 : (n_rows <= 4 ? 4 : 8));
-    const bool single = n_rows <= 4 && (size_t)c.d_model * mp <= (size_t)GEMV_LDS_FLOATS && (size_t)qdim * mp <= (size_t)GEMV_LDS_FLOATS;
+    // a single row goes through the FMA GEMV kernels; two rows or more go through the MFMA kernels
+    // (measured: 3.5 ms against 3.8 ms for a two-row call of the 7B shape)
+    const int mp = 1;
+    const bool single = n_rows == 1 && (size_t)c.d_model <= (size_t)GEMV_LDS_FLOATS && (size_t)qdim <= (size_t)GEMV_LDS_FLOATS;
     rs_status rc;
+    float *pend_part = nullptr; int pend_ks = 0; size_t pend_stride = 0;   // multi-row path: partial sums of the last down projection
     // optional event pair around one chosen kernel (rs_set_phase_timer)
     auto tic = [&](int phase, int layer) {
         if (m->timer_phase == phase && (phase == RS_PHASE_LMHEAD || m->timer_layer == layer)) (void)hipEventRecord(m->timer_start, st);
@@ -406,9 +444,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             // attention
             tic(RS_PHASE_ATTN, l);
             switch (hd) {
-                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
-                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
-                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
+                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
             }
             toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
@@ -446,27 +484,30 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             const size_t xn_plane = (size_t)c.max_rows * c.d_model;
             GemmArgs g{};
             g.M = n_rows; g.d_ffn = c.d_ffn;
-            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, (const float *)h, m->attn_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane);
+            // the down projection of the layer before may have left its result as partial sums (pend_*)
+            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->attn_norm[l], c.rms_eps,
+                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)pend_part, pend_ks, pend_stride);
             RS_LAUNCHED("rmsnorm_rows");
+            pend_part = nullptr; pend_ks = 0; pend_stride = 0;
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
             g.out_f32 = m->at<float>(L.qkv_raw); g.ld_out = qkv_rows;
             tic(RS_PHASE_QKV, l);
             if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv"))) return rc;
             toc(RS_PHASE_QKV, l);
             RopeArgs ra{};
-            ra.qkv = m->at<float>(L.qkv_raw); ra.qbuf = m->at<float>(L.qbuf); ra.kcache = m->kv_k; ra.vcache = m->kv_v;
+            ra.qkv = g.ksplit > 1 ? g.part : m->at<float>(L.qkv_raw); ra.ksplit = g.ksplit; ra.part_stride = g.part_stride;
+            ra.qbuf = m->at<float>(L.qbuf); ra.kcache = m->kv_k; ra.vcache = m->kv_v;
             ra.rope_cos = m->at<float>(L.rope_cos); ra.rope_sin = m->at<float>(L.rope_sin);
             ra.row_pos = row_pos; ra.row_slot = row_slot; ra.row_bad = row_bad;
             ra.n_q = c.n_q_heads; ra.n_kv = c.n_kv_heads; ra.head_dim = hd; ra.max_ctx = c.max_ctx;
             ra.max_seqs = c.max_seqs; ra.layer = l;
-            hipLaunchKernelGGL(k_rope_kv_rows, dim3(n_rows), dim3(256), 0, st, ra);
+            hipLaunchKernelGGL(k_rope_kv_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, ra);
             RS_LAUNCHED("rope_kv_rows");
             tic(RS_PHASE_ATTN, l);
             switch (hd) {
-                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
-                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
-                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, st); break;
+                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
             }
             toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
@@ -476,8 +517,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             tic(RS_PHASE_OPROJ, l);
             if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj"))) return rc;
             toc(RS_PHASE_OPROJ, l);
-            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(256), 0, st, (const float *)h, m->mlp_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane);
+            hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->mlp_norm[l], c.rms_eps,
+                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)(g.ksplit > 1 ? g.part : nullptr),
+                               g.ksplit, g.part_stride);
             RS_LAUNCHED("rmsnorm_rows");
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
             g.act = m->at<uint16_t>(L.act_pl); g.act_plane = (size_t)c.max_rows * c.d_ffn;
@@ -489,6 +531,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             tic(RS_PHASE_DOWN, l);
             if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down"))) return rc;
             toc(RS_PHASE_DOWN, l);
+            if (g.ksplit > 1) { pend_part = g.part; pend_ks = g.ksplit; pend_stride = g.part_stride; }
         }
     }
 
@@ -501,15 +544,15 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
         n_parts = m->plan.lm_blocks; g.n_parts = n_parts;
-        const int mp_lm = n_seqs <= 1 ? 1 : (n_seqs <= 2 ? 2 : (n_seqs <= 4 ? 4 : 8));
+        const int mp_lm = 1;
         tic(RS_PHASE_LMHEAD, 0);
         if ((rc = launch_gemv<G_LMHEAD, 8, 1, 2>(m, g, mp_lm, m->plan.lm_blocks, st, "gemv_lmhead"))) return rc;
         toc(RS_PHASE_LMHEAD, 0);
     } else {
         uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
         const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seqs), dim3(256), 0, st, (const float *)h, m->final_norm, c.rms_eps,
-                           c.d_model, (const int *)m->at<int>(L.out_row), lm_pl, lm_plane);
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seqs), dim3(ROWK_THREADS), 0, st, h, m->final_norm, c.rms_eps,
+                           c.d_model, (const int *)m->at<int>(L.out_row), lm_pl, lm_plane, (const float *)pend_part, pend_ks, pend_stride);
         RS_LAUNCHED("rmsnorm_rows");
         GemmArgs g{};
         g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane;
