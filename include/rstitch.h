@@ -199,15 +199,6 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
                    rs_route_out *d_out, void *d_scratch, size_t scratch_bytes,
                    void *stream);
 
-/* Measurement aid (not part of the method): while armed, every forward call on
- * this model records `start_event` immediately before and `stop_event`
- * immediately after the launch of ONE kernel on the call's stream: the kernel of
- * phase `phase` (RS_PHASE_*) in layer `layer` (layer is ignored for
- * RS_PHASE_LMHEAD).  Both are caller-owned hipEvent_t handles passed as void*;
- * the caller reads them with hipEventElapsedTime after synchronising.
- * phase < 0 disarms.  While armed, single-row steps run as one kernel per phase
- * instead of the single-kernel step, so that there is a kernel to bracket.
- * Errors: RS_EINVAL (null model/event, layer out of range). */
 /* Test aid: the single-kernel decode step separates its phases with grid-wide
  * waits that give up after `polls` polls (default 2^22, about a second) instead
  * of hanging; a tiny value forces that error path from the host.  0 restores the
@@ -215,6 +206,15 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
  * every record) until it is created again. */
 rs_status rs_set_spin_limit(rs_model *model, uint32_t polls);
 
+/* Measurement aid (not part of the method): while armed, every forward call on
+ * this model records `start_event` immediately before and `stop_event`
+ * immediately after the launch of ONE kernel on the call's stream: the kernel of
+ * phase `phase` (RS_PHASE_*) in layer `layer` (layer is ignored for
+ * RS_PHASE_LMHEAD).  Both are caller-owned hipEvent_t handles passed as void*;
+ * the caller reads them with hipEventElapsedTime after synchronising.
+ * phase < 0 disarms.  While armed, calls run as plain launches (no launch-graph
+ * replay, no single-kernel step), so that there is a kernel to bracket.
+ * Errors: RS_EINVAL (null model/event, layer out of range). */
 #define RS_PHASE_QKV     0
 #define RS_PHASE_OPROJ   1
 #define RS_PHASE_GATEUP  2
