@@ -330,6 +330,38 @@ def main() -> int:
                           "roofline_ms": round(bytes_step / HBM_PEAK * 1e3, 4),
                           "roofline_frac": round(bytes_step / HBM_PEAK / (ms * 1e-3), 4)}
 
+    # ---- what the router costs: the fused LM head + softmax-state kernel of each model (event pair around that
+    # kernel in a plain-launch decode step) beside the standalone router of the same rows (rs_route on logits in
+    # HBM: two small kernels after an LM head that would have to write V floats and read them back).  The paper
+    # reports 0.028 ms per token for its separate entropy evaluation.
+    router = {}
+    vocab = wl.slm.vocab
+    logits = torch.randn(1, vocab, device=dev, dtype=torch.float32)
+    r_out = P.binding.new_route_out(1, device=dev)
+    r_scratch = torch.empty(P.binding.rs_route_scratch_bytes(1, vocab), dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        P.binding.rs_route(logits, 1, vocab, None, tau, 0, r_out, r_scratch, sh)
+    pair.stream.synchronize()
+    ev.record(a, sh)
+    for _ in range(20):
+        P.binding.rs_route(logits, 1, vocab, None, tau, 0, r_out, r_scratch, sh)
+    ev.record(b, sh)
+    pair.stream.synchronize()
+    router["standalone_rs_route_us"] = round(ev.elapsed_ms(a, b) / 20 * 1e3, 2)
+    for tag, mid, mdl in (("slm", SLM, slm), ("llm", LLM, llm)):
+        P.rs_set_phase_timer(mdl.handle, P.binding.PHASE_LMHEAD, 0, e0, e1)
+        tot = 0.0
+        for i in range(8):
+            pair._forward(mid, max_ctx - 16 + i, max_ctx - 15 + i, tau)
+            pair.stream.synchronize()
+            tot += ev.elapsed_ms(e0, e1)
+        P.rs_set_phase_timer(mdl.handle, -1)
+        shape = wl.slm if mid == SLM else wl.llm
+        lm_bytes = shape.vocab * shape.d_model * 2
+        router[f"{tag}_lm_head_with_fused_router_us"] = round(tot / 8 * 1e3, 2)
+        router[f"{tag}_lm_head_gbps"] = round(lm_bytes / (tot / 8 * 1e-3) / 1e9, 1)
+    router["paper_separate_entropy_us"] = 28.0
+
     # ---- CPU oracle on a bounded sample
     cpu = None
     if not args.no_cpu_baseline:
@@ -368,6 +400,7 @@ def main() -> int:
                      "llm_span_mean": round(sum(spans) / max(len(spans), 1), 2), "llm_span_max": max(spans) if spans else 0,
                      "roofline_ms_per_token": round(ideal_s / args.steps * 1e3, 4),
                      "roofline_frac": round(ideal_s / elapsed, 4)},
+        "router": router,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

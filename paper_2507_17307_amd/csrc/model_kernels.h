@@ -315,9 +315,9 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
     int parity = 0;
 
     // accumulate chunks [c_begin, c_end) of the tile; the LDS segment starts at chunk seg_c0
-    auto accumulate = [&](const uint4 *const (&wp)[RT], int seg_c0, int c_begin, int c_end, float (&acc)[RT][MP]) {
+    auto accumulate = [&](const uint4 *const (&wp)[RT], int seg_c0, int c_begin, int c_end, int c_step, float (&acc)[RT][MP]) {
 #pragma unroll UNR
-        for (int c = c_begin; c < c_end; c += cstride) {
+        for (int c = c_begin; c < c_end; c += c_step) {
             uint4 wv[RT];
 #pragma unroll
             for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
@@ -395,14 +395,20 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 }
                 cb = c0 + PRE * cstride;
             }
-            accumulate(wp, 0, cb, K >> 3, acc);
+#ifdef RS_KS_CONTIG
+            if (KS == 4 && PRE == 0) {
+                const int chunks = K >> 3, Q = (chunks + 3) >> 2;
+                accumulate(wp, 0, wave * Q + lane, min((wave + 1) * Q, chunks), 64, acc);
+            } else
+#endif
+            accumulate(wp, 0, cb, K >> 3, cstride, acc);
         } else {
             for (int k0 = 0; k0 < K; k0 += seg) {              // KS == 4 only: the tile loop is workgroup-uniform
                 const int len = min(seg, K - k0);
                 __syncthreads();
                 stage(k0, len);
                 __syncthreads();
-                accumulate(wp, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, acc);
+                accumulate(wp, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, cstride, acc);
             }
         }
         if (t == unit0) GEMV_T(3);

@@ -42,9 +42,7 @@ __device__ __forceinline__ bool grid_barrier(SyncState *s, unsigned long long ta
     __shared__ int ok_sh;
     __syncthreads();
     if (threadIdx.x == 0) {
-#if !defined(RS_EXP_BAR) || RS_EXP_BAR <= 1
         __threadfence();
-#endif
         atomicAdd(&s->arrive, 1ULL);
         unsigned int spins = 0;
         int ok = 1;
@@ -58,9 +56,7 @@ __device__ __forceinline__ bool grid_barrier(SyncState *s, unsigned long long ta
             }
         }
         if (!ok) __hip_atomic_store(&s->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#if !defined(RS_EXP_BAR) || RS_EXP_BAR == 0
         __threadfence();
-#endif
         ok_sh = ok;
     }
     __syncthreads();
