@@ -294,8 +294,13 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 const int n4 = len >> 2;
                 for (int i0 = tid; i0 < n4; i0 += 256 * SB) {
                     float4 v[SB];
+#ifdef RS_STAGE_SKIP
+#pragma unroll
+                    for (int j = 0; j < SB; ++j) v[j] = x4[min(i0 & 255, n4 - 1)];      // timing experiment only: 1 KB of x per workgroup
+#else
 #pragma unroll
                     for (int j = 0; j < SB; ++j) v[j] = x4[min(i0 + j * 256, n4 - 1)];
+#endif
 #pragma unroll
                     for (int j = 0; j < SB; ++j) {
                         const int i = i0 + j * 256;
