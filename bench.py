@@ -168,7 +168,7 @@ def bench_batched(args, wl) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1024, help="accepted tokens in the timed region")
+    ap.add_argument("--steps", type=int, default=4032, help="accepted tokens in the timed region")
     ap.add_argument("--warmup", type=int, default=64, help="accepted tokens before the timed region")
     ap.add_argument("--workload", default="cfg3_s15_m7")
     ap.add_argument("--no-cpu-baseline", action="store_true")
