@@ -172,6 +172,8 @@ struct GemmArgs {
     const uint16_t *W; int N, K, M;       // M = valid token rows
     const uint16_t *X; size_t x_plane;    // three [.., K] bf16 planes, x_plane elements apart
     float *out_f32; int ld_out;           // raw fp32 output [M, ld_out] (QKV)
+    int yblocks;                          // > 1: the token rows are cut into yblocks blocks of 16*NB rows, each taken by its own
+                                          //      workgroups (same weights; ids arranged so that they meet in one XCD's L2)
     int ksplit; size_t part_stride;       // > 1: K is split over workgroups too; split ks writes its partial sums to
     float *part;                          //      part[ks * part_stride + m * N + n] (QKV, O-proj, down) and the consumer adds them up
     float *h_out; int ld_h;               // residual accumulate
@@ -209,19 +211,34 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     const int n_win = K / GEMM_KW;
     const int KSP = a.ksplit > 1 ? a.ksplit : 1;
 
+    // Workgroup id -> (work unit, token-row block).  The hardware deals consecutive workgroup ids round
+    // robin over the 8 XCDs; the row blocks of one unit stream the same weights, so they get ids that are
+    // congruent modulo 8: one of them fetches a weight line from HBM, the others find it in that XCD's L2.
+    const int Y = a.yblocks > 1 ? a.yblocks : 1;
+    const int n_units = n_groups * KSP;
+    int unit_first, unit_step, yb;
+    if (Y == 1) { unit_first = blockIdx.x; unit_step = gridDim.x; yb = 0; }
+    else {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        yb = slot % Y;
+        unit_first = (slot / Y) * 8 + xcd;
+        unit_step = n_units + 8;                                          // one unit per workgroup
+    }
+    const int m_base = yb * 16 * NB;
+
     // token side: rows past M read row 0 and are cleared after the load
     const uint16_t *xp[NB];
     bool xok[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const int m = nb * 16 + i16;
+        const int m = m_base + nb * 16 + i16;
         xok[nb] = m < a.M;
         xp[nb] = a.X + (size_t)(xok[nb] ? m : 0) * K + g * 8;
     }
     SoftState st; st.init();
     const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
 
-    for (int unit = blockIdx.x; unit < n_groups * KSP; unit += gridDim.x) {
+    for (int unit = unit_first; unit < n_units; unit += unit_step) {
         const int grp = unit / KSP, ksp = unit - grp * KSP;
         const int w_lo = (int)(((long long)n_win * ksp) / KSP), w_hi = (int)(((long long)n_win * (ksp + 1)) / KSP);
         f32x4_t acc[R][NT][NB];
@@ -332,7 +349,7 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
         // n0 + 4 g + rr (rr = 0..3) of token nb*16 + i16
         for (int p = wave; p < R * NB; p += GEMM_NW) {
             const int r = p / NB, nb = p - r * NB;
-            const int tile = grp * R + r, n0 = tile * 16, m = nb * 16 + i16;
+            const int tile = grp * R + r, n0 = tile * 16, m = m_base + nb * 16 + i16;
             float4 v[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {

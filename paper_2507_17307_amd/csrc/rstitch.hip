@@ -256,6 +256,10 @@ rs_status launch_gemm_r(GemmArgs &a, int blocks, hipStream_t st, const char *nam
 // groups (QKV, O-proj, down: few output rows) K is split over workgroups as well: split ks leaves partial
 // sums in a buffer that the next kernel (rotary / RMSNorm) adds up in a fixed order.  Gate/up needs whole
 // sums for its activation and has tiles to spare.
+// workgroups for `units` work units and `yblocks` token-row blocks: with several row blocks the kernel
+// decodes ids in groups of 8 (one per XCD), so the unit count is padded to a multiple of 8
+int gemm_grid(int units, int yblocks) { return yblocks > 1 ? ((units + 7) / 8) * 8 * yblocks : units; }
+
 template <int MODE, int NB>
 rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     constexpr bool SPLITS = MODE == G_QKV || MODE == G_OPROJ || MODE == G_DOWN;
@@ -271,7 +275,7 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
             a.ksplit = ks; a.part = m->at<float>(m->lay.gemm_part);
             a.part_stride = (size_t)m->cfg.max_rows * (size_t)a.N;
         }
-        const int blocks = groups * ks;
+        const int blocks = gemm_grid(groups * ks, a.yblocks);
         if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
         if constexpr (NB == 1) return launch_gemm_r<MODE, NB, 4, 4>(a, blocks, st, name);
         else return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
@@ -282,6 +286,7 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
             if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;             // one partial per workgroup
             a.n_parts = blocks;
         }
+        blocks = gemm_grid(blocks, a.yblocks);
         if constexpr (NB <= 2) {
             if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
         }
@@ -293,12 +298,15 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
 template <int MODE>
 rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     if (a.K % GEMM_KW) return fail(RS_EINVAL, "internal: K = %d is not a multiple of %d", a.K, GEMM_KW);
+    a.yblocks = 1;
     if constexpr (MODE == G_LMHEAD) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
     else {
-        const int nb = (a.M + 15) / 16;
-        if (nb <= 1) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
-        if (nb == 2) return launch_gemm_nb<MODE, 2>(m, a, n_tiles, st, name);
-        return launch_gemm_nb<MODE, 4>(m, a, n_tiles, st, name);
+        // up to 16 rows: one 16-row block; more: blocks of 32 rows (two 16-row blocks per workgroup), each
+        // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.8 ms, 64 rows 10.6 ms this
+        // way, against 7.1 / 11.8 ms with 16-row blocks and 9.1 / 12.9 ms with 64-row blocks.
+        if (a.M <= 16) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
+        a.yblocks = (a.M + 31) / 32;
+        return launch_gemm_nb<MODE, 2>(m, a, n_tiles, st, name);
     }
 }
 
