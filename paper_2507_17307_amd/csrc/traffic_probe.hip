@@ -5,7 +5,10 @@
 // counter reports for that copy.  No framework is loaded, so counter collection
 // sees only these dispatches.
 //
-//   traffic_probe <s15|m7> [layers=2] [steps=6] [position=4575]
+//   traffic_probe <s15|m7> [layers=2] [steps=6] [position=4575] [span=1]
+//
+// span > 1 runs catch-up calls of that many token rows ending at `position` instead of decode steps
+// (the matrix-core path).
 //
 // Weights are a fixed byte pattern (their values do not matter for traffic), the
 // KV cache is zero-filled up to `position`.
@@ -29,13 +32,14 @@ int main(int argc, char **argv) {
     const int layers = argc > 2 ? atoi(argv[2]) : 2;
     const int steps = argc > 3 ? atoi(argv[3]) : 6;
     const int position = argc > 4 ? atoi(argv[4]) : 4575;
+    const int span = argc > 5 ? atoi(argv[5]) : 1;
     rs_config c{};
     if (!strcmp(shape, "s15")) { c.d_model = 1536; c.n_q_heads = 12; c.n_kv_heads = 2; c.d_ffn = 8960; }
     else if (!strcmp(shape, "m7")) { c.d_model = 3584; c.n_q_heads = 28; c.n_kv_heads = 4; c.d_ffn = 18944; }
     else { fprintf(stderr, "shape must be s15 or m7\n"); return 2; }
     c.n_layers = layers; c.head_dim = 128; c.vocab = 152064; c.tied_lm_head = 1;
     c.max_ctx = 4608; c.max_seqs = 1; c.max_rows = 64; c.rms_eps = 1e-6f; c.rope_theta = 1e6f;
-    if (layers < 1 || layers > 64 || steps < 1 || position < 0 || position >= c.max_ctx) { fprintf(stderr, "bad arguments\n"); return 2; }
+    if (layers < 1 || layers > 64 || steps < 1 || position < 0 || position >= c.max_ctx || span < 1 || span > 64 || span > position + 1) { fprintf(stderr, "bad arguments\n"); return 2; }
     setenv("RSTITCH_GRAPHS", "0", 1);                      // plain launches: one dispatch per kernel for the profiler
 
     const size_t qkv_rows = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, qdim = (size_t)c.n_q_heads * c.head_dim;
@@ -70,11 +74,13 @@ int main(int argc, char **argv) {
     rs_model *m = nullptr;
     if (rs_create_model(&c, &w, kv_k, kv_v, ws, wsb, &m) != RS_OK) { fprintf(stderr, "rs_create_model: %s\n", rs_last_error()); return 1; }
 
-    int32_t h_ctl[3] = {0, 17, position};                 // slot, token, position
+    // control block: slot, first position of the span, span offsets {0, span}, then the span's tokens
+    std::vector<int32_t> h_ctl(4 + 64, 17);
+    h_ctl[0] = 0; h_ctl[1] = position - span + 1; h_ctl[2] = 0; h_ctl[3] = span;
     float h_scale = 1.0f;
     int32_t *d_ctl; float *d_scale; rs_route_out *d_out;
-    CK(hipMalloc(&d_ctl, sizeof h_ctl)); CK(hipMalloc(&d_scale, 4)); CK(hipMalloc(&d_out, sizeof(rs_route_out)));
-    CK(hipMemcpy(d_ctl, h_ctl, sizeof h_ctl, hipMemcpyHostToDevice)); CK(hipMemcpy(d_scale, &h_scale, 4, hipMemcpyHostToDevice));
+    CK(hipMalloc(&d_ctl, h_ctl.size() * 4)); CK(hipMalloc(&d_scale, 4)); CK(hipMalloc(&d_out, sizeof(rs_route_out)));
+    CK(hipMemcpy(d_ctl, h_ctl.data(), h_ctl.size() * 4, hipMemcpyHostToDevice)); CK(hipMemcpy(d_scale, &h_scale, 4, hipMemcpyHostToDevice));
     hipStream_t st; CK(hipStreamCreate(&st));
 
     // the known-size dispatch: 2^28 bytes read, 2^28 bytes written, three times
@@ -86,15 +92,16 @@ int main(int argc, char **argv) {
     CK(hipStreamSynchronize(st));
 
     for (int i = 0; i < steps; ++i) {
-        if (rs_decode_step(m, 1, d_ctl, d_ctl + 1, d_ctl + 2, d_scale, 0.5f, RS_LLM, d_out, nullptr, st) != RS_OK) {
-            fprintf(stderr, "rs_decode_step: %s\n", rs_last_error()); return 1;
-        }
+        const rs_status rc = span == 1
+            ? rs_decode_step(m, 1, d_ctl, d_ctl + 4, d_ctl + 1, d_scale, 0.5f, RS_LLM, d_out, nullptr, st)
+            : rs_catchup_prefill(m, 1, span, d_ctl, d_ctl + 4, d_ctl + 2, d_ctl + 1, d_scale, 0.5f, RS_LLM, d_out, nullptr, st);
+        if (rc != RS_OK) { fprintf(stderr, "forward call: %s\n", rs_last_error()); return 1; }
     }
     CK(hipStreamSynchronize(st));
     rs_route_out r;
     CK(hipMemcpy(&r, d_out, sizeof r, hipMemcpyDeviceToHost));
-    printf("traffic_probe %s layers=%d steps=%d position=%d: token %d flags %u h_norm %.6f; copy kernel k_probe_copy moved %zu bytes each way\n",
-           shape, layers, steps, position, r.token, r.flags, r.h_norm, copy_bytes);
+    printf("traffic_probe %s layers=%d steps=%d position=%d span=%d: token %d flags %u h_norm %.6f; copy kernel k_probe_copy moved %zu bytes each way\n",
+           shape, layers, steps, position, span, r.token, r.flags, r.h_norm, copy_bytes);
     rs_destroy_model(m);
     return 0;
 }

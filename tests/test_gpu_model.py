@@ -306,3 +306,17 @@ def test_full_1p5b_model_self_consistency_at_bench_configuration(monkeypatch):
     assert r_c[0].h_nats <= ln_v + 1e-3
     ka, kb = graphs.kv_view("k")[:, 0, :, end - 9:end].float(), plain.kv_view("k")[:, 0, :, end - 9:end].float()
     assert float((ka - kb).abs().max()) <= 2 ** -7 * float(kb.abs().max())
+
+
+def test_counter_run_driver_runs_decode_and_catchup_calls():
+    """The stand-alone driver used for hardware-counter runs (no framework in the process) links against the
+    library, builds a two-layer 1.5B-shape model and finishes decode steps and a 5-row catch-up with a sane record."""
+    import os
+    import subprocess
+    import paper_2507_17307_amd as P
+    probe = os.path.join(os.path.dirname(os.path.abspath(P.__file__)), "traffic_probe")
+    assert os.path.exists(probe), "build the package first (paper_2507_17307_amd.build)"
+    for extra in ([], ["5"]):
+        r = subprocess.run([probe, "s15", "2", "2", "300"] + extra, capture_output=True, text=True, timeout=120)
+        assert r.returncode == 0, r.stderr
+        assert "traffic_probe s15 layers=2 steps=2 position=300" in r.stdout and "h_norm" in r.stdout
