@@ -1,6 +1,7 @@
-// Decode-step kernels for one token row (batch 1): row table + embedding,
-// bandwidth-bound GEMV phases with fused prologues/epilogues, split-K GQA
-// decode attention with an in-kernel combine.  Wave64, 256-thread workgroups.
+// Decode-step kernels: row table + embedding, bandwidth-bound GEMV phases with
+// fused prologues/epilogues for one token row, split-context GQA decode
+// attention on the matrix cores (a partial kernel for one row, one for spans of
+// rows, and the merge of the slices).  Wave64, 256-thread workgroups.
 #pragma once
 
 #include "device_utils.h"
@@ -104,7 +105,7 @@ __global__ void __launch_bounds__(256) k_prepare(PrepArgs a) {
 //   G_GATEUP  x = RMSNorm(h);  rows come in (gate i, up i) pairs; act[i] = silu(gate) * up
 //   G_DOWN    x = act;  h += y
 //   G_LMHEAD  x = RMSNorm(h[gather]);  logit = y * scale feeds the single-pass softmax state of
-//             the wave (one state per token row)
+//             the wave; the workgroup's four states are merged into one partial per token row
 // ------------------------------------------------------------------------------------------------
 enum { G_QKV = 0, G_OPROJ = 1, G_GATEUP = 2, G_DOWN = 3, G_LMHEAD = 4 };
 
