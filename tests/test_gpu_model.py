@@ -320,3 +320,45 @@ def test_counter_run_driver_runs_decode_and_catchup_calls():
         r = subprocess.run([probe, "s15", "2", "2", "300"] + extra, capture_output=True, text=True, timeout=120)
         assert r.returncode == 0, r.stderr
         assert "traffic_probe s15 layers=2 steps=2 position=300" in r.stdout and "h_norm" in r.stdout
+
+
+ODD_SHAPES = [
+    # name, layers, d, n_q, n_kv, head_dim, ffn, vocab: head_dim 64 and the extreme group sizes
+    ("mha_hd64", 2, 256, 4, 4, 64, 512, 2048),          # G = 1: sixteen rows share one matrix-core pass
+    ("g8_hd64", 2, 512, 8, 1, 64, 640, 1536),           # G = 8: two rows per pass, one KV head
+    ("g3_hd128", 1, 384, 3, 1, 128, 384, 1280),         # G = 3: five rows per pass, one column unused
+]
+
+
+@pytest.mark.parametrize("name,n_layers,d,n_q,n_kv,hd,ffn,vocab", ODD_SHAPES, ids=[s[0] for s in ODD_SHAPES])
+def test_other_head_shapes_decode_and_catchup_against_oracle(name, n_layers, d, n_q, n_kv, hd, ffn, vocab):
+    """Head sizes and group sizes the five configurations do not use (head_dim 64, G = 1, 3, 8): a prompt fed as
+    catch-up calls, single-token steps, a ragged two-sequence call and a 40-row span, each against the oracle."""
+    import paper_2507_17307_amd as P
+    from workloads.shapes import ModelShape
+    shape = ModelShape(name, n_layers, d, n_q, n_kv, hd, ffn, vocab, tied_lm_head=False)
+    w = W.make_weights(shape, 11, 1)
+    max_ctx = 200
+    ref = decoder.OracleModel(w, max_ctx, n_slots=2)
+    gpu = P.Model(w.to("cuda"), max_ctx=max_ctx, max_seqs=2, max_rows=64)
+    toks = W.rng.randint(11, 5, 0, 160, vocab).tolist()
+    tau = 0.6
+
+    def both(span, pos0, slot, scale):
+        lr = ref.forward(span, pos0, slot=slot, logit_scale=scale)["logits"]
+        got, lg = gpu.forward_span(span, pos0, tau, P.RS_LLM, scale, slot=slot, want_logits=True)
+        torch.cuda.synchronize()
+        check_invocation(got[0], lg[0], lr, tau, P.RS_LLM, where=f"{name} span {len(span)} at {pos0} slot {slot}")
+
+    both(toks[:70], 0, 0, 3.0)                 # 64 + 6 rows
+    for i in range(70, 73):
+        both([toks[i]], i, 0, 1.0 + i % 3)
+    both(toks[73:113], 73, 0, 5.0)             # 40 rows crossing a context-slice boundary
+    both(toks[:9], 0, 1, 2.0)                  # second slot
+    # ragged call over both slots at once
+    spans, pos0 = [toks[113:116], toks[9:26]], [113, 9]
+    want = [ref.forward(s, p, slot=i, logit_scale=2.5)["logits"] for i, (s, p) in enumerate(zip(spans, pos0))]
+    got, lg = gpu.catchup_prefill(spans, pos0, tau, P.RS_SLM, [2.5, 2.5], want_logits=True)
+    torch.cuda.synchronize()
+    for i in range(2):
+        check_invocation(got[i], lg[i], want[i], tau, P.RS_SLM, where=f"{name} ragged sequence {i}")
