@@ -150,7 +150,7 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
     const int plane_len = seg >> 3;                       // float4 per plane; row m uses planes 2m and 2m+1
     float *red = reinterpret_cast<float *>(smem + (size_t)seg * MP * 4);   // [2][4][RT*MP]
     float *red_ss = red + 2 * 4 * RT * MP;                                  // [4][MP]
-    const bool resident = seg == K;
+    const bool resident = KS != 4 || seg == K;            // only the split-K launch may walk K in segments (the host checks)
     constexpr bool NORM = (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD);
 
     // ---- tiles

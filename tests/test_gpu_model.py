@@ -316,8 +316,11 @@ def test_counter_run_driver_runs_decode_and_catchup_calls():
     import paper_2507_17307_amd as P
     probe = os.path.join(os.path.dirname(os.path.abspath(P.__file__)), "traffic_probe")
     assert os.path.exists(probe), "build the package first (paper_2507_17307_amd.build)"
+    # the driver always runs one kernel per phase: a second process cannot take the device's cooperative-launch
+    # queue while this one holds it
+    env = {k: v for k, v in os.environ.items() if k != "RSTITCH_DECODE"}
     for extra in ([], ["5"]):
-        r = subprocess.run([probe, "s15", "2", "2", "300"] + extra, capture_output=True, text=True, timeout=120)
+        r = subprocess.run([probe, "s15", "2", "2", "300"] + extra, capture_output=True, text=True, timeout=120, env=env)
         assert r.returncode == 0, r.stderr
         assert "traffic_probe s15 layers=2 steps=2 position=300" in r.stdout and "h_norm" in r.stdout
 
