@@ -245,31 +245,39 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
 template <int MODE, int NB, int R, int NW>
 rs_status launch_gemm_r(GemmArgs &a, int blocks, hipStream_t st, const char *name) {
     constexpr size_t lds = gemm_lds_bytes<MODE, NB, R, NW>();
-    static_assert(lds <= 64 * 1024, "two workgroups per CU must fit");
+    static_assert(lds <= 76 * 1024, "two workgroups per CU must fit");
+    if (lds > 64 * 1024) {
+        static bool raised = false;                       // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_gemm_rows<MODE, NB, R, NW>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
+            raised = true;
+        }
+    }
     hipLaunchKernelGGL((k_gemm_rows<MODE, NB, R, NW>), dim3(blocks), dim3(NW * 64), lds, st, a);
     RS_LAUNCHED(name);
     return RS_OK;
 }
 
-// Launch shape.  Measured on MI355X: a CU draws at most ~30 GB/s and the weight stream needs well over
-// two thousand waves in flight (1184 waves reach 3.4 TB/s, 2368 reach 6.1), all groups resident at once;
-// and with one tile per workgroup the X pieces (three planes), not the weights, fill the CU's load path.
-// So a workgroup takes R >= 2 tiles (one X piece serves them all), and where a matrix then has too few
-// groups (QKV, O-proj, down: few output rows) K is split over workgroups as well: split ks leaves partial
-// sums in a buffer that the next kernel (rotary / RMSNorm) adds up in a fixed order.  Gate/up needs whole
-// sums for its activation and has tiles to spare.
 // workgroups for `units` work units and `yblocks` token-row blocks: with several row blocks the kernel
 // decodes ids in groups of 8 (one per XCD), so the unit count is padded to a multiple of 8
 int gemm_grid(int units, int yblocks) { return yblocks > 1 ? ((units + 7) / 8) * 8 * yblocks : units; }
 
+// Launch shape.  Measured on MI355X: a CU draws at most ~30 GB/s and the weight stream needs well over
+// two thousand waves in flight (1184 waves reach 3.4 TB/s, 2368 reach 6.1), all groups resident at once;
+// and with one tile per workgroup the X pieces (three planes), not the weights, fill the CU's load path.
+// So a workgroup takes R >= 2 tiles (one X piece serves them all; R = 4 where 32 rows make the X piece
+// twice as large), and where a matrix then has too few groups (QKV, O-proj, down: few output rows) K is
+// split over workgroups as well: split ks leaves partial sums in a buffer that the next kernel (rotary /
+// RMSNorm) adds up in a fixed order.  Gate/up needs whole sums for its activation and has tiles to spare.
 template <int MODE, int NB>
 rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     constexpr bool SPLITS = MODE == G_QKV || MODE == G_OPROJ || MODE == G_DOWN;
     const int target = 2 * m->n_cu, n_win = a.K / GEMM_KW;
     a.ksplit = 1; a.part = nullptr; a.part_stride = 0;
     if constexpr (SPLITS) {
-        constexpr int R = (NB == 1) ? 4 : 2;
-        const int r = (NB == 1 && n_win < 128) ? 2 : R;             // short rows: smaller groups rather than thin K slices
+        const int r = (NB == 1 && n_win < 128) ? 2 : 4;             // one 16-row block and short rows: smaller groups rather than thin K slices
         const int groups = (n_tiles + r - 1) / r;
         int ks = 1;
         while (ks < GEMM_KSPLIT_MAX && groups * ks < target && n_win / (2 * ks) >= 4) ks *= 2;
@@ -279,19 +287,23 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
         }
         const int blocks = gemm_grid(groups * ks, a.yblocks);
         if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
-        if constexpr (NB == 1) return launch_gemm_r<MODE, NB, 4, 4>(a, blocks, st, name);
-        else return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
+        return launch_gemm_r<MODE, NB, 4, 4>(a, blocks, st, name);
+    } else if constexpr (MODE == G_GATEUP && NB >= 2) {
+        const int r = (NB == 2 && (n_tiles + 3) / 4 >= m->n_cu) ? 4 : 2;
+        const int blocks = gemm_grid((n_tiles + r - 1) / r, a.yblocks);
+        if constexpr (NB == 2) {
+            if (r == 4) return launch_gemm_r<MODE, NB, 4, 4>(a, blocks, st, name);
+        }
+        return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
     } else {
-        const int r = (NB <= 2 && (n_tiles + 1) / 2 >= target) ? 2 : 1;
+        const int r = (n_tiles + 1) / 2 >= target ? 2 : 1;
         int blocks = (n_tiles + r - 1) / r;
         if (MODE == G_LMHEAD) {
             if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;             // one partial per workgroup
             a.n_parts = blocks;
         }
         blocks = gemm_grid(blocks, a.yblocks);
-        if constexpr (NB <= 2) {
-            if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
-        }
+        if (r == 2) return launch_gemm_r<MODE, NB, 2, 4>(a, blocks, st, name);
         return launch_gemm_r<MODE, NB, 1, 4>(a, blocks, st, name);
     }
 }
@@ -304,8 +316,8 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
     if constexpr (MODE == G_LMHEAD) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
     else {
         // up to 16 rows: one 16-row block; more: blocks of 32 rows (two 16-row blocks per workgroup), each
-        // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.8 ms, 64 rows 10.6 ms this
-        // way, against 7.1 / 11.8 ms with 16-row blocks and 9.1 / 12.9 ms with 64-row blocks.
+        // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.0 ms, 64 rows 9.1 ms this
+        // way; 64-row blocks are no faster (9.7 ms) and 16-row blocks slower.
         if (a.M <= 16) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
         a.yblocks = (a.M + 31) / 32;
         return launch_gemm_nb<MODE, 2>(m, a, n_tiles, st, name);
