@@ -226,11 +226,14 @@ def main() -> int:
         del src, dst
 
     ev = HipEvents()
-    stats = {"timed": False, "inv": []}
+    stats = {"timed": False, "inv": [], "dt": [], "t_prev": 0.0}
 
     def on_inv(model, pos0, n_rows):
+        now = time.perf_counter()
         if stats["timed"]:
             stats["inv"].append((model, pos0, n_rows))
+            stats["dt"].append(now - stats["t_prev"])          # wall time of this invocation (call, sync, host loop)
+        stats["t_prev"] = now
 
     pair.on_invocation = on_inv
 
@@ -264,6 +267,16 @@ def main() -> int:
     llm_tokens = sum(1 for t in timed_trace if t.model == LLM and t.accept)
     rejected = sum(1 for t in timed_trace if not t.accept)
     spans = [n for m, _, n in inv if m == LLM]
+    # decode steps against catch-up calls, per model: count and mean wall time by span length
+    by_span = {"slm": {}, "llm": {}}
+    for (m_, _, n), dt in zip(inv, stats["dt"]):
+        key = str(n) if n <= 4 else ("5-8" if n <= 8 else ("9-16" if n <= 16 else ("17-32" if n <= 32 else "33+")))
+        rec = by_span["slm" if m_ == SLM else "llm"].setdefault(key, [0, 0.0])
+        rec[0] += 1
+        rec[1] += dt
+    by_span = {k: {sp: {"calls": c, "ms": round(t / c * 1e3, 3)} for sp, (c, t) in sorted(v.items(), key=lambda kv: (len(kv[0]), kv[0]))}
+               for k, v in by_span.items()}
+    switches = sum(1 for i in range(1, len(inv)) if inv[i][0] != inv[i - 1][0])
 
     # ---- dominant kernel: the large model's gate/up projection.  The launch graphs of the timed
     # region cannot carry event records, so the same invocations (same kernels, grids and data) are
@@ -398,6 +411,7 @@ def main() -> int:
         "stitched": {"invocations": len(inv), "slm_invocations": n_slm_inv, "llm_invocations": n_llm_inv,
                      "llm_token_frac": round(llm_tokens / max(args.steps, 1), 4), "rejected_slm_steps": rejected,
                      "llm_span_mean": round(sum(spans) / max(len(spans), 1), 2), "llm_span_max": max(spans) if spans else 0,
+                     "model_switches": switches, "calls_by_span": by_span,
                      "roofline_ms_per_token": round(ideal_s / args.steps * 1e3, 4),
                      "roofline_frac": round(ideal_s / elapsed, 4)},
         "router": router,
