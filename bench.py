@@ -295,11 +295,45 @@ def main() -> int:
         k[0] += 1
         k[1] += ev.elapsed_ms(e0, e1)
     P.rs_set_phase_timer(llm.handle, -1)
+    # What the two event records themselves add to such a bracket: the same bracket around one launch of a
+    # streaming kernel of about the same length (an in-place add over 2^24 floats, ~20 us), minus that kernel's
+    # duration when 50 of them run back to back inside one bracket.  Medians over 30 brackets.
+    cal_x = torch.zeros(1 << 24, device=dev)
+    cal_s = torch.zeros(1 << 16, device=dev)
+    sh_cal = pair.stream.cuda_stream
+    with torch.cuda.stream(pair.stream):
+        for _ in range(5):
+            cal_x.add_(1.0)
+        singles = []
+        for _ in range(30):
+            for _ in range(4):
+                cal_s.add_(1.0)
+            ev.record(e0, sh_cal)
+            cal_x.add_(1.0)
+            ev.record(e1, sh_cal)
+            for _ in range(2):
+                cal_s.add_(1.0)
+            pair.stream.synchronize()
+            singles.append(ev.elapsed_ms(e0, e1))
+        ev.record(e0, sh_cal)
+        for _ in range(50):
+            cal_x.add_(1.0)
+        ev.record(e1, sh_cal)
+        pair.stream.synchronize()
+        event_overhead_ms = sorted(singles)[len(singles) // 2] - ev.elapsed_ms(e0, e1) / 50
+    del cal_x, cal_s
+    # an unprofiled run gives 2.7-3.2 us; with a profiler attached every dispatch costs more and the figure
+    # no longer describes the bracket, so a value outside 0..5 us is dropped and the raw bracket is reported
+    overhead_ok = 0.0 <= event_overhead_ms <= 5e-3
+    if not overhead_ok:
+        log(f"[bench] event-pair calibration gave {event_overhead_ms * 1e3:.2f} us: not applied")
+        event_overhead_ms = 0.0
     dom = max(kern.items(), key=lambda kv: kv[1][1]) if kern else None
     roofline = None
     if dom:
         name, (cnt, tot_ms) = dom
-        avg_s = tot_ms / cnt * 1e-3
+        avg_events_s = tot_ms / cnt * 1e-3
+        avg_s = avg_events_s - event_overhead_ms * 1e-3
         # HBM bytes per launch of that kernel from hardware-counter runs (FETCH_SIZE + WRITE_SIZE, scaled by a
         # copy kernel of known size), stored with the package; only the single-row kernel has been counted
         traffic = None
@@ -311,11 +345,15 @@ def main() -> int:
         except OSError:
             pass
         roofline = {"bound": "hbm", "kernel": name, "launches": cnt, "avg_us": round(avg_s * 1e6, 2),
+                    "avg_us_between_events": round(avg_events_s * 1e6, 2),
+                    "event_pair_overhead_us": round(event_overhead_ms * 1e3, 2) if overhead_ok else None,
                     "achieved": round(gateup_bytes / avg_s / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                     "frac": round(gateup_bytes / avg_s / HBM_PEAK, 4), "traffic": traffic,
                     "bytes_per_launch": gateup_bytes,
-                    "measured": "replay of the timed region's large-model invocations as plain launches",
-                    "all_variants": {k: {"launches": v[0], "avg_us": round(v[1] / v[0] * 1e3, 2)}
+                    "measured": "replay of the timed region's large-model invocations as plain launches, one event "
+                                "pair around this kernel per invocation; avg_us = time between the events minus what "
+                                "the event records add to such a bracket (calibrated in this run)",
+                    "all_variants": {k: {"launches": v[0], "avg_us": round((v[1] / v[0] - event_overhead_ms) * 1e3, 2)}
                                      for k, v in kern.items()}}
 
     # ---- each model alone: decode steps at the end of the context, GPU time per step from an
@@ -371,8 +409,9 @@ def main() -> int:
         P.rs_set_phase_timer(mdl.handle, -1)
         shape = wl.slm if mid == SLM else wl.llm
         lm_bytes = shape.vocab * shape.d_model * 2
-        router[f"{tag}_lm_head_with_fused_router_us"] = round(tot / 8 * 1e3, 2)
-        router[f"{tag}_lm_head_gbps"] = round(lm_bytes / (tot / 8 * 1e-3) / 1e9, 1)
+        lm_ms = tot / 8 - event_overhead_ms          # the same bracket as the roofline kernel's, same correction
+        router[f"{tag}_lm_head_with_fused_router_us"] = round(lm_ms * 1e3, 2)
+        router[f"{tag}_lm_head_gbps"] = round(lm_bytes / (lm_ms * 1e-3) / 1e9, 1)
     router["paper_separate_entropy_us"] = 28.0
 
     # ---- CPU oracle on a bounded sample
