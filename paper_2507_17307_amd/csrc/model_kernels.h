@@ -295,13 +295,8 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 const int n4 = len >> 2;
                 for (int i0 = tid; i0 < n4; i0 += 256 * SB) {
                     float4 v[SB];
-#ifdef RS_STAGE_SKIP
-#pragma unroll
-                    for (int j = 0; j < SB; ++j) v[j] = x4[min(i0 & 255, n4 - 1)];      // timing experiment only: 1 KB of x per workgroup
-#else
 #pragma unroll
                     for (int j = 0; j < SB; ++j) v[j] = x4[min(i0 + j * 256, n4 - 1)];
-#endif
 #pragma unroll
                     for (int j = 0; j < SB; ++j) {
                         const int i = i0 + j * 256;
@@ -401,12 +396,6 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 }
                 cb = c0 + PRE * cstride;
             }
-#ifdef RS_KS_CONTIG
-            if (KS == 4 && PRE == 0) {
-                const int chunks = K >> 3, Q = (chunks + 3) >> 2;
-                accumulate(wp, 0, wave * Q + lane, min((wave + 1) * Q, chunks), 64, acc);
-            } else
-#endif
             accumulate(wp, 0, cb, K >> 3, cstride, acc);
         } else {
             for (int k0 = 0; k0 < K; k0 += seg) {              // KS == 4 only: the tile loop is workgroup-uniform
