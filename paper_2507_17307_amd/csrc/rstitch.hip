@@ -203,11 +203,13 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
     GemvPlan p{};
     const int hd = c.head_dim, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * hd;
     auto pick = [&](size_t bytes) { return bytes >= ((size_t)128 << 20) ? 2 * n_cu : 3 * n_cu; };
-    p.qkv_rt = 2;
-    const int qkv_tiles = (c.n_q_heads + c.n_kv_heads) * (hd / 2) + (c.n_kv_heads * hd) / 2;
-    // a small QKV matrix (1.5B shape: 6 MB) runs best with one workgroup per CU (5.8 us against 6.4 us with three)
+    // QKV: two rows per wave tile; a large matrix (14B/32B shapes: 73 MB) takes four rows (two rotary pairs) with
+    // three early weight chunks at two workgroups per CU.  A small matrix (1.5B shape: 6 MB) runs best with one
+    // workgroup per CU (5.8 us against 6.4 us with three).
     const size_t qkv_bytes = (size_t)qkv_rows * c.d_model * 2;
-    p.qkv_blocks = clamp_blocks(qkv_bytes < ((size_t)16 << 20) ? n_cu : pick(qkv_bytes), (qkv_tiles + 3) / 4);
+    p.qkv_rt = qkv_bytes >= ((size_t)64 << 20) ? 4 : 2;
+    const int qkv_tiles = (c.n_q_heads + c.n_kv_heads) * (hd / p.qkv_rt) + (c.n_kv_heads * hd) / p.qkv_rt;
+    p.qkv_blocks = clamp_blocks(p.qkv_rt == 4 ? 2 * n_cu : qkv_bytes < ((size_t)16 << 20) ? n_cu : pick(qkv_bytes), (qkv_tiles + 3) / 4);
     p.o_rt = 2;
     p.o_blocks = clamp_blocks(pick((size_t)c.d_model * c.n_q_heads * hd * 2), ((c.d_model + 1) / 2 + 3) / 4);
     p.gu_blocks = clamp_blocks(pick((size_t)2 * c.d_ffn * c.d_model * 2), (c.d_ffn / 2 + 3) / 4);
@@ -460,7 +462,8 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             // QKV (+ RMSNorm, RoPE, KV write)
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_QKV, l);
-            rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
+            if (pl.qkv_rt == 4) rc = launch_gemv<G_QKV, 4, 1, 2, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
+            else rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
             toc(RS_PHASE_QKV, l);
             if (rc) return rc;
             // attention
