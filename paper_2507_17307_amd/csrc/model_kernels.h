@@ -549,7 +549,7 @@ struct AttnArgs {
 };
 
 constexpr int ATT_GMAX = 8;       // query heads per kv head, at most
-constexpr int ATT_SMAX = 128;     // context slices, at most
+constexpr int ATT_SMAX = 192;     // context slices, at most (a multiple of 64: the merge gives each lane ATT_SMAX / 64 of them)
 constexpr int ATT_WT = 16;        // tokens per wave and pass
 constexpr int ATT_BT = 64;        // tokens per workgroup and pass
 
@@ -918,9 +918,11 @@ __global__ void __launch_bounds__(256) k_attn_partial_rows(AttnArgs a) {
 template <int HD>
 __host__ __device__ constexpr size_t attn_combine_lds_bytes() { return (size_t)(ATT_SMAX + (256 / (HD / 4)) * HD) * 4; }
 
-template <int HD>
+// SMAX: the slice count this instantiation is unrolled for (n_slices <= SMAX <= ATT_SMAX, a multiple of 64)
+template <int HD, int SMAX = ATT_SMAX>
 __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned char *smem, int head, int row) {
-    constexpr int PS = HD + 4, NQ = HD / 4, NSG = 256 / NQ, NLD = (ATT_SMAX + NSG - 1) / NSG;
+    static_assert(SMAX % 64 == 0 && SMAX <= ATT_SMAX, "whole slices per lane, inside the LDS weights array");
+    constexpr int PS = HD + 4, NQ = HD / 4, NSG = 256 / NQ, NLD = (SMAX + NSG - 1) / NSG;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = a.n_slices;
     float *w_sh = reinterpret_cast<float *>(smem);                               // [ATT_SMAX]
@@ -939,22 +941,29 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
         if (s < S_act) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + 4 * qd);
     }
     if (wave == 0) {
-        static_assert(ATT_SMAX <= 128, "two slices per lane");
-        float ms[2], ls[2];
+        constexpr int NPL = SMAX / 64;                      // slices per lane
+        float ms[NPL], ls[NPL], w[NPL];
+        float mx = -INFINITY;
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < NPL; ++k) {
             const int s = lane + 64 * k;
             ms[k] = -INFINITY; ls[k] = 0.f;
             if (s < S_act) {
                 const float2 ml = *reinterpret_cast<const float2 *>(pbase + (size_t)s * PS);
                 ls[k] = ml.y; ms[k] = ls[k] > 0.f ? ml.x : -INFINITY;
             }
+            mx = fmaxf(mx, ms[k]);
         }
-        const float M = wave_max(fmaxf(ms[0], ms[1]));
-        const float w0 = ls[0] > 0.f ? __expf(ms[0] - M) : 0.f, w1 = ls[1] > 0.f ? __expf(ms[1] - M) : 0.f;
-        const float L = wave_sum(ls[0] * w0 + ls[1] * w1);
-        w_sh[lane] = L > 0.f ? w0 / L : 0.f;
-        w_sh[lane + 64] = L > 0.f ? w1 / L : 0.f;
+        const float M = wave_max(mx);
+        float lsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+            w[k] = ls[k] > 0.f ? __expf(ms[k] - M) : 0.f;
+            lsum = fmaf(ls[k], w[k], lsum);
+        }
+        const float L = wave_sum(lsum);
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) w_sh[lane + 64 * k] = L > 0.f ? w[k] / L : 0.f;
     }
     __syncthreads();
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -982,10 +991,10 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
     }
 }
 
-template <int HD>
+template <int HD, int SMAX>
 __global__ void __launch_bounds__(256) k_attn_combine(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    attn_combine_unit<HD>(a, smem, blockIdx.x, blockIdx.y);
+    attn_combine_unit<HD, SMAX>(a, smem, blockIdx.x, blockIdx.y);
 }
 
 }  // namespace rs

@@ -239,7 +239,11 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
         hipLaunchKernelGGL((k_attn_partial<HD>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(), st, a);
         RS_LAUNCHED("attn_partial");
     }
-    hipLaunchKernelGGL((k_attn_combine<HD>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
+    // the merge is unrolled for 128 slices (contexts up to 8192 positions) or for the most the kernels take
+    if (n_splits <= 128)
+        hipLaunchKernelGGL((k_attn_combine<HD, 128>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
+    else
+        hipLaunchKernelGGL((k_attn_combine<HD, ATT_SMAX>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
     RS_LAUNCHED("attn_combine");
     return RS_OK;
 }
@@ -485,8 +489,13 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             // gate/up (+ RMSNorm, SwiGLU)
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_GATEUP, l);
-            // large matrices run two workgroups per CU, which leaves registers for the early weight request
-            if (pl.gu_early && mp == 1) rc = launch_gemv<G_GATEUP, 4, 1, 4, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
+            // large matrices run two workgroups per CU, which leaves registers for the early weight request; the
+            // early chunks and the unroll are picked so that the chunks left per lane (d_model / 512 minus the
+            // early ones) are a whole number of unrolled rounds: 7 = 3 + 4 (7B shape), 10 = 4 + 3 * 2 (14B/32B shapes,
+            // 48 us against 51 us with the other variant)
+            if (pl.gu_early && mp == 1 && (c.d_model / 512 - 3) % 4 != 0 && (c.d_model / 512 - 4) % 2 == 0)
+                rc = launch_gemv<G_GATEUP, 4, 1, 2, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
+            else if (pl.gu_early && mp == 1) rc = launch_gemv<G_GATEUP, 4, 1, 4, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
             else rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
             toc(RS_PHASE_GATEUP, l);
             if (rc) return rc;

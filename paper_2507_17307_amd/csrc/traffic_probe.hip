@@ -5,7 +5,9 @@
 // counter reports for that copy.  No framework is loaded, so counter collection
 // sees only these dispatches.
 //
-//   traffic_probe <s15|m7> [layers=2] [steps=6] [position=4575] [span=1]
+//   traffic_probe <s15|m7|m14|m32> [layers=2] [steps=6] [position=4575] [span=1]
+//
+// (context capacity 4608 for s15 and m7, 9216 for m14, 10240 for m32)
 //
 // span > 1 runs catch-up calls of that many token rows ending at `position` instead of decode steps
 // (the matrix-core path).
@@ -36,9 +38,12 @@ int main(int argc, char **argv) {
     rs_config c{};
     if (!strcmp(shape, "s15")) { c.d_model = 1536; c.n_q_heads = 12; c.n_kv_heads = 2; c.d_ffn = 8960; }
     else if (!strcmp(shape, "m7")) { c.d_model = 3584; c.n_q_heads = 28; c.n_kv_heads = 4; c.d_ffn = 18944; }
-    else { fprintf(stderr, "shape must be s15 or m7\n"); return 2; }
+    else if (!strcmp(shape, "m14")) { c.d_model = 5120; c.n_q_heads = 40; c.n_kv_heads = 8; c.d_ffn = 13824; c.max_ctx = 9216; }
+    else if (!strcmp(shape, "m32")) { c.d_model = 5120; c.n_q_heads = 40; c.n_kv_heads = 8; c.d_ffn = 27648; c.max_ctx = 10240; }
+    else { fprintf(stderr, "shape must be s15, m7, m14 or m32\n"); return 2; }
     c.n_layers = layers; c.head_dim = 128; c.vocab = 152064; c.tied_lm_head = 1;
-    c.max_ctx = 4608; c.max_seqs = 1; c.max_rows = 64; c.rms_eps = 1e-6f; c.rope_theta = 1e6f;
+    if (!c.max_ctx) c.max_ctx = 4608;
+    c.max_seqs = 1; c.max_rows = 64; c.rms_eps = 1e-6f; c.rope_theta = 1e6f;
     if (layers < 1 || layers > 64 || steps < 1 || position < 0 || position >= c.max_ctx || span < 1 || span > 64 || span > position + 1) { fprintf(stderr, "bad arguments\n"); return 2; }
     setenv("RSTITCH_GRAPHS", "0", 1);                      // plain launches: one dispatch per kernel for the profiler
 
