@@ -570,7 +570,7 @@ __device__ __forceinline__ void split3(const float (&x)[8], bf16x8_t (&pl)[3]) {
 }
 
 template <int HD>
-__host__ __device__ constexpr size_t attn_lds_bytes() { return (size_t)(4 * 16 * (HD + 4) + 2 * 4 * 16) * 4; }
+__host__ __device__ constexpr size_t attn_lds_bytes(int G = ATT_GMAX) { return (size_t)(4 * G * (HD + 4) + 2 * 4 * 16) * 4; }
 
 #ifdef RS_ATT_TRACE
 __device__ long long g_att_trace[4096 * 8];
@@ -606,7 +606,15 @@ struct AttnTile {
 // are known at launch, so the row table, q, K and V are all requested at once and the unit pays one
 // memory round trip instead of three dependent ones.  Slices at or past the context length write
 // nothing; attn_combine_unit derives the same slice length and reads only the slices before it.
-template <int HD>
+// UPFRONT = false gives that up: the unit first waits for the row's position and leaves before
+// requesting anything when its slice lies past the context.  With UPFRONT every launch reads K and V
+// of ALL slices up to max_ctx, whatever the context is; that is the better trade while a layer's cache
+// is a few MB (the 1.5B and 7B shapes at 4608 positions: 4.7 and 9.4 MB), and a poor one for a large
+// cache (eight KV heads at 9216 positions: 37.7 MB per layer, 12.7 us at a context of 1000).
+// ONEPASS: the host promises that a slice is one 64-position pass (C == ATT_BT); the unit then keeps no
+// second tile and builds q's bf16 planes d step by d step, which brings it under a third of a SIMD's
+// registers (more resident workgroups: a long cache is a throughput problem, not a latency one).
+template <int HD, bool UPFRONT = true, bool ONEPASS = false>
 __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned char *smem, int split, int S, int kvh, int row) {
     constexpr int NDS = HD / 32;       // 32-wide d steps of the score contraction
     constexpr int NDB = HD / 16;       // 16-wide d blocks of the output
@@ -615,9 +623,11 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     const int j = lane & 15, kg = lane >> 4;
     const int G = a.n_q / a.n_kv;
 
-    float (*acc_lds)[16][HD + 4] = reinterpret_cast<float (*)[16][HD + 4]>(smem);        // [4 waves][16 heads][HD+4]
-    float (*m_lds)[16] = reinterpret_cast<float (*)[16]>(smem + (size_t)4 * 16 * (HD + 4) * 4);   // [4][16]
+    // a small footprint matters: eight KV heads at 9216 positions are 1152 workgroups, one round only if a CU
+    // holds five of them
+    float (*m_lds)[16] = reinterpret_cast<float (*)[16]>(smem);                         // [4 waves][16 columns]
     float (*l_lds)[16] = m_lds + 4;
+    float *acc_lds = reinterpret_cast<float *>(smem + (size_t)2 * 4 * 16 * 4);          // [4 waves][G heads][HD+4]
 
     ATT_T(0);
     int C = (a.max_ctx + S - 1) / S;
@@ -633,6 +643,9 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     const uint16_t *Kp = a.kcache + kv_base;      // [position][hd]
     const uint16_t *Vp = a.vcache + kv_base;      // [hd][position]
     const float scale = 1.0f / sqrtf((float)HD);
+    if (!UPFRONT) {
+        if (t_begin >= (bad ? 0 : pos + 1)) return;
+    }
 
     // lanes j >= G have no head: they fetch head G-1 again and are cleared after the wait
     float4 qraw[NDS][2];
@@ -650,16 +663,19 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     if (t_begin >= t_end) return;                  // nothing of this slice is in the context: the merge skips it too
 
     // q of head j as the B operand of the score contraction: three exact bf16 planes per d step
-    bf16x8_t qB[NDS][3];
-#pragma unroll
-    for (int ds = 0; ds < NDS; ++ds) {
+    auto q_planes = [&](int ds, bf16x8_t (&out)[3]) {
         const float4 x0 = qraw[ds][0], x1 = qraw[ds][1];
         float qv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
         if (j >= G) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) qv[e] = 0.f;
         }
-        split3(qv, qB[ds]);
+        split3(qv, out);
+    };
+    bf16x8_t qB[ONEPASS ? 1 : NDS][3];
+    if (!ONEPASS) {
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) q_planes(ds, qB[ds]);
     }
 
     ATT_T(1);
@@ -670,7 +686,7 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
 
     for (int t0 = t_begin + wave * ATT_WT; t0 < t_end; t0 += ATT_BT) {
         AttnTile<HD> nxt;
-        const bool more = t0 + ATT_BT < t_end;
+        const bool more = !ONEPASS && t0 + ATT_BT < t_end;
         if (more) nxt.load(Kp, Vp, t0 + ATT_BT, a.max_ctx, j, kg);
         // ---- scores of 16 tokens; lane holds tokens t0 + 4 kg + r of head j.
         // Positions at or past t_end may hold anything (a rejected step's rows, never-written memory):
@@ -679,8 +695,15 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
 #pragma unroll
         for (int ds = 0; ds < NDS; ++ds) {
             const bf16x8_t A = __builtin_bit_cast(bf16x8_t, cur.k[ds]);
+            if (ONEPASS) {
+                bf16x8_t qb[3];
+                q_planes(ds, qb);
 #pragma unroll
-            for (int pl = 2; pl >= 0; --pl) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc, 0, 0, 0);
+                for (int pl = 2; pl >= 0; --pl) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qb[pl], sc, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int pl = 2; pl >= 0; --pl) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc, 0, 0, 0);
+            }
         }
         float mx = -INFINITY;
         const int tok_lo = t0 + 4 * kg;
@@ -731,9 +754,11 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     l_run += __shfl_xor(l_run, 32, RS_WAVE);
 
     // ---- merge the four waves
+    if (j < G) {
 #pragma unroll
-    for (int db = 0; db < NDB; ++db)
-        *reinterpret_cast<float4 *>(&acc_lds[wave][j][16 * db + 4 * kg]) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+        for (int db = 0; db < NDB; ++db)
+            *reinterpret_cast<float4 *>(&acc_lds[(size_t)(wave * G + j) * PS + 16 * db + 4 * kg]) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+    }
     if (kg == 0) { m_lds[wave][j] = m_run; l_lds[wave][j] = l_run; }
     __syncthreads();
     for (int i = tid; i < G * HD; i += 256) {
@@ -745,7 +770,8 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
             const float w0 = m0 > -INFINITY ? __expf(m0 - M) : 0.f, w1 = m1 > -INFINITY ? __expf(m1 - M) : 0.f;
             const float w2 = m2 > -INFINITY ? __expf(m2 - M) : 0.f, w3 = m3 > -INFINITY ? __expf(m3 - M) : 0.f;
             L = l_lds[0][g] * w0 + l_lds[1][g] * w1 + l_lds[2][g] * w2 + l_lds[3][g] * w3;
-            O = acc_lds[0][g][d] * w0 + acc_lds[1][g][d] * w1 + acc_lds[2][g][d] * w2 + acc_lds[3][g][d] * w3;
+            O = acc_lds[(size_t)(0 * G + g) * PS + d] * w0 + acc_lds[(size_t)(1 * G + g) * PS + d] * w1 +
+                acc_lds[(size_t)(2 * G + g) * PS + d] * w2 + acc_lds[(size_t)(3 * G + g) * PS + d] * w3;
         }
         float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
         p[4 + d] = O;
@@ -754,19 +780,19 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     ATT_T(5);
 }
 
-template <int HD>
-__global__ void __launch_bounds__(256) k_attn_partial(AttnArgs a) {
+template <int HD, bool UPFRONT, bool ONEPASS>
+__global__ void __launch_bounds__(256, ONEPASS ? 3 : 1) k_attn_partial(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    attn_partial_unit<HD>(a, smem, blockIdx.x, gridDim.x, blockIdx.y, blockIdx.z);
+    attn_partial_unit<HD, UPFRONT, ONEPASS>(a, smem, blockIdx.x, gridDim.x, blockIdx.y, blockIdx.z);
 }
 
 // ------------------------------------------------------------------------------------------------
 // k_attn_partial_rows: the same partial records for a call with several token rows (catch-up spans).
-// grid (n_slices, n_kv_heads, ceil(n_rows / (4 RP))), block 256, no LDS.  The 16 columns of the
+// grid (n_slices, n_kv_heads, ceil(row slots / W)), block 64 W with W = 1..4 waves, no LDS.  The 16 columns of the
 // matrix-core tiles carry RP = 16 / G token rows at once (G = query heads per KV head): column
 // rr * G + gh is head gh of the rr-th row of the wave's row slot, so one K/V tile serves RP rows.
 // A wave owns one row slot (RP consecutive rows) and one context slice, walks the slice in passes of
-// 64 positions with an online softmax per column, and writes its columns' records itself; the four
+// 64 positions with an online softmax per column, and writes its columns' records itself; the
 // waves of a workgroup hold neighbouring row slots of the SAME slice, so their K/V requests meet in
 // the CU's cache and HBM is read once per slice.  Rows of one slot that belong to different
 // sequences (different cache slots) are taken in separate turns.  Causality is per column: row r
@@ -784,7 +810,7 @@ __global__ void __launch_bounds__(256) k_attn_partial_rows(AttnArgs a) {
     C = ((C + 63) / 64) * 64;
     const int t_begin = split * C;
     const float scale = 1.0f / sqrtf((float)HD);
-    const int slot_first = (blockIdx.z * 4 + wave) * RP, slot_end = min(slot_first + RP, a.n_rows);
+    const int slot_first = (blockIdx.z * (blockDim.x >> 6) + wave) * RP, slot_end = min(slot_first + RP, a.n_rows);
 
     for (int r0 = slot_first; r0 < slot_end;) {
         // a turn: the rows r0 .. r1-1 of the slot that share r0's cache slot (and are valid)

@@ -232,11 +232,27 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
     a.n_rows = n_rows;
     if (spans) {
         // several rows per sequence: rows share K/V tiles through the columns of the matrix-core tiles
+        // one wave per row slot (rp rows); the kernel needs most of a SIMD's registers, so a workgroup brings
+        // only as many waves as it has slots (up to four): with idle waves in it, a CU held one workgroup at a
+        // time and a two-row call on eight KV heads at 5000 positions took 17.5 us instead of ~7
         const int rp = 16 / (a.n_q / n_kv);
-        hipLaunchKernelGGL((k_attn_partial_rows<HD>), dim3(n_splits, n_kv, (n_rows + 4 * rp - 1) / (4 * rp)), dim3(256), 0, st, a);
+        const int slots = (n_rows + rp - 1) / rp, wpb = slots < 4 ? slots : 4;
+        hipLaunchKernelGGL((k_attn_partial_rows<HD>), dim3(n_splits, n_kv, (slots + wpb - 1) / wpb), dim3(64 * wpb), 0, st, a);
         RS_LAUNCHED("attn_partial_rows");
     } else {
-        hipLaunchKernelGGL((k_attn_partial<HD>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(), st, a);
+        // requesting every slice's K and V before the context length is known reads the rows' whole caches:
+        // worth it up to ~12 MB per launch, beyond that the units wait for the position first
+        const size_t cache_bytes = (size_t)n_rows * n_kv * a.max_ctx * HD * 4;
+        // a large cache is also where throughput counts: when every slice is a single 64-position pass (the
+        // kernel's own slice length, recomputed here) the variant that fits three waves per SIMD is used
+        int slice_len = (a.max_ctx + n_splits - 1) / n_splits;
+        slice_len = ((slice_len + ATT_BT - 1) / ATT_BT) * ATT_BT;
+        if (cache_bytes <= ((size_t)12 << 20))
+            hipLaunchKernelGGL((k_attn_partial<HD, true, false>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(a.n_q / n_kv), st, a);
+        else if (slice_len == ATT_BT)
+            hipLaunchKernelGGL((k_attn_partial<HD, false, true>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(a.n_q / n_kv), st, a);
+        else
+            hipLaunchKernelGGL((k_attn_partial<HD, false, false>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(a.n_q / n_kv), st, a);
         RS_LAUNCHED("attn_partial");
     }
     // the merge is unrolled for 128 slices (contexts up to 8192 positions) or for the most the kernels take
