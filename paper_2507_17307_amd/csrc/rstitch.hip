@@ -240,14 +240,17 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
         hipLaunchKernelGGL((k_attn_partial_rows<HD>), dim3(n_splits, n_kv, (slots + wpb - 1) / wpb), dim3(64 * wpb), 0, st, a);
         RS_LAUNCHED("attn_partial_rows");
     } else {
-        // requesting every slice's K and V before the context length is known reads the rows' whole caches:
-        // worth it up to ~12 MB per launch, beyond that the units wait for the position first
+        // requesting every slice's K and V before the context length is known reads the rows' whole caches up to
+        // max_ctx.  That saves a dependent round trip, but on a decode run that walks a 4608-position cache the
+        // variant that waits for the position first is the faster one for both the 1.5B and the 7B shape (stitched
+        // rate +0.7 % in the same process; at full context the two are within 0.2 us per layer), and by far for
+        // larger caches, so only launches whose caches total <= 2 MB request everything up front
         const size_t cache_bytes = (size_t)n_rows * n_kv * a.max_ctx * HD * 4;
-        // a large cache is also where throughput counts: when every slice is a single 64-position pass (the
-        // kernel's own slice length, recomputed here) the variant that fits three waves per SIMD is used
+        // when every slice is a single 64-position pass (the kernel's own slice length, recomputed here) the
+        // variant that fits three waves per SIMD is used: more resident workgroups for a long cache
         int slice_len = (a.max_ctx + n_splits - 1) / n_splits;
         slice_len = ((slice_len + ATT_BT - 1) / ATT_BT) * ATT_BT;
-        if (cache_bytes <= ((size_t)12 << 20))
+        if (cache_bytes <= ((size_t)2 << 20))
             hipLaunchKernelGGL((k_attn_partial<HD, true, false>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(a.n_q / n_kv), st, a);
         else if (slice_len == ATT_BT)
             hipLaunchKernelGGL((k_attn_partial<HD, false, true>), dim3(n_splits, n_kv, n_rows), dim3(256), attn_lds_bytes<HD>(a.n_q / n_kv), st, a);

@@ -158,6 +158,8 @@ FULL_SHAPES = [
     ("m7", W.M7, 28, 4607 - 40, [1, 2, 37]),
     ("m14_4layers", W.ModelShape("m14_4", 4, 5120, 40, 8, 128, 13824, 152064, False), 4, 9215 - 20, [1, 19]),
     ("m32_2layers", W.ModelShape("m32_2", 2, 5120, 40, 8, 128, 27648, 152064, False), 2, 10239 - 70, [1, 64, 5]),
+    # a cache longer than 192 slices of 64 positions: every context slice is two passes
+    ("long_cache_small_model", W.ModelShape("long_cache", 2, 512, 4, 2, 128, 768, 2048, False), 2, 13000, [1, 5, 1]),
 ]
 
 
