@@ -74,6 +74,7 @@ struct Layout {
 
 struct GemvPlan {
     int qkv_rt, qkv_blocks, o_rt, o_blocks, gu_blocks, down_rt, down_blocks, lm_blocks;
+    bool o_all_early;     // O-proj of a mid-sized matrix: every chunk of a wave's first tile requested before the prologue
     bool gu_early;      // gate/up single-row kernel with the early weight request
 };
 
@@ -212,8 +213,15 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
     p.qkv_blocks = clamp_blocks(p.qkv_rt == 4 ? 2 * n_cu : qkv_bytes < ((size_t)16 << 20) ? n_cu : pick(qkv_bytes), (qkv_tiles + 3) / 4);
     p.o_rt = 2;
     p.o_blocks = clamp_blocks(pick((size_t)c.d_model * c.n_q_heads * hd * 2), ((c.d_model + 1) / 2 + 3) / 4);
-    p.gu_blocks = clamp_blocks(pick((size_t)2 * c.d_ffn * c.d_model * 2), (c.d_ffn / 2 + 3) / 4);
     p.gu_early = (size_t)2 * c.d_ffn * c.d_model * 2 >= ((size_t)128 << 20);
+    // gate/up: large matrices take two gate/up pairs per wave tile at two workgroups per CU; small ones one pair
+    // per tile and two tiles per wave (1.5B shape: 1120 workgroups), 1.5B decode step -2.5 % against four-row
+    // tiles at three workgroups per CU
+    p.gu_blocks = p.gu_early ? clamp_blocks(pick((size_t)2 * c.d_ffn * c.d_model * 2), (c.d_ffn / 2 + 3) / 4)
+                             : clamp_blocks((c.d_ffn + 7) / 8, (c.d_ffn + 3) / 4);
+    const size_t o_bytes = (size_t)c.d_model * c.n_q_heads * hd * 2;
+    p.o_all_early = o_bytes >= ((size_t)16 << 20) && o_bytes < ((size_t)40 << 20) && c.n_q_heads * hd <= 3584;
+    if (p.o_all_early) p.o_blocks = clamp_blocks(2 * n_cu, ((c.d_model + 1) / 2 + 3) / 4);
     // down: split-K workgroups, rows per workgroup chosen so that ~2 workgroups per CU have one tile each
     const int want = (c.d_model + 2 * n_cu - 1) / (2 * n_cu);
     const int opts[] = {2, 4, 5, 7, 8, 10};
@@ -237,7 +245,11 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
         // time and a two-row call on eight KV heads at 5000 positions took 17.5 us instead of ~7
         const int rp = 16 / (a.n_q / n_kv);
         const int slots = (n_rows + rp - 1) / rp, wpb = slots < 4 ? slots : 4;
-        hipLaunchKernelGGL((k_attn_partial_rows<HD>), dim3(n_splits, n_kv, (slots + wpb - 1) / wpb), dim3(64 * wpb), 0, st, a);
+        const dim3 grid(n_splits, n_kv, (slots + wpb - 1) / wpb);
+        if ((size_t)n_kv * a.max_ctx * HD * 4 <= ((size_t)16 << 20))
+            hipLaunchKernelGGL((k_attn_partial_rows<HD, 1>), grid, dim3(64 * wpb), 0, st, a);
+        else
+            hipLaunchKernelGGL((k_attn_partial_rows<HD, 2>), grid, dim3(64 * wpb), 0, st, a);
         RS_LAUNCHED("attn_partial_rows");
     } else {
         // requesting every slice's K and V before the context length is known reads the rows' whole caches up to
@@ -486,6 +498,8 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_QKV, l);
             if (pl.qkv_rt == 4) rc = launch_gemv<G_QKV, 4, 1, 2, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
+            // d_model <= 1536: a row is three chunks per lane, all requested before the prologue (1.5B step -1 %)
+            else if (c.d_model <= 1536) rc = launch_gemv<G_QKV, 2, 1, 1, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
             else rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
             toc(RS_PHASE_QKV, l);
             if (rc) return rc;
@@ -502,7 +516,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.attn_out);
             tic(RS_PHASE_OPROJ, l);
-            rc = launch_gemv<G_OPROJ, 2, 1, 2, 4>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
+            // 7B shape (25.7 MB, seven chunks per lane and row): all seven early at two workgroups per CU, step -0.5 %
+            if (pl.o_all_early) rc = launch_gemv<G_OPROJ, 2, 1, 1, 7>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
+            else rc = launch_gemv<G_OPROJ, 2, 1, 2, 4>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
             toc(RS_PHASE_OPROJ, l);
             if (rc) return rc;
             // gate/up (+ RMSNorm, SwiGLU)
@@ -515,7 +531,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             if (pl.gu_early && mp == 1 && (c.d_model / 512 - 3) % 4 != 0 && (c.d_model / 512 - 4) % 2 == 0)
                 rc = launch_gemv<G_GATEUP, 4, 1, 2, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
             else if (pl.gu_early && mp == 1) rc = launch_gemv<G_GATEUP, 4, 1, 4, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
-            else rc = launch_gemv<G_GATEUP, 4, 1, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
+            else rc = launch_gemv<G_GATEUP, 2, 1, 1, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
             toc(RS_PHASE_GATEUP, l);
             if (rc) return rc;
             // down + residual
