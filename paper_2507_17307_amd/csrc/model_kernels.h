@@ -942,20 +942,23 @@ __global__ void __launch_bounds__(256, MINW) k_attn_partial_rows(AttnArgs a) {
     }
 }
 
-// merge the context slices of one (row, query head): 256 threads = (HD/4 float4 columns) x slice groups.
-// smem: ATT_SMAX + (256 / (HD/4)) * HD floats
+// merge the context slices of one (row, query head); 256 threads = (float4 columns) x (slice groups).
+// DQ workgroups share a head, each taking HD / DQ output columns: a head's records are S * (HD+4) floats
+// (38 KB for 72 slices), and with one workgroup per head only n_q CUs pull them.
+// smem: ATT_SMAX + 1024 floats
 template <int HD>
-__host__ __device__ constexpr size_t attn_combine_lds_bytes() { return (size_t)(ATT_SMAX + (256 / (HD / 4)) * HD) * 4; }
+__host__ __device__ constexpr size_t attn_combine_lds_bytes() { return (size_t)(ATT_SMAX + 1024) * 4; }
 
 // SMAX: the slice count this instantiation is unrolled for (n_slices <= SMAX <= ATT_SMAX, a multiple of 64)
-template <int HD, int SMAX = ATT_SMAX>
-__device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned char *smem, int head, int row) {
+template <int HD, int SMAX = ATT_SMAX, int DQ = 1>
+__device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned char *smem, int head, int row, int dq = 0) {
     static_assert(SMAX % 64 == 0 && SMAX <= ATT_SMAX, "whole slices per lane, inside the LDS weights array");
-    constexpr int PS = HD + 4, NQ = HD / 4, NSG = 256 / NQ, NLD = (SMAX + NSG - 1) / NSG;
+    static_assert(HD % (4 * DQ) == 0 && 256 % (HD / 4 / DQ) == 0, "whole float4 columns per workgroup");
+    constexpr int PS = HD + 4, NQ = HD / 4 / DQ, NSG = 256 / NQ, NLD = (SMAX + NSG - 1) / NSG, HDB = HD / DQ;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = a.n_slices;
     float *w_sh = reinterpret_cast<float *>(smem);                               // [ATT_SMAX]
-    float (*red)[HD] = reinterpret_cast<float (*)[HD]>(w_sh + ATT_SMAX);         // [NSG][HD]
+    float (*red)[HDB] = reinterpret_cast<float (*)[HDB]>(w_sh + ATT_SMAX);       // [NSG][HDB]: 1024 floats
     const float *pbase = a.partials + ((size_t)row * a.n_q + head) * S * PS;
     const int qd = tid % NQ, sg = tid / NQ;
     // slices that hold context: same slice length as attn_partial_unit
@@ -967,7 +970,7 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
     for (int k = 0; k < NLD; ++k) {
         const int s = sg + k * NSG;
         buf[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (s < S_act) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + 4 * qd);
+        if (s < S_act) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + dq * HDB + 4 * qd);
     }
     if (wave == 0) {
         constexpr int NPL = SMAX / 64;                      // slices per lane
@@ -1004,11 +1007,11 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
     }
     *reinterpret_cast<float4 *>(&red[sg][4 * qd]) = sum;
     __syncthreads();
-    if (tid < HD) {
+    if (tid < HDB) {
         float o = 0.f;
 #pragma unroll
         for (int g = 0; g < NSG; ++g) o += red[g][tid];
-        const size_t oi = ((size_t)row * a.n_q + head) * HD + tid;
+        const size_t oi = ((size_t)row * a.n_q + head) * HD + dq * HDB + tid;
         a.out[oi] = o;
         if (a.out_planes) {
             const uint16_t p0 = f32_to_bf16(o);
@@ -1020,10 +1023,11 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
     }
 }
 
-template <int HD, int SMAX>
+// grid (n_q_heads, n_rows, DQ)
+template <int HD, int SMAX, int DQ>
 __global__ void __launch_bounds__(256) k_attn_combine(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    attn_combine_unit<HD, SMAX>(a, smem, blockIdx.x, blockIdx.y);
+    attn_combine_unit<HD, SMAX, DQ>(a, smem, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 }  // namespace rs

@@ -271,10 +271,12 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
         RS_LAUNCHED("attn_partial");
     }
     // the merge is unrolled for 128 slices (contexts up to 8192 positions) or for the most the kernels take
+    // HD / 64 workgroups per head, 64 output columns each
+    constexpr int DQ = HD / 64 > 0 ? HD / 64 : 1;
     if (n_splits <= 128)
-        hipLaunchKernelGGL((k_attn_combine<HD, 128>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
+        hipLaunchKernelGGL((k_attn_combine<HD, 128, DQ>), dim3(a.n_q, n_rows, DQ), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
     else
-        hipLaunchKernelGGL((k_attn_combine<HD, ATT_SMAX>), dim3(a.n_q, n_rows), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
+        hipLaunchKernelGGL((k_attn_combine<HD, ATT_SMAX, DQ>), dim3(a.n_q, n_rows, DQ), dim3(256), attn_combine_lds_bytes<HD>(), st, a);
     RS_LAUNCHED("attn_combine");
     return RS_OK;
 }
