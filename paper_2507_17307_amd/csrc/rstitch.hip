@@ -313,7 +313,10 @@ int gemm_grid(int units, int yblocks) { return yblocks > 1 ? ((units + 7) / 8) *
 template <int MODE, int NB>
 rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     constexpr bool SPLITS = MODE == G_QKV || MODE == G_OPROJ || MODE == G_DOWN;
-    const int target = 2 * m->n_cu, n_win = a.K / GEMM_KW;
+    // K is split further while the launch has fewer than 1.75 workgroups per CU (A/B of the whole stitched run:
+    // with a threshold of 2 the 7B O-proj went from 448 to 896 workgroups of 7 windows each and its calls
+    // were 0.04 ms slower)
+    const int target = 7 * m->n_cu / 4, n_win = a.K / GEMM_KW;
     a.ksplit = 1; a.part = nullptr; a.part_stride = 0;
     if constexpr (SPLITS) {
         const int r = (NB == 1 && n_win < 128) ? 2 : 4;             // one 16-row block and short rows: smaller groups rather than thin K slices
