@@ -761,20 +761,28 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     }
     if (kg == 0) { m_lds[wave][j] = m_run; l_lds[wave][j] = l_run; }
     __syncthreads();
-    for (int i = tid; i < G * HD; i += 256) {
-        const int g = i / HD, d = i - g * HD;
+    // one float4 of one head per thread: G * HD / 4 items (224 for seven heads of 128 channels)
+    for (int i = tid; i < G * (HD / 4); i += 256) {
+        const int g = i / (HD / 4), d = 4 * (i - g * (HD / 4));
         const float m0 = m_lds[0][g], m1 = m_lds[1][g], m2 = m_lds[2][g], m3 = m_lds[3][g];
         const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-        float L = 0.f, O = 0.f;
+        float L = 0.f;
+        float4 O = make_float4(0.f, 0.f, 0.f, 0.f);
         if (M > -INFINITY) {
             const float w0 = m0 > -INFINITY ? __expf(m0 - M) : 0.f, w1 = m1 > -INFINITY ? __expf(m1 - M) : 0.f;
             const float w2 = m2 > -INFINITY ? __expf(m2 - M) : 0.f, w3 = m3 > -INFINITY ? __expf(m3 - M) : 0.f;
             L = l_lds[0][g] * w0 + l_lds[1][g] * w1 + l_lds[2][g] * w2 + l_lds[3][g] * w3;
-            O = acc_lds[(size_t)(0 * G + g) * PS + d] * w0 + acc_lds[(size_t)(1 * G + g) * PS + d] * w1 +
-                acc_lds[(size_t)(2 * G + g) * PS + d] * w2 + acc_lds[(size_t)(3 * G + g) * PS + d] * w3;
+            const float4 a0 = *reinterpret_cast<const float4 *>(&acc_lds[(size_t)(0 * G + g) * PS + d]);
+            const float4 a1 = *reinterpret_cast<const float4 *>(&acc_lds[(size_t)(1 * G + g) * PS + d]);
+            const float4 a2 = *reinterpret_cast<const float4 *>(&acc_lds[(size_t)(2 * G + g) * PS + d]);
+            const float4 a3 = *reinterpret_cast<const float4 *>(&acc_lds[(size_t)(3 * G + g) * PS + d]);
+            O.x = a0.x * w0 + a1.x * w1 + a2.x * w2 + a3.x * w3;
+            O.y = a0.y * w0 + a1.y * w1 + a2.y * w2 + a3.y * w3;
+            O.z = a0.z * w0 + a1.z * w1 + a2.z * w2 + a3.z * w3;
+            O.w = a0.w * w0 + a1.w * w1 + a2.w * w2 + a3.w * w3;
         }
         float *p = a.partials + (((size_t)row * a.n_q + kvh * G + g) * S + split) * PS;
-        p[4 + d] = O;
+        *reinterpret_cast<float4 *>(p + 4 + d) = O;
         if (d == 0) { p[0] = M; p[1] = L; }
     }
     ATT_T(5);
