@@ -113,6 +113,35 @@ def test_batched_ragged_calls_match_per_sequence_oracle(spans):
         check_invocation(got[i], lg[i], ref, 0.7, router.SLM, where=f"decode seq {i}")
 
 
+def test_batched_decode_over_large_caches_matches_per_sequence_oracle():
+    """Three sequences, one token each, on a model whose caches (three slots of 2 KV heads x 2048 positions x
+    128 channels) are large enough that the single-row attention kernel waits for each row's position before it
+    requests K and V: the rows of a batched step go through that variant side by side."""
+    import paper_2507_17307_amd as P
+    from workloads.shapes import ModelShape
+    shape = ModelShape("batched_large_cache", 2, 256, 4, 2, 128, 512, 1024, tied_lm_head=False)
+    w = W.make_weights(shape, 21, 1)
+    n, max_ctx = 3, 2048
+    gpu = P.Model(w.to("cuda"), max_ctx=max_ctx, max_seqs=4, max_rows=64)
+    refs = [decoder.OracleModel(w, max_ctx) for _ in range(n)]
+    slots = [2, 0, 3]
+    pre = [130, 61, 200]                                      # prefixes that end in different context slices
+    toks = [W.rng.randint(21, 300 + i, 0, pre[i] + 3, shape.vocab).tolist() for i in range(n)]
+    for i in range(n):
+        refs[i].forward(toks[i][:pre[i]], 0)
+        for c0 in range(0, pre[i], 64):
+            gpu.forward_span(toks[i][c0:min(c0 + 64, pre[i])], c0, 0.5, P.RS_LLM, slot=slots[i])
+    scales = [1.5, 2.5, 4.0]
+    for step in range(2):
+        nxt = [toks[i][pre[i] + step] for i in range(n)]
+        pos = [pre[i] + step for i in range(n)]
+        got, lg = gpu.decode_step(nxt, pos, 0.6, P.RS_SLM, scales, slots, want_logits=True)
+        torch.cuda.synchronize()
+        for i in range(n):
+            ref = refs[i].forward([nxt[i]], pos[i], logit_scale=scales[i])["logits"]
+            check_invocation(got[i], lg[i], ref, 0.6, router.SLM, where=f"step {step} seq {i}")
+
+
 def test_device_side_argument_errors_are_flagged_not_faulted():
     import paper_2507_17307_amd as P
     w = W.make_weights(W.TINY_S, 5, 0).to("cuda")
