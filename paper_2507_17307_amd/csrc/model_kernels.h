@@ -511,6 +511,130 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Single-row down projection (h += W_down . act) with staging waves: 512 threads.  Waves 0..3 own a
+// quarter of K each, as in the split-K GEMV above; waves 4..7 do nothing but copy the activation vector
+// (K fp32, tens of KB) from L2 into LDS.  A wave's loads return in order, so a wave that stages x cannot
+// have weight requests in flight ahead of it without stalling the copy; with the copy on waves of its
+// own the compute waves request the first PRE chunks of their tile at once and the weight stream starts
+// while x is still on its way.  Every wave executes the same barriers (one after the copy, one per
+// tile); the staging waves only wait at them.
+// grid: workgroups share the ceil(N / RT) row tiles in contiguous ranges; LDS: K * 4 + 512 bytes.
+// ------------------------------------------------------------------------------------------------
+__host__ __device__ constexpr size_t down_staged_lds_bytes(int K) { return (size_t)K * 4 + 512; }
+
+template <int RT, int UNR, int PRE>
+__global__ void __launch_bounds__(512, 4) k_down_staged(GemvArgs a) {      // four waves per SIMD: two workgroups per CU
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int K = a.K, n_chunks = K >> 3, plane_len = K >> 3;
+    float4 *xs = reinterpret_cast<float4 *>(smem);                          // two planes of K/8 float4
+    float *red = reinterpret_cast<float *>(smem + (size_t)K * 4);           // [2][4][RT] (RT <= 10: 320 bytes)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool stager = wave >= 4;
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    const int n_tiles = (a.N + RT - 1) / RT;
+    const int t_lo = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)nwg), t_hi = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)nwg);
+    const int c0 = (wave & 3) * 64 + lane, cstride = 256;
+
+    uint4 pre[PRE > 0 ? PRE : 1][RT];
+    if (!stager) {
+        // first tile's early chunks (a workgroup without a tile requests the last tile's and never uses them)
+        const int t0 = min(t_lo, n_tiles - 1);
+#pragma unroll
+        for (int u = 0; u < PRE; ++u) {
+            const int c = min(c0 + u * cstride, n_chunks - 1);
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+                pre[u][r] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)min(t0 * RT + r, a.N - 1) * K) + c);
+        }
+    } else {
+        // x: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
+        const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in);
+        const int n4 = K >> 2, st = tid - 256;
+        constexpr int SB = 10;
+        for (int b0 = 0; b0 < n4; b0 += 256 * SB) {
+            float4 v[SB];
+#pragma unroll
+            for (int j = 0; j < SB; ++j) v[j] = x4[min(b0 + st + j * 256, n4 - 1)];
+#pragma unroll
+            for (int j = 0; j < SB; ++j) {
+                const int i = b0 + st + j * 256;
+                if (i < n4) xs[(i & 1) * plane_len + (i >> 1)] = v[j];
+            }
+        }
+    }
+    __syncthreads();
+
+    int parity = 0;
+    for (int t = t_lo; t < t_hi; ++t) {
+        float acc[RT];
+        float epi[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) { acc[r] = 0.f; epi[r] = 0.f; }
+        if (!stager) {
+            const uint4 *wp[RT];
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const int row = min(t * RT + r, a.N - 1);
+                wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)row * K);
+                epi[r] = a.h_out[row];                                     // requested ahead of the weight stream
+            }
+            int cb = c0;
+            if (PRE > 0 && t == t_lo) {
+#pragma unroll
+                for (int u = 0; u < PRE; ++u) {
+                    const int c = c0 + u * cstride;
+                    const bool valid = c < n_chunks;
+                    const int cc = valid ? c : 0;
+                    float4 xa = xs[cc], xb = xs[plane_len + cc];
+                    if (!valid) { xa = make_float4(0.f, 0.f, 0.f, 0.f); xb = xa; }
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) {
+                        const uint4 w = pre[u][r];
+                        float v = acc[r];
+                        v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
+                        v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
+                        acc[r] = v;
+                    }
+                }
+                cb = c0 + PRE * cstride;
+            }
+#pragma unroll UNR
+            for (int c = cb; c < n_chunks; c += cstride) {
+                uint4 wv[RT];
+#pragma unroll
+                for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
+                const float4 xa = xs[c], xb = xs[plane_len + c];
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const uint4 w = wv[r];
+                    float v = acc[r];
+                    v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
+                    v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
+                    acc[r] = v;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < RT; ++r) red[(parity * 4 + wave) * RT + r] = acc[r];
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const int row = t * RT + r;
+                if (row < a.N)
+                    a.h_out[row] = epi[r] + (red[(parity * 4 + 0) * RT + r] + red[(parity * 4 + 1) * RT + r] +
+                                             red[(parity * 4 + 2) * RT + r] + red[(parity * 4 + 3) * RT + r]);
+            }
+        }
+        parity ^= 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Split-K grouped-query decode attention in two kernels.
 //
 // k_attn_partial: grid (n_slices, n_kv_heads, n_rows), block 256.  A workgroup owns one KV head,

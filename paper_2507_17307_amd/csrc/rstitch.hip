@@ -188,6 +188,23 @@ rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *na
     return RS_OK;
 }
 
+template <int RT, int UNR, int PRE>
+rs_status launch_down_staged(GemvArgs &a, int blocks, hipStream_t st) {
+    const size_t lds = down_staged_lds_bytes(a.K);
+    if (lds > 64 * 1024) {
+        static bool raised = false;                       // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_down_staged<RT, UNR, PRE>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of the down projection: %s", hipGetErrorString(e));
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((k_down_staged<RT, UNR, PRE>), dim3(blocks), dim3(512), lds, st, a);
+    RS_LAUNCHED("down_staged");
+    return RS_OK;
+}
+
 // Single-row launches.  (gemv_phase can be compiled for 2, 4 or 8 token rows as well; on this chip the
 // matrix-core path overtakes those variants already at two rows, so only the one-row form is built.)
 // PRE: early weight request.
@@ -547,7 +564,13 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
                 case 2: rc = launch_gemv<G_DOWN, 2, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
                 case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
                 case 5: rc = launch_gemv<G_DOWN, 5, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
-                case 7: rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                // seven-row tiles (7B shape): the variant with staging waves, as long as two workgroups of it fit a CU
+                // (x in LDS <= 76 KB); 7B decode step -0.024 ms.  With ten-row tiles it would spill registers, with
+                // two-row tiles (1.5B shape) it measured no gain.
+                case 7:
+                    if (mp == 1 && (size_t)c.d_ffn <= (size_t)GEMV_LDS_FLOATS / 2) rc = launch_down_staged<7, 1, 1>(g, pl.down_blocks, st);
+                    else rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down");
+                    break;
                 case 8: rc = launch_gemv<G_DOWN, 8, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
                 default: rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
             }
