@@ -565,14 +565,19 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
                 case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
                 case 5: rc = launch_gemv<G_DOWN, 5, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
                 // seven-row tiles (7B shape): the variant with staging waves, as long as two workgroups of it fit a CU
-                // (x in LDS <= 76 KB); 7B decode step -0.024 ms.  With ten-row tiles it would spill registers, with
+                // (x in LDS <= 76 KB); 7B decode step -0.024 ms.  With ten-row tiles or a second unrolled round it would spill registers, with
                 // two-row tiles (1.5B shape) it measured no gain.
                 case 7:
                     if (mp == 1 && (size_t)c.d_ffn <= (size_t)GEMV_LDS_FLOATS / 2) rc = launch_down_staged<7, 1, 1>(g, pl.down_blocks, st);
                     else rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down");
                     break;
                 case 8: rc = launch_gemv<G_DOWN, 8, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
-                default: rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
+                // ten-row tiles (14B/32B shapes): where two workgroups with x in LDS fit a CU (14B: 54 KB each), the
+                // staging-wave kernel with five-row tiles, two per workgroup; 14B decode step 6.035 -> 5.947 ms
+                default:
+                    if (mp == 1 && (size_t)c.d_ffn <= (size_t)GEMV_LDS_FLOATS / 2) rc = launch_down_staged<5, 2, 1>(g, pl.down_blocks, st);
+                    else rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down");
+                    break;
             }
             toc(RS_PHASE_DOWN, l);
             if (rc) return rc;
