@@ -6,19 +6,25 @@ A "step" is one ACCEPTED token of the live stitched run (Algorithm 1 driven from
 the host through the C ABI): it costs one or more model invocations - small-model
 decode steps (accepted or rejected), large-model catch-up prefills and decode
 steps.  All inputs (weights, prompt, logit-scale schedule) are seeded synthetic
-data resident in HBM before the timed region starts.
+data resident in HBM before the timed region starts, and BOTH models have
+processed the prompt before it starts (the large model's first participation,
+a prefill of the whole prompt, is set-up and is reported as such), so a timed
+window of any length measures steady-state stitched decoding.
 
 Prints ONE JSON line.  Extra objects:
   roofline      live HIP-event timing of the dominant kernel (the large model's
-                gate/up projection) against the 8 TB/s HBM peak
+                single-row gate/up projection, picked by name) against the
+                8 TB/s HBM peak, plus the whole-step fraction of each model
   per_model     decode ms/token of each model alone and its roofline fraction
   stitched      invocation mix of the timed region and its roofline fraction
-  cpu_baseline  the CPU oracle timed on this machine's cores on a small sample
+  latency_fit   Eq. 5-6 of the paper re-fitted to this machine's timings
+  cpu_baseline  the CPU oracle timed on this machine's cores on a bounded sample
 """
 from __future__ import annotations
 
 import argparse
 import ctypes as C
+import dataclasses
 import json
 import math
 import os
@@ -29,6 +35,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12   # bytes/s, MI355X published
+DTYPE = "bf16 weights, f32 activations and accumulation"
 
 
 def log(*a):
@@ -60,6 +67,166 @@ class HipEvents:
         return ms.value if rc == 0 else float("nan")
 
 
+def event_pair_overhead_ms(ev, stream, e0, e1):
+    """What two event records add to a bracket around ONE kernel: the same bracket around one launch of a
+    streaming kernel of about the same length (an in-place add over 2^24 floats, ~20 us), minus that kernel's
+    duration when 50 of them run back to back inside one bracket.  Median over 30 brackets.  An unprofiled run
+    gives 2.7-3.2 us; with a profiler attached every dispatch costs more and the figure no longer describes the
+    bracket, so a value outside 0..5 us is dropped (returns 0.0, False) and raw brackets are reported."""
+    import torch
+    cal_x = torch.zeros(1 << 24, device="cuda")
+    cal_s = torch.zeros(1 << 16, device="cuda")
+    sh = stream.cuda_stream
+    with torch.cuda.stream(stream):
+        for _ in range(5):
+            cal_x.add_(1.0)
+        singles = []
+        for _ in range(30):
+            for _ in range(4):
+                cal_s.add_(1.0)
+            ev.record(e0, sh)
+            cal_x.add_(1.0)
+            ev.record(e1, sh)
+            for _ in range(2):
+                cal_s.add_(1.0)
+            stream.synchronize()
+            singles.append(ev.elapsed_ms(e0, e1))
+        ev.record(e0, sh)
+        for _ in range(50):
+            cal_x.add_(1.0)
+        ev.record(e1, sh)
+        stream.synchronize()
+        over = sorted(singles)[len(singles) // 2] - ev.elapsed_ms(e0, e1) / 50
+    del cal_x, cal_s
+    if not 0.0 <= over <= 5e-3:
+        log(f"[bench] event-pair calibration gave {over * 1e3:.2f} us: not applied")
+        return 0.0, False
+    return over, True
+
+
+def time_phase(ev, P, model, phase, layer, run_once, sync, n, e0, e1):
+    """Mean time between an event pair that the library places around ONE kernel (phase, layer) of every call
+    `run_once(i)` makes on `model` (plain launches while the timer is armed)."""
+    P.rs_set_phase_timer(model.handle, phase, layer, e0, e1)
+    tot = 0.0
+    try:
+        for i in range(n + 2):
+            run_once(i)
+            sync()
+            if i >= 2:
+                tot += ev.elapsed_ms(e0, e1)
+    finally:
+        P.rs_set_phase_timer(model.handle, -1)
+    return tot / n
+
+
+def measured_traffic(P, shape_name, key):
+    """HBM bytes per launch of a kernel from the hardware-counter runs stored with the package
+    (FETCH_SIZE + WRITE_SIZE of the counter-run driver, scaled by a copy kernel of known size), or None."""
+    try:
+        with open(os.path.join(os.path.dirname(os.path.abspath(P.__file__)), "measured_traffic.json")) as f:
+            rec = json.load(f).get(shape_name, {}).get(key)
+        return rec["fetch_bytes"] + rec["write_bytes"] if rec else None
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def gateup_roofline(ev, P, model, shape, run_once, sync, rows, overhead_ms, overhead_ok, e0, e1, n=24):
+    """The `roofline` object: the gate/up projection of `model` (the largest kernel of a step: over half of a
+    layer's bytes) in a call of `rows` token rows, timed live with an event pair around that kernel."""
+    bracket_ms = time_phase(ev, P, model, P.binding.PHASE_GATEUP, shape.n_layers // 2, run_once, sync, n, e0, e1)
+    avg_s = (bracket_ms - overhead_ms) * 1e-3
+    nbytes = 2 * shape.d_ffn * shape.d_model * 2
+    name = f"k_gemv<GATEUP> ({shape.name}, 1 token row)" if rows == 1 else f"k_gemm_rows<GATEUP> ({shape.name}, {rows} token rows)"
+    return {"bound": "hbm", "kernel": name, "launches": n, "avg_us": round(avg_s * 1e6, 2),
+            "avg_us_between_events": round(bracket_ms * 1e3, 2),
+            "event_pair_overhead_us": round(overhead_ms * 1e3, 2) if overhead_ok else None,
+            "achieved": round(nbytes / avg_s / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+            "frac": round(nbytes / avg_s / HBM_PEAK, 4),
+            "traffic": measured_traffic(P, shape.name, "gateup_rows1") if rows == 1 else None,
+            "bytes_per_launch": nbytes,
+            "measured": "plain launches of the model's calls with one event pair around this kernel per call; avg_us = "
+                        "time between the events minus what the event records add to such a bracket (calibrated in this run)"}
+
+
+def oracle_sample(W, odec, wts, ctx, rows_list, k_layers=4, seed=77):
+    """Seconds per oracle invocation of the FULL model, for each row count in rows_list, at context `ctx`.
+
+    Bounded sample: the oracle (as it stands, fp64) runs on the first k_layers layers and on zero layers (embedding
+    + final norm + LM head only); a full invocation is the zero-layer time plus n_layers / k_layers times the
+    difference.  The K/V cache of the sample is filled with seeded noise up to `ctx` (the time does not depend on
+    the values)."""
+    import torch
+    from workloads.recipes import ModelWeights
+    shape = wts.shape
+    k = min(k_layers, shape.n_layers)
+    emb = wts.embed.to("cpu")
+    lm = emb if shape.tied_lm_head else wts.lm_head.to("cpu")
+    fn = wts.final_norm.to("cpu")
+    layers = [type(l)(*(getattr(l, f).to("cpu") for f in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down")))
+              for l in wts.layers[:k]]
+    out = {}
+    for n_l in (0, k):
+        sub_shape = dataclasses.replace(shape, n_layers=n_l)
+        sub = ModelWeights(sub_shape, emb, lm, fn, layers[:n_l])
+        om = odec.OracleModel(sub, max_ctx=ctx + max(rows_list) + 1, keep_fp64_weights=False)
+        if n_l:
+            noise = W.rng.normal(seed, 5, 0, n_l * shape.n_kv_heads * ctx * shape.head_dim).view(n_l, shape.n_kv_heads, ctx, shape.head_dim)
+            om.k_cache[:, 0, :, :ctx] = noise
+            om.v_cache[:, 0, :, :ctx] = noise
+        om.forward([1], ctx)                      # untimed: first touch of the caches and of the BLAS threads
+        for rows in rows_list:
+            t0 = time.perf_counter()
+            om.forward(list(range(1, rows + 1)), ctx)
+            out[(n_l, rows)] = time.perf_counter() - t0
+        del om
+    return {rows: out[(0, rows)] + (out[(k, rows)] - out[(0, rows)]) * shape.n_layers / k for rows in rows_list}, k
+
+
+def cpu_baseline(W, models, inv, steps, ctx):
+    """`cpu_baseline` object.  models: {tag: (model id, weights)}; inv: (model id, pos0, rows) of the timed region."""
+    import torch
+    from oracle import decoder as odec
+    torch.set_grad_enabled(False)
+    t_inv, ks = {}, {}
+    for tag, (mid, wts) in models.items():
+        t0 = time.time()
+        t_inv[mid], ks[tag] = oracle_sample(W, odec, wts, ctx, [1, 4])
+        log(f"[bench] oracle {tag}: 1-row invocation {t_inv[mid][1]:.2f}s, 4-row {t_inv[mid][4]:.2f}s at context {ctx} "
+            f"(extrapolated from {ks[tag]} layers; sample took {time.time() - t0:.1f}s)")
+    total = 0.0
+    for mid, _, rows in inv:
+        t1, t4 = t_inv[mid][1], t_inv[mid][4]
+        total += t1 + (t4 - t1) * (rows - 1) / 3.0
+    per_tok = total / max(steps, 1)
+    names = {tag: mid for tag, (mid, _) in models.items()}
+    return {"value": round(1.0 / per_tok, 4), "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": (f"the fp64 oracle timed on 1-row and 4-row invocations at context {ctx} over a noise-filled cache, on "
+                       f"{ {t: k for t, k in ks.items()} } layers of each model plus its LM head, scaled to the full layer count "
+                       "and to each invocation's row count, summed over the invocation mix of the timed GPU run "
+                       f"({len(inv)} invocations per {steps} tokens)"),
+            "s_per_invocation": {tag: {"rows1": round(t_inv[mid][1], 2), "rows4": round(t_inv[mid][4], 2)} for tag, mid in names.items()}}
+
+
+def fit_latency(samples):
+    """Least-squares fit of the paper's latency model (Eq. 5): T = a N_inf N_kv + b N_inf^2 + c N_inf + d over
+    samples (N_inf, N_kv, ms); Eq. 6 is its N_inf = 1 case.  Returns coefficients in ms and R^2."""
+    import numpy as np
+    a = np.array([[n * kv, n * n, n, 1.0] for n, kv, _ in samples], dtype=np.float64)
+    y = np.array([t for _, _, t in samples], dtype=np.float64)
+    coef, *_ = np.linalg.lstsq(a, y, rcond=None)
+    pred = a @ coef
+    ss_res, ss_tot = float(((y - pred) ** 2).sum()), float(((y - y.mean()) ** 2).sum())
+    return {"a": float(coef[0]), "b": float(coef[1]), "c": float(coef[2]), "d": float(coef[3]),
+            "r2": round(1.0 - ss_res / ss_tot, 4) if ss_tot > 0 else None, "samples": len(samples)}
+
+
+PAPER_LATENCY_A100_MS = {   # Section "Latency Regression Results" (one A100, vLLM engines): a, b, c, d in ms
+    "s15": (0.000021, 0.000231, -0.121046, 27.090929), "m7": (0.000027, 0.000031, -0.045256, 27.040801),
+    "m14": (0.000045, 0.000123, -0.082998, 45.118931),
+}
+
+
 def bench_single_model(args, wl) -> int:
     """Workload without a large model: the small model decodes alone after its prompt (no routing)."""
     import torch
@@ -89,13 +256,23 @@ def bench_single_model(args, wl) -> int:
     elapsed = time.perf_counter() - marks["t0"]
     ctx_mid = len(prompt) + args.warmup + args.steps // 2
     ideal = S.step_bytes(wl.slm, [ctx_mid]) / HBM_PEAK
+
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    over, ok = event_pair_overhead_ms(ev, pair.stream, e0, e1)
+    roofline = gateup_roofline(ev, P, slm, wl.slm, lambda i: pair._forward(SLM, ctx_mid + i, ctx_mid + i + 1, 2.0),
+                               pair.stream.synchronize, 1, over, ok, e0, e1)
+    roofline["step_frac"] = {"slm": round(ideal / (elapsed / args.steps), 4)}
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(W, {"slm": (SLM, w_s)}, [(SLM, ctx_mid, 1)] * args.steps, args.steps, ctx_mid)
     print(json.dumps({
         "metric": f"decode tokens/s at batch 1 ({wl.slm.name} shape alone)", "value": round(args.steps / elapsed, 2),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": args.workload, "slm": wl.slm.name, "batch": 1, "prompt_len": len(prompt), "max_ctx": max_ctx},
-        "roofline": None, "cpu_baseline": None,
+        "roofline": roofline, "cpu_baseline": cpu,
         "per_model": {"slm": {"shape": wl.slm.name, "ctx": ctx_mid, "ms_per_token_wall": round(elapsed / args.steps * 1e3, 4),
                               "roofline_ms": round(ideal * 1e3, 4), "roofline_frac": round(ideal / (elapsed / args.steps), 4)}},
     }), flush=True)
@@ -127,7 +304,13 @@ def bench_batched(args, wl) -> int:
     solo = batch.generate(prompts, 2.0, n_tau, single_model=SLM)
     tau = W.pick_tau([t.h_norm for r in solo for t in r.trace], wl.tau_percentile, 4e-3 / ln_v)
     log(f"[bench] small-model-only run of {n_tau} tokens per sequence; tau = {tau:.6f}")
+    # set-up: the large model processes every prompt before the timed region (its first participation)
+    t0 = time.perf_counter()
+    batch.prefill_prompts(LLM, prompts, tau)
+    torch.cuda.synchronize()
+    setup_ms = (time.perf_counter() - t0) * 1e3
     marks = {}
+    calls_log = []
 
     def progress(accepted_total):
         if "t0" not in marks and accepted_total >= args.warmup * nb:
@@ -135,32 +318,53 @@ def bench_batched(args, wl) -> int:
             marks["t0"] = time.perf_counter()
             marks["acc0"] = accepted_total
             marks["calls0"] = batch.calls
+            marks["log0"] = len(batch.call_log)
 
     batch.on_call = progress
-    runs = batch.generate(prompts, tau, n_total)
+    if args.warmup == 0:
+        progress(0)
+    runs = batch.generate(prompts, tau, n_total, llm_prefilled=True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - marks["t0"]
     accepted = sum(len(r.output) for r in runs) - marks["acc0"]
     calls = batch.calls - marks["calls0"]
+    calls_log = batch.call_log[marks["log0"]:]
     llm_tok = sum(1 for r in runs for t in r.trace if t.model == LLM and t.accept)
     all_tok = sum(len(r.output) for r in runs)
-    # roofline of one round in which every sequence takes a small-model step and the routed share a large-model step
-    ctx = [len(p) + n_total // 2 for p in prompts]
+    shapes = {SLM: wl.slm, LLM: wl.llm}
+    # algorithmic bytes of every library call of the timed region: weights once per call, each sequence's cache once
+    ideal_s = sum(S.step_bytes(shapes[m], ctxs, rows) for m, ctxs, rows in calls_log) / HBM_PEAK
     frac = llm_tok / max(all_tok, 1)
-    ideal_round = (S.step_bytes(wl.slm, ctx) + frac * S.step_bytes(wl.llm, ctx)) / HBM_PEAK
+
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    over, ok = event_pair_overhead_ms(ev, batch.stream, e0, e1)
+    lengths = [len(p) + n_total - 2 for p in prompts]
+    entries = [(b, lengths[b] - 1, 1) for b in range(nb)]
+    roofline = gateup_roofline(ev, P, llm, wl.llm, lambda i: batch.raw_call(LLM, entries, tau, lengths),
+                               batch.stream.synchronize, nb, over, ok, e0, e1, n=12)
+    roofline["step_frac"] = {"stitched": round(ideal_s / elapsed, 4)}
+    cpu = None
+    if not args.no_cpu_baseline:
+        ctx = sum(lengths) // nb
+        inv = [(m, 0, rows) for m, _, rows in calls_log]
+        cpu = cpu_baseline(W, {"slm": (SLM, w_s), "llm": (LLM, w_l)}, inv, accepted, ctx)
+        cpu["sample"] += "; a call over several sequences is costed as one oracle invocation of its total row count"
     print(json.dumps({
         "metric": f"stitched decode tokens/s over {nb} sequences ({wl.llm.name}+{wl.slm.name} shapes)",
         "value": round(accepted / elapsed, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / max(accepted, 1) * nb * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",
+        "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": args.workload, "slm": wl.slm.name, "llm": wl.llm.name, "batch": nb,
                    "prompt_lens": [len(p) for p in prompts], "tau": round(tau, 6), "tau_percentile": wl.tau_percentile,
                    "max_ctx": max_ctx},
-        "roofline": None, "cpu_baseline": None,
+        "roofline": roofline, "cpu_baseline": cpu,
+        "setup": {"llm_prompt_prefill_ms": round(setup_ms, 2)},
         "stitched": {"accepted_tokens": accepted, "library_calls": calls, "llm_token_frac": round(frac, 4),
                      "ms_per_call": round(elapsed / max(calls, 1) * 1e3, 4),
                      "rejected_slm_steps": sum(1 for r in runs for t in r.trace if not t.accept),
-                     "roofline_ms_per_round_estimate": round(ideal_round * 1e3, 4)},
+                     "roofline_ms_per_token": round(ideal_s / max(accepted, 1) * 1e3, 4),
+                     "roofline_frac": round(ideal_s / elapsed, 4)},
     }), flush=True)
     return 0
 
@@ -172,6 +376,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=64, help="accepted tokens before the timed region")
     ap.add_argument("--workload", default="cfg3_s15_m7")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-latency-fit", action="store_true")
     ap.add_argument("--tau-steps", type=int, default=None, help="small-model-only tokens used to place tau")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, three times: the "
@@ -235,6 +440,15 @@ def main() -> int:
             stats["dt"].append(now - stats["t_prev"])          # wall time of this invocation (call, sync, host loop)
         stats["t_prev"] = now
 
+    # ---- set-up: the large model's first participation (a prefill of the whole prompt, Section "KV Cache
+    # management") happens here, before the timed region, whatever the warm-up length is.  Its K/V rows are the
+    # ones the loop would have written at the first hand-over.
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pair.prefill_prompt(LLM, prompt, tau)
+    torch.cuda.synchronize()
+    setup_ms = (time.perf_counter() - t0) * 1e3
+    log(f"[bench] set-up: large-model prompt prefill of {len(prompt)} tokens in {setup_ms:.1f} ms")
     pair.on_invocation = on_inv
 
     # ---- live stitched run: warmup tokens, then the timed region
@@ -245,22 +459,30 @@ def main() -> int:
             torch.cuda.synchronize()
             stats["timed"] = True
             marks["t0"] = time.perf_counter()
+            stats["t_prev"] = marks["t0"]
         return False
 
     if args.warmup == 0:
         stats["timed"] = True
         torch.cuda.synchronize()
         marks["t0"] = time.perf_counter()
-    run = pair.generate(prompt, tau, args.warmup + args.steps, stop_after=stop_after)
+        stats["t_prev"] = marks["t0"]
+    run = pair.generate(prompt, tau, args.warmup + args.steps, stop_after=stop_after, llm_prefilled=True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - marks["t0"]
     pair.on_invocation = None
     tokens_per_s = args.steps / elapsed
 
-    # ---- invocation mix and stitched roofline of the timed region
+    # ---- invocation mix and stitched roofline of the timed region (an invocation longer than max_rows is fed in
+    # chunks, each of which reads the weights once)
     inv = stats["inv"]
     shapes = {SLM: wl.slm, LLM: wl.llm}
-    ideal_s = sum(S.step_bytes(shapes[m], [p0 + n], n) for m, p0, n in inv) / HBM_PEAK
+    mr = pair.max_rows
+
+    def inv_bytes(m, p0, n):
+        return sum(S.step_bytes(shapes[m], [p0 + c0 + min(mr, n - c0)], min(mr, n - c0)) for c0 in range(0, n, mr))
+
+    ideal_s = sum(inv_bytes(m, p0, n) for m, p0, n in inv) / HBM_PEAK
     n_llm_inv = sum(1 for m, _, _ in inv if m == LLM)
     n_slm_inv = len(inv) - n_llm_inv
     timed_trace = run.trace[-len(inv):] if inv else []
@@ -277,84 +499,6 @@ def main() -> int:
     by_span = {k: {sp: {"calls": c, "ms": round(t / c * 1e3, 3)} for sp, (c, t) in sorted(v.items(), key=lambda kv: (len(kv[0]), kv[0]))}
                for k, v in by_span.items()}
     switches = sum(1 for i in range(1, len(inv)) if inv[i][0] != inv[i - 1][0])
-
-    # ---- dominant kernel: the large model's gate/up projection.  The launch graphs of the timed
-    # region cannot carry event records, so the same invocations (same kernels, grids and data) are
-    # replayed right after it as plain launches with an event pair around that one kernel.
-    e0, e1 = ev.create(), ev.create()
-    gateup_bytes = 2 * wl.llm.d_ffn * wl.llm.d_model * 2
-    kern = {}
-    P.rs_set_phase_timer(llm.handle, P.binding.PHASE_GATEUP, wl.llm.n_layers // 2, e0, e1)
-    for m_, p0, n in [x for x in inv if x[0] == LLM][:96]:
-        if n > pair.max_rows:
-            continue
-        pair._forward(LLM, p0, p0 + n, tau)
-        pair.stream.synchronize()
-        name = "k_gemv<GATEUP,rows<=1>" if n == 1 else f"k_gemm_rows<GATEUP,NB={1 if n <= 16 else (2 if n <= 32 else 4)}>"
-        k = kern.setdefault(name, [0, 0.0])
-        k[0] += 1
-        k[1] += ev.elapsed_ms(e0, e1)
-    P.rs_set_phase_timer(llm.handle, -1)
-    # What the two event records themselves add to such a bracket: the same bracket around one launch of a
-    # streaming kernel of about the same length (an in-place add over 2^24 floats, ~20 us), minus that kernel's
-    # duration when 50 of them run back to back inside one bracket.  Medians over 30 brackets.
-    cal_x = torch.zeros(1 << 24, device=dev)
-    cal_s = torch.zeros(1 << 16, device=dev)
-    sh_cal = pair.stream.cuda_stream
-    with torch.cuda.stream(pair.stream):
-        for _ in range(5):
-            cal_x.add_(1.0)
-        singles = []
-        for _ in range(30):
-            for _ in range(4):
-                cal_s.add_(1.0)
-            ev.record(e0, sh_cal)
-            cal_x.add_(1.0)
-            ev.record(e1, sh_cal)
-            for _ in range(2):
-                cal_s.add_(1.0)
-            pair.stream.synchronize()
-            singles.append(ev.elapsed_ms(e0, e1))
-        ev.record(e0, sh_cal)
-        for _ in range(50):
-            cal_x.add_(1.0)
-        ev.record(e1, sh_cal)
-        pair.stream.synchronize()
-        event_overhead_ms = sorted(singles)[len(singles) // 2] - ev.elapsed_ms(e0, e1) / 50
-    del cal_x, cal_s
-    # an unprofiled run gives 2.7-3.2 us; with a profiler attached every dispatch costs more and the figure
-    # no longer describes the bracket, so a value outside 0..5 us is dropped and the raw bracket is reported
-    overhead_ok = 0.0 <= event_overhead_ms <= 5e-3
-    if not overhead_ok:
-        log(f"[bench] event-pair calibration gave {event_overhead_ms * 1e3:.2f} us: not applied")
-        event_overhead_ms = 0.0
-    dom = max(kern.items(), key=lambda kv: kv[1][1]) if kern else None
-    roofline = None
-    if dom:
-        name, (cnt, tot_ms) = dom
-        avg_events_s = tot_ms / cnt * 1e-3
-        avg_s = avg_events_s - event_overhead_ms * 1e-3
-        # HBM bytes per launch of that kernel from hardware-counter runs (FETCH_SIZE + WRITE_SIZE, scaled by a
-        # copy kernel of known size), stored with the package; only the single-row kernel has been counted
-        traffic = None
-        try:
-            with open(os.path.join(os.path.dirname(os.path.abspath(P.__file__)), "measured_traffic.json")) as f:
-                rec = json.load(f).get(wl.llm.name, {}).get("gateup_rows1")
-            if rec and name == "k_gemv<GATEUP,rows<=1>":
-                traffic = rec["fetch_bytes"] + rec["write_bytes"]
-        except OSError:
-            pass
-        roofline = {"bound": "hbm", "kernel": name, "launches": cnt, "avg_us": round(avg_s * 1e6, 2),
-                    "avg_us_between_events": round(avg_events_s * 1e6, 2),
-                    "event_pair_overhead_us": round(event_overhead_ms * 1e3, 2) if overhead_ok else None,
-                    "achieved": round(gateup_bytes / avg_s / 1e9, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                    "frac": round(gateup_bytes / avg_s / HBM_PEAK, 4), "traffic": traffic,
-                    "bytes_per_launch": gateup_bytes,
-                    "measured": "replay of the timed region's large-model invocations as plain launches, one event "
-                                "pair around this kernel per invocation; avg_us = time between the events minus what "
-                                "the event records add to such a bracket (calibrated in this run)",
-                    "all_variants": {k: {"launches": v[0], "avg_us": round((v[1] / v[0] - event_overhead_ms) * 1e3, 2)}
-                                     for k, v in kern.items()}}
 
     # ---- each model alone: decode steps at the end of the context, GPU time per step from an
     # event pair around every call (wall time per step, with the host round trip, beside it)
@@ -381,6 +525,19 @@ def main() -> int:
                           "roofline_ms": round(bytes_step / HBM_PEAK * 1e3, 4),
                           "roofline_frac": round(bytes_step / HBM_PEAK / (ms * 1e-3), 4)}
 
+    # ---- dominant kernel, picked by name: the large model's single-row gate/up projection (over half of the
+    # bytes of the largest model's step), in plain-launch decode steps at the end of the context
+    e0, e1 = ev.create(), ev.create()
+    event_overhead_ms, overhead_ok = event_pair_overhead_ms(ev, pair.stream, e0, e1)
+    p_roof = max_ctx - 40
+    roofline = gateup_roofline(ev, P, llm, wl.llm, lambda i: pair._forward(LLM, p_roof + i, p_roof + i + 1, tau),
+                               pair.stream.synchronize, 1, event_overhead_ms, overhead_ok, e0, e1)
+    # the whole decode step of each model against its own roofline (weights + KV bytes per token at 8 TB/s): the
+    # figure the target is stated on; the kernel above is the best-placed part of it
+    roofline["step_frac"] = {"slm": per_model["slm"]["roofline_frac"], "llm": per_model["llm"]["roofline_frac"],
+                             "min": min(per_model["slm"]["roofline_frac"], per_model["llm"]["roofline_frac"]),
+                             "stitched_run": round(ideal_s / elapsed, 4)}
+
     # ---- what the router costs: the fused LM head + softmax-state kernel of each model (event pair around that
     # kernel in a plain-launch decode step) beside the standalone router of the same rows (rs_route on logits in
     # HBM: two small kernels after an LM head that would have to write V floats and read them back).  The paper
@@ -400,53 +557,53 @@ def main() -> int:
     pair.stream.synchronize()
     router["standalone_rs_route_us"] = round(ev.elapsed_ms(a, b) / 20 * 1e3, 2)
     for tag, mid, mdl in (("slm", SLM, slm), ("llm", LLM, llm)):
-        P.rs_set_phase_timer(mdl.handle, P.binding.PHASE_LMHEAD, 0, e0, e1)
-        tot = 0.0
-        for i in range(8):
-            pair._forward(mid, max_ctx - 16 + i, max_ctx - 15 + i, tau)
-            pair.stream.synchronize()
-            tot += ev.elapsed_ms(e0, e1)
-        P.rs_set_phase_timer(mdl.handle, -1)
+        lm_ms = time_phase(ev, P, mdl, P.binding.PHASE_LMHEAD, 0,
+                           lambda i, mid=mid: pair._forward(mid, max_ctx - 16 + i, max_ctx - 15 + i, tau),
+                           pair.stream.synchronize, 8, e0, e1) - event_overhead_ms
         shape = wl.slm if mid == SLM else wl.llm
         lm_bytes = shape.vocab * shape.d_model * 2
-        lm_ms = tot / 8 - event_overhead_ms          # the same bracket as the roofline kernel's, same correction
         router[f"{tag}_lm_head_with_fused_router_us"] = round(lm_ms * 1e3, 2)
         router[f"{tag}_lm_head_gbps"] = round(lm_bytes / (lm_ms * 1e-3) / 1e9, 1)
     router["paper_separate_entropy_us"] = 28.0
 
-    # ---- CPU oracle on a bounded sample
+    # ---- latency model of the paper (Eq. 5-6) re-fitted to this machine: GPU time of calls with N_inf token rows
+    # on a cache of N_kv positions, each model; coefficients in ms beside the paper's A100 ones
+    latency_fit = None
+    if not args.no_latency_fit:
+        latency_fit = {}
+        for tag, mid, shape in (("slm", SLM, wl.slm), ("llm", LLM, wl.llm)):
+            samples = []
+            for n_inf in (1, 2, 4, 8, 16, 32, 64):
+                for n_kv in (256, max_ctx // 4, max_ctx // 2, max_ctx - 72):
+                    for rep in range(3):            # the last of three (graph captured by then)
+                        ev.record(a, sh)
+                        pair._forward(mid, n_kv, n_kv + n_inf, tau)
+                        ev.record(b, sh)
+                        pair.stream.synchronize()
+                    samples.append((n_inf, n_kv, ev.elapsed_ms(a, b)))
+            fit = fit_latency(samples)
+            fit["decode_ms_at"] = {str(kv): round(t, 4) for n, kv, t in samples if n == 1}
+            fit["paper_a100_ms"] = dict(zip("abcd", PAPER_LATENCY_A100_MS.get(shape.name, (None,) * 4)))
+            latency_fit[tag] = fit
+
+    # ---- CPU oracle on a bounded sample of the benchmarked work
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import decoder as odec
-        torch.set_grad_enabled(False)
-        t_inv = {}
-        for tag, wts in (("slm", w_s), ("llm", w_l)):
-            t0 = time.time()
-            w_cpu = wts.to("cpu")
-            om = odec.OracleModel(w_cpu, max_ctx=8, keep_fp64_weights=False)
-            t1 = time.time()
-            om.forward(prompt[:1], 0)
-            t_inv[tag] = time.time() - t1
-            log(f"[bench] oracle {tag}: one invocation {t_inv[tag]:.1f}s (+{t1 - t0:.1f}s to copy weights to the host)")
-            del om, w_cpu
-        per_tok = (n_slm_inv * t_inv["slm"] + n_llm_inv * t_inv["llm"]) / max(args.steps, 1)
-        cpu = {"value": round(1.0 / per_tok, 4), "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-               "sample": ("one 1-token invocation of each full-shape oracle model (fp64, weights converted from bf16 per "
-                          "layer), combined with the invocation mix of the timed GPU run: "
-                          f"{n_slm_inv} small-model and {n_llm_inv} large-model invocations per {args.steps} tokens"),
-               "s_per_invocation": {k: round(v, 2) for k, v in t_inv.items()}}
+        ctx_mid = len(prompt) + args.warmup + args.steps // 2
+        cpu = cpu_baseline(W, {"slm": (SLM, w_s), "llm": (LLM, w_l)}, inv, args.steps, ctx_mid)
 
     line = {
         "metric": ("stitched decode tokens/s at batch 1 (7B+1.5B shapes)" if args.workload == "cfg3_s15_m7"
                    else f"stitched decode tokens/s at batch 1 ({wl.llm.name}+{wl.slm.name} shapes)"),
         "value": round(tokens_per_s, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 weights, f32 activations and accumulation", "data": "synthetic",
+        "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": args.workload, "slm": wl.slm.name, "llm": wl.llm.name, "batch": 1,
                    "prompt_len": len(prompt), "tau": round(tau, 6), "tau_percentile": wl.tau_percentile,
                    "max_ctx": max_ctx},
         "roofline": roofline,
         "per_model": per_model,
+        "setup": {"llm_prompt_prefill_ms": round(setup_ms, 2), "llm_prompt_tokens": len(prompt)},
         "stitched": {"invocations": len(inv), "slm_invocations": n_slm_inv, "llm_invocations": n_llm_inv,
                      "llm_token_frac": round(llm_tokens / max(args.steps, 1), 4), "rejected_slm_steps": rejected,
                      "llm_span_mean": round(sum(spans) / max(len(spans), 1), 2), "llm_span_max": max(spans) if spans else 0,
@@ -454,6 +611,7 @@ def main() -> int:
                      "roofline_ms_per_token": round(ideal_s / args.steps * 1e3, 4),
                      "roofline_frac": round(ideal_s / elapsed, 4)},
         "router": router,
+        "latency_fit": latency_fit,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

@@ -100,16 +100,28 @@ class StitchedPair:
                 raise B.RsError(rc, B.rs_last_error())
             p += n
 
+    def prefill_prompt(self, model: int, prompt: Sequence[int], tau: float) -> None:
+        """Feed the whole prompt to `model` ahead of generate(..., llm_prefilled=True): the prefill a model does
+        when it first takes part (Section "KV Cache management"), moved out of the loop.  The K/V rows are the
+        ones the loop would write; the record of this call is not used."""
+        n0 = len(prompt)
+        self.seq_np[:n0] = np.asarray(prompt, dtype=np.int32)
+        self._forward(model, 0, n0, tau)
+        self.stream.synchronize()
+
     def generate(self, prompt: Sequence[int], tau: float, n_tokens: int, single_model: Optional[int] = None,
-                 keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None) -> StitchRun:
+                 keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None,
+                 llm_prefilled: bool = False) -> StitchRun:
         """Algorithm 1 until n_tokens tokens are accepted.  single_model = SLM or LLM runs that model
-        alone (every token accepted) while still reporting its entropies."""
+        alone (every token accepted) while still reporting its entropies.  llm_prefilled: the large model's
+        cache already holds the prompt (prefill_prompt), so its first participation only catches up with the
+        tokens accepted since."""
         n0 = len(prompt)
         if n0 + n_tokens > self.max_ctx + 1:
             raise ValueError("prompt + tokens exceed max_ctx")
         self.seq_np[:n0] = np.asarray(prompt, dtype=np.int32)
         length = n0
-        n_kv = [0, 0]
+        n_kv = [0, n0 if llm_prefilled else 0]
         active = SLM if single_model is None else single_model
         run = StitchRun()
         sync = self.stream.synchronize
@@ -175,6 +187,7 @@ class StitchedBatch:
         self._o_rec = self._o_scale + ns
         self._base = self.stage.data_ptr()
         self.calls = 0
+        self.call_log: List[tuple] = []                            # (model, context length per sequence, rows) of every call
         self.on_call: Optional[Callable[[int], None]] = None     # (accepted tokens so far, all sequences) after each call
         torch.cuda.synchronize()
 
@@ -182,7 +195,24 @@ class StitchedBatch:
         return self._base + 4 * index
 
     def _call(self, model: int, entries, tau: float, lengths) -> None:
-        """entries: (sequence, first position, row count), at most n_slots of them and max_rows rows in all."""
+        self.raw_call(model, entries, tau, lengths)
+        self.stream.synchronize()
+        self.calls += 1
+        self.call_log.append((model, [p0 + n for _, p0, n in entries], sum(n for _, _, n in entries)))
+
+    def prefill_prompts(self, model: int, prompts: Sequence[Sequence[int]], tau: float) -> None:
+        """Feed every prompt to `model` ahead of generate(..., llm_prefilled=True) (see StitchedPair.prefill_prompt)."""
+        self.seqs = [np.zeros(self.max_ctx + 1, dtype=np.int32) for _ in prompts]
+        lengths = [len(p) for p in prompts]
+        for b, p in enumerate(prompts):
+            self.seqs[b][:len(p)] = np.asarray(p, dtype=np.int32)
+            for c0 in range(0, len(p), self.max_rows):
+                self.raw_call(model, [(b, c0, min(self.max_rows, len(p) - c0))], tau, lengths)
+                self.stream.synchronize()
+
+    def raw_call(self, model: int, entries, tau: float, lengths) -> None:
+        """One library call, enqueued only.
+        entries: (sequence, first position, row count), at most n_slots of them and max_rows rows in all."""
         si, sf = self.stage_i, self.stage_f
         row = 0
         for i, (b, p0, n) in enumerate(entries):
@@ -203,11 +233,9 @@ class StitchedBatch:
                                         tau, model, self._ptr(self._o_rec), None, sh)
         if rc != 0:
             raise B.RsError(rc, B.rs_last_error())
-        self.stream.synchronize()
-        self.calls += 1
 
     def generate(self, prompts: Sequence[Sequence[int]], tau: float, n_tokens: int,
-                 single_model: Optional[int] = None) -> List[StitchRun]:
+                 single_model: Optional[int] = None, llm_prefilled: bool = False) -> List[StitchRun]:
         nb = len(prompts)
         if nb > len(self.scale_np):
             raise ValueError("more prompts than scale tables")
@@ -218,7 +246,7 @@ class StitchedBatch:
                 raise ValueError("prompt + tokens exceed max_ctx")
             self.seqs[b][:len(p)] = np.asarray(p, dtype=np.int32)
             lengths.append(len(p))
-        n_kv = [[0] * nb, [0] * nb]
+        n_kv = [[0] * nb, list(lengths) if llm_prefilled else [0] * nb]
         active = [SLM if single_model is None else single_model] * nb
         runs = [StitchRun() for _ in range(nb)]
         live = set(range(nb))
