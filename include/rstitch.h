@@ -199,6 +199,25 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
                    rs_route_out *d_out, void *d_scratch, size_t scratch_bytes,
                    void *stream);
 
+/* rs_route for callers that cannot allocate device memory or hand over a
+ * scratch buffer (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation).  Same arguments, kernels and results as rs_route, but
+ * the partial states go to a 256 KB array that lives inside the library's code
+ * object on every GPU it runs on (held until the process ends).  The call never
+ * allocates or frees; the first call on a device looks the array's device
+ * address up once (make that first call outside a graph capture).
+ *   n             1..64 rows; n * ceil(vocab / 1024, at most 128) partial
+ *                 states of 32 bytes must fit the array
+ * All calls on one GPU share the array: calls that overlap on one GPU (two
+ * streams, two threads) race; calls on one stream are ordered.  Nothing has to
+ * be cleared between calls (every state the merge reads is written by the same
+ * call).
+ * Errors: RS_EINVAL as rs_route; RS_ECAPACITY (n > 64, state count beyond the
+ * array, device ordinal >= 64); RS_EHIP. */
+rs_status rs_route_static(const float *d_logits, int32_t n, int32_t vocab,
+                          const float *d_logit_scale, float tau, int32_t active,
+                          rs_route_out *d_out, void *stream);
+
 /* Test aid: the single-kernel decode step separates its phases with grid-wide
  * waits that give up after `polls` polls (default 2^22, about a second) instead
  * of hanging; a tiny value forces that error path from the host.  0 restores the

@@ -70,6 +70,8 @@ def _load() -> C.CDLL:
     lib.rs_route_scratch_bytes.argtypes = [i32, i32]
     lib.rs_route.restype = i32
     lib.rs_route.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp, sz, vp]
+    lib.rs_route_static.restype = i32
+    lib.rs_route_static.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp]
     lib.rs_set_spin_limit.restype = i32
     lib.rs_set_spin_limit.argtypes = [vp, C.c_uint32]
     lib.rs_set_phase_timer.restype = i32
@@ -154,6 +156,10 @@ def rs_route(d_logits, n: int, vocab: int, d_logit_scale, tau: float, active: in
              stream=None) -> None:
     _check(lib.rs_route(_ptr(d_logits), n, vocab, _ptr(d_logit_scale), tau, active, _ptr(d_out), _ptr(d_scratch),
                         0 if d_scratch is None else d_scratch.numel() * d_scratch.element_size(), _stream(stream)))
+
+
+def rs_route_static(d_logits, n: int, vocab: int, d_logit_scale, tau: float, active: int, d_out, stream=None) -> None:
+    _check(lib.rs_route_static(_ptr(d_logits), n, vocab, _ptr(d_logit_scale), tau, active, _ptr(d_out), _stream(stream)))
 
 
 PHASE_QKV, PHASE_OPROJ, PHASE_GATEUP, PHASE_DOWN, PHASE_LMHEAD, PHASE_ATTN = range(6)

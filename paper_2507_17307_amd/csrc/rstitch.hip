@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -922,3 +923,62 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab, const float 
 }
 
 }  // extern "C"
+
+// ================================================================================================
+// rs_route for callers that cannot allocate: the partial softmax states live in a file-scope device
+// array instead of a caller-provided scratch buffer.  Every device the library runs on holds its own
+// copy of the array at its own address; that address is looked up once per device (with that device
+// current) and used from then on: the array's name is only a host-side stand-in for it.
+namespace {
+
+constexpr int ROUTE_STATIC_MAX_ROWS = 64;
+constexpr size_t ROUTE_STATIC_BYTES = (size_t)ROUTE_STATIC_MAX_ROWS * 128 * sizeof(rs::SoftPartial);   // 256 KB
+
+static __device__ __align__(256) unsigned char scratch[ROUTE_STATIC_BYTES];
+
+constexpr int ROUTE_STATIC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[ROUTE_STATIC_MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device
+rs_status route_static_scratch(void **out) {
+    int dev = -1;
+    RS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= ROUTE_STATIC_MAX_DEVICES) return fail(RS_ECAPACITY, "device ordinal %d is beyond the %d this call supports", dev, ROUTE_STATIC_MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        RS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(RS_EHIP, "the static scratch array has no device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RS_OK;
+}
+
+}  // namespace
+
+extern "C" rs_status rs_route_static(const float *d_logits, int32_t n, int32_t vocab, const float *d_logit_scale,
+                                     float tau, int32_t active, rs_route_out *d_out, void *stream) {
+    if (n < 1) return fail(RS_EINVAL, "n must be at least 1");
+    if (vocab < 2) return fail(RS_EINVAL, "vocab must be at least 2");
+    if (n > ROUTE_STATIC_MAX_ROWS)
+        return fail(RS_ECAPACITY, "n = %d exceeds the %d rows the static scratch array holds", n, ROUTE_STATIC_MAX_ROWS);
+    if (!d_logits || !d_out) return fail(RS_EINVAL, "null argument");
+    if (active != RS_SLM && active != RS_LLM) return fail(RS_EINVAL, "active must be RS_SLM or RS_LLM");
+    if ((uintptr_t)d_logits % 16) return fail(RS_EINVAL, "logits must be 16-byte aligned");
+    const int parts = route_parts(vocab);
+    if ((size_t)n * parts * sizeof(rs::SoftPartial) > ROUTE_STATIC_BYTES)
+        return fail(RS_ECAPACITY, "%d rows of %d partial states exceed the static scratch array", n, parts);
+    void *ptr = nullptr;
+    if (rs_status rc = route_static_scratch(&ptr)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    // every partial the merge reads is written by the first kernel of the same call: nothing to clear
+    hipLaunchKernelGGL(rs::k_route_partials, dim3(parts, n), dim3(256), 0, st, d_logits, vocab, d_logit_scale,
+                       (rs::SoftPartial *)ptr);
+    RS_LAUNCHED("route_partials");
+    hipLaunchKernelGGL(rs::k_route_merge, dim3(n), dim3(256), 0, st, (const rs::SoftPartial *)ptr, parts, vocab, tau,
+                       active, (const int *)nullptr, d_out);
+    RS_LAUNCHED("route_merge");
+    return RS_OK;
+}
