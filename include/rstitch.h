@@ -12,7 +12,8 @@
  *     the tokens produced since it last ran (Section "KV Cache management").
  * The decoder layer itself (RMSNorm, rotary embedding, grouped-query attention
  * over a KV cache, SwiGLU MLP, LM head; bf16 weights, fp32 accumulation) is the
- * public Qwen2-style block; the paper treats it as "a full forward pass".
+ * public Qwen2-style block; the paper does not describe it (Section
+ * "Preliminary" only states that every token costs one pass of the active model).
  *
  * General rules of this ABI
  *   - Every pointer argument says whether it is HOST or DEVICE memory.  The
@@ -54,7 +55,8 @@ extern "C" {
 
 typedef int32_t rs_status;
 #define RS_OK          0
-#define RS_EINVAL     (-1)  /* malformed argument (null pointer, bad shape, bad count)      */
+#define RS_EINVAL     (-1)  /* malformed argument (null pointer, bad count, a shape rule of
+                               rs_config violated: see there)                               */
 #define RS_ECAPACITY  (-2)  /* request exceeds what the model was created for               */
 #define RS_EHIP       (-3)  /* the HIP runtime reported an error (see rs_last_error)        */
 #define RS_ENOTIMPL   (-4)  /* valid request that this build does not support               */
@@ -72,20 +74,27 @@ typedef int32_t rs_status;
 #define RS_FLAG_ABORTED   32u  /* a bounded wait inside a kernel ran out: the step did not complete,
                                   the record is invalid and the model refuses further steps          */
 
+/* Shape rules (rs_workspace_bytes / rs_kv_bytes return 0 and rs_create_model returns
+ * RS_EINVAL when one is violated; rs_last_error names it):
+ *   d_model, d_ffn and n_q_heads*head_dim are multiples of 128; d_model and
+ *   n_q_heads*head_dim are at most 12288; d_ffn >= 128; head_dim is 32, 64 or 128;
+ *   n_kv_heads divides n_q_heads with at most 8 query heads per KV head; vocab >= 2;
+ *   max_ctx is a multiple of 8, at least 8; 1 <= max_seqs <= 8; 1 <= max_rows <= 64;
+ *   rms_eps > 0; rope_theta > 1. */
 typedef struct rs_config {
-    int32_t n_layers;
-    int32_t d_model;
-    int32_t n_q_heads;
-    int32_t n_kv_heads;    /* divides n_q_heads                                              */
+    int32_t n_layers;      /* >= 1                                                            */
+    int32_t d_model;       /* multiple of 128, <= 12288                                      */
+    int32_t n_q_heads;     /* n_q_heads * head_dim: multiple of 128, <= 12288                */
+    int32_t n_kv_heads;    /* divides n_q_heads; n_q_heads / n_kv_heads <= 8                 */
     int32_t head_dim;      /* 32, 64 or 128                                                  */
-    int32_t d_ffn;         /* multiple of 8                                                  */
+    int32_t d_ffn;         /* multiple of 128                                                */
     int32_t vocab;         /* >= 2                                                           */
     int32_t tied_lm_head;  /* informational; lm_head may simply alias embed                  */
-    int32_t max_ctx;       /* positions per sequence slot in the KV cache; multiple of 8     */
+    int32_t max_ctx;       /* positions per sequence slot in the KV cache; multiple of 8, >= 8 */
     int32_t max_seqs;      /* sequence slots in the KV cache (1..8)                          */
     int32_t max_rows;      /* most token rows one call may carry (1..64)                     */
-    float   rms_eps;
-    float   rope_theta;
+    float   rms_eps;       /* > 0                                                            */
+    float   rope_theta;    /* > 1                                                            */
 } rs_config;
 
 typedef struct rs_weights {
@@ -143,7 +152,8 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *weights,
                           void *workspace, size_t workspace_bytes,
                           rs_model **out);
 
-/* Frees the host handle only. */
+/* Frees the host handle and the launch graphs cached for it (after draining the
+ * device, since a replay may still be running); no device memory is touched. */
 rs_status rs_destroy_model(rs_model *model);
 
 /* Algorithm 1, "Decode": one new token for each of n_seqs sequences
@@ -217,31 +227,6 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
 rs_status rs_route_static(const float *d_logits, int32_t n, int32_t vocab,
                           const float *d_logit_scale, float tau, int32_t active,
                           rs_route_out *d_out, void *stream);
-
-/* Test aid: the single-kernel decode step separates its phases with grid-wide
- * waits that give up after `polls` polls (default 2^22, about a second) instead
- * of hanging; a tiny value forces that error path from the host.  0 restores the
- * default.  After a wait has given up the model is unusable (RS_FLAG_ABORTED on
- * every record) until it is created again. */
-rs_status rs_set_spin_limit(rs_model *model, uint32_t polls);
-
-/* Measurement aid (not part of the method): while armed, every forward call on
- * this model records `start_event` immediately before and `stop_event`
- * immediately after the launch of ONE kernel on the call's stream: the kernel of
- * phase `phase` (RS_PHASE_*) in layer `layer` (layer is ignored for
- * RS_PHASE_LMHEAD).  Both are caller-owned hipEvent_t handles passed as void*;
- * the caller reads them with hipEventElapsedTime after synchronising.
- * phase < 0 disarms.  While armed, calls run as plain launches (no launch-graph
- * replay, no single-kernel step), so that there is a kernel to bracket.
- * Errors: RS_EINVAL (null model/event, layer out of range). */
-#define RS_PHASE_QKV     0
-#define RS_PHASE_OPROJ   1
-#define RS_PHASE_GATEUP  2
-#define RS_PHASE_DOWN    3
-#define RS_PHASE_LMHEAD  4
-#define RS_PHASE_ATTN    5
-rs_status rs_set_phase_timer(rs_model *model, int32_t phase, int32_t layer,
-                             void *start_event, void *stop_event);
 
 #ifdef __cplusplus
 }

@@ -132,17 +132,9 @@ __host__ __device__ constexpr int gemv_seg(int K) { return K * MP <= GEMV_LDS_FL
 template <int MP>
 __host__ __device__ constexpr size_t gemv_lds_bytes(int K) { return (size_t)gemv_seg<MP>(K) * MP * 4 + 4096; }
 
-#ifdef RS_GEMV_TRACE
-__device__ long long g_gemv_trace[4096 * 8];
-#define GEMV_T(k) do { if (threadIdx.x == 0 && wg < 4096) g_gemv_trace[wg * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define GEMV_T(k) do { } while (0)
-#endif
-
 template <int MODE, int RT, int KS, int UNR, int MP, int PRE = 0>
 __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *smem, int wg, int nwg) {
     static_assert(PRE == 0 || MP == 1, "the early weight request exists for single-row calls only");
-    GEMV_T(0);
     float4 *xs = reinterpret_cast<float4 *>(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int K = a.K, M = a.m_rows;
@@ -255,7 +247,6 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
             if (lane == 0) red_ss[wave * MP + m] = ss;
         }
         __syncthreads();
-        GEMV_T(1);
 #pragma unroll
         for (int m = 0; m < MP; ++m)
             inv[m] = 1.0f / sqrtf((red_ss[0 * MP + m] + red_ss[1 * MP + m] + red_ss[2 * MP + m] + red_ss[3 * MP + m]) / (float)K + a.eps);
@@ -307,7 +298,6 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
         }
     };
     if (resident) { stage(0, K); __syncthreads(); }
-    GEMV_T(2);
 
     SoftState st[MP];
     float lm_scale[MP];
@@ -406,12 +396,10 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 accumulate(wp, k0 >> 3, (k0 >> 3) + c0, (k0 + len) >> 3, cstride, acc);
             }
         }
-        if (t == unit0) GEMV_T(3);
 #pragma unroll
         for (int r = 0; r < RT; ++r)
 #pragma unroll
             for (int m = 0; m < MP; ++m) acc[r][m] = wave_sum(acc[r][m]);
-        if (t == unit0) GEMV_T(4);
         if (KS > 1) {
             if (lane == 0) {
 #pragma unroll
@@ -428,7 +416,6 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                                 red[(parity * 4 + 2) * RT * MP + r * MP + m] + red[(parity * 4 + 3) * RT * MP + r * MP + m];
             parity ^= 1;
         }
-        if (t == unit0) GEMV_T(5);
         const bool writer = (KS == 1) ? (lane == 0) : (tid == 0);
         if (!writer) continue;
 
@@ -481,7 +468,6 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
             }
         }
     }
-    GEMV_T(6);
     if (MODE == G_LMHEAD) {
         // one partial per workgroup and token row: the four waves' states meet in LDS
         SoftPartial *sp = reinterpret_cast<SoftPartial *>(red);           // [4][MP], inside the 4 KB tail of the segment
@@ -696,13 +682,6 @@ __device__ __forceinline__ void split3(const float (&x)[8], bf16x8_t (&pl)[3]) {
 template <int HD>
 __host__ __device__ constexpr size_t attn_lds_bytes(int G = ATT_GMAX) { return (size_t)(4 * G * (HD + 4) + 2 * 4 * 16) * 4; }
 
-#ifdef RS_ATT_TRACE
-__device__ long long g_att_trace[4096 * 8];
-#define ATT_T(k) do { if (threadIdx.x == 0) g_att_trace[((kvh * S + split) * 8) + (k)] = wall_clock64(); } while (0)
-#else
-#define ATT_T(k) do { } while (0)
-#endif
-
 // Cache operands of one wave pass (ATT_WT = 16 tokens from t0): K rows as the A operand of the score
 // contraction, V^T rows as the A operand of the output contraction.  The loads are unconditional:
 // positions are clamped into the cache row (max_ctx is a multiple of 8, so a group of 4 positions
@@ -753,7 +732,6 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
     float (*l_lds)[16] = m_lds + 4;
     float *acc_lds = reinterpret_cast<float *>(smem + (size_t)2 * 4 * 16 * 4);          // [4 waves][G heads][HD+4]
 
-    ATT_T(0);
     int C = (a.max_ctx + S - 1) / S;
     C = ((C + ATT_BT - 1) / ATT_BT) * ATT_BT;
     const int t_begin = split * C;
@@ -802,7 +780,6 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
         for (int ds = 0; ds < NDS; ++ds) q_planes(ds, qB[ds]);
     }
 
-    ATT_T(1);
     float m_run = -INFINITY, l_run = 0.f;          // head j (replicated over the four kg groups)
     f32x4_t acc[NDB];                              // out[d = 16 db + 4 kg + r][head j]
 #pragma unroll
@@ -837,7 +814,6 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
             sc[r] = v;
             mx = fmaxf(mx, v);
         }
-        ATT_T(2);
         mx = fmaxf(mx, __shfl_xor(mx, 16, RS_WAVE));
         mx = fmaxf(mx, __shfl_xor(mx, 32, RS_WAVE));
         const float m_new = fmaxf(m_run, mx);                         // finite: the pass has at least one valid token
@@ -846,7 +822,6 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
         l_run *= alpha;
 #pragma unroll
         for (int db = 0; db < NDB; ++db) { acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha; }
-        ATT_T(3);
         // ---- P V: k slot (kg, r) is token t0 + 4 kg + r; slots (kg, 4..7) are unused (zero on both sides)
         float pv[8];
 #pragma unroll
@@ -872,7 +847,6 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
         }
         if (more) cur = nxt;
     }
-    ATT_T(4);
     // l_run so far covers this lane's own tokens: add the other three kg groups
     l_run += __shfl_xor(l_run, 16, RS_WAVE);
     l_run += __shfl_xor(l_run, 32, RS_WAVE);
@@ -909,7 +883,6 @@ __device__ __forceinline__ void attn_partial_unit(const AttnArgs &a, unsigned ch
         *reinterpret_cast<float4 *>(p + 4 + d) = O;
         if (d == 0) { p[0] = M; p[1] = L; }
     }
-    ATT_T(5);
 }
 
 template <int HD, bool UPFRONT, bool ONEPASS>

@@ -4,6 +4,7 @@
 // cos/sin table, which is input-independent and built once per model.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -14,6 +15,7 @@
 #include <vector>
 
 #include "../../include/rstitch.h"
+#include "../../include/rstitch_aids.h"
 #include "device_utils.h"
 #include "router.h"
 #include "model_kernels.h"
@@ -145,7 +147,9 @@ struct rs_model {
         int n_seqs, n_rows, active; float tau;
         const void *slot, *tok, *off, *pos, *scale, *out, *logits; hipStream_t st;
         hipGraph_t graph; hipGraphExec_t exec;
+        unsigned long long last_used;
     };
+    unsigned long long graph_clock = 0;
     std::vector<GraphEntry> graphs;
     std::vector<size_t> seen_once;                 // signatures launched eagerly once (ring buffer)
     size_t seen_next = 0;
@@ -175,7 +179,7 @@ template <int MODE, int RT, int KS, int UNR, int MP, int PRE = 0>
 rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *name) {
     const size_t lds = gemv_lds_bytes<MP>(a.K);
     if (lds > 64 * 1024) {
-        static bool raised = false;                       // per instantiation
+        static std::atomic<bool> raised{false};           // per instantiation; setting the attribute twice is harmless
         if (!raised) {
             hipError_t e = hipFuncSetAttribute((const void *)k_gemv<MODE, RT, KS, UNR, MP, PRE>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
@@ -193,7 +197,7 @@ template <int RT, int UNR, int PRE>
 rs_status launch_down_staged(GemvArgs &a, int blocks, hipStream_t st) {
     const size_t lds = down_staged_lds_bytes(a.K);
     if (lds > 64 * 1024) {
-        static bool raised = false;                       // per instantiation
+        static std::atomic<bool> raised{false};           // per instantiation; setting the attribute twice is harmless
         if (!raised) {
             hipError_t e = hipFuncSetAttribute((const void *)k_down_staged<RT, UNR, PRE>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
@@ -304,7 +308,7 @@ rs_status launch_gemm_r(GemmArgs &a, int blocks, hipStream_t st, const char *nam
     constexpr size_t lds = gemm_lds_bytes<MODE, NB, R, NW>();
     static_assert(lds <= 76 * 1024, "two workgroups per CU must fit");
     if (lds > 64 * 1024) {
-        static bool raised = false;                       // per instantiation
+        static std::atomic<bool> raised{false};           // per instantiation; setting the attribute twice is harmless
         if (!raised) {
             hipError_t e = hipFuncSetAttribute((const void *)k_gemm_rows<MODE, NB, R, NW>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -693,6 +697,7 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
         if (g.n_seqs == n_seqs && g.n_rows == n_rows && g.active == active && g.tau == tau && g.slot == d_seq_slot &&
             g.tok == d_tokens && g.off == d_span_off && g.pos == d_pos0 && g.scale == d_scale && g.out == d_out &&
             g.logits == d_logits && g.st == st) {
+            g.last_used = ++m->graph_clock;
             hipError_t e = hipGraphLaunch(g.exec, st);
             if (e != hipSuccess) return fail(RS_EHIP, "graph launch: %s", hipGetErrorString(e));
             return RS_OK;
@@ -721,12 +726,20 @@ rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, co
     hipGraphExec_t exec = nullptr;
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
     if (e != hipSuccess) { (void)hipGraphDestroy(graph); (void)hipGetLastError(); return eager(); }
-    if (m->graphs.size() >= 256) {                      // callers that never reuse buffers: stop hoarding
-        for (auto &g : m->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
-        m->graphs.clear();
+    if (m->graphs.size() >= 1024) {
+        // full (a batched driver has up to 8 x 64 signatures per model): the entry that was used longest ago goes;
+        // a launch of it may still be running on its stream, so that stream is drained first
+        size_t lru = 0;
+        for (size_t i = 1; i < m->graphs.size(); ++i)
+            if (m->graphs[i].last_used < m->graphs[lru].last_used) lru = i;
+        (void)hipStreamSynchronize(m->graphs[lru].st);
+        (void)hipGraphExecDestroy(m->graphs[lru].exec);
+        (void)hipGraphDestroy(m->graphs[lru].graph);
+        m->graphs[lru] = m->graphs.back();
+        m->graphs.pop_back();
     }
     m->graphs.push_back(rs_model::GraphEntry{n_seqs, n_rows, active, tau, d_seq_slot, d_tokens, d_span_off, d_pos0, d_scale,
-                                             d_out, d_logits, st, graph, exec});
+                                             d_out, d_logits, st, graph, exec, ++m->graph_clock});
     e = hipGraphLaunch(exec, st);
     if (e != hipSuccess) return fail(RS_EHIP, "graph launch: %s", hipGetErrorString(e));
     return RS_OK;
@@ -841,8 +854,11 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *w, void *kv_k,
 }
 
 rs_status rs_destroy_model(rs_model *model) {
-    if (model)
+    if (model) {
+        // a replay launched by the last call may still be running: drain the device before its graphs go
+        if (!model->graphs.empty()) (void)hipDeviceSynchronize();
         for (auto &g : model->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
+    }
     delete model;
     return RS_OK;
 }

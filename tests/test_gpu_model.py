@@ -17,10 +17,11 @@ from parity import check_invocation
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["kernel_per_phase", "single_kernel_step"], autouse=True)
+@pytest.fixture(params=["kernel_per_phase", "single_kernel_step"])
 def decode_path(request, monkeypatch):
-    """Every test runs twice: single-row steps as one kernel per phase (the default) and as one
-    persistent kernel with grid-wide waits (RSTITCH_DECODE=persistent, read when a model is created)."""
+    """Tests that take this fixture run twice: single-row steps as one kernel per phase (the default) and as one
+    experimental persistent kernel with grid-wide waits (RSTITCH_DECODE=persistent, read when a model is
+    created).  The full-size cases run the default path only."""
     if request.param == "single_kernel_step":
         monkeypatch.setenv("RSTITCH_DECODE", "persistent")
     else:
@@ -44,7 +45,7 @@ def pair_run(wl, n_tokens=None):
     return (ws, wl_), models, res, log, tau, scales
 
 
-def test_config1_tiny_pair_teacher_forced():
+def test_config1_tiny_pair_teacher_forced(decode_path):
     import paper_2507_17307_amd as P
     wl = W.WORKLOADS["cfg1_tiny_pair"]
     weights, oracle_models, res, ref_logits, tau, scales = pair_run(wl)
@@ -65,7 +66,7 @@ def test_config1_tiny_pair_teacher_forced():
             assert float((g - r).abs().max()) <= 2 ** -7 * float(r.abs().max()) + 1e-6
 
 
-def test_catchup_equals_sequential_decode_on_gpu():
+def test_catchup_equals_sequential_decode_on_gpu(decode_path):
     import paper_2507_17307_amd as P
     w = W.make_weights(W.TINY_L, 3, 1).to("cuda")
     toks = W.rng.randint(3, 77, 0, 40, 1024).tolist()
@@ -82,7 +83,7 @@ def test_catchup_equals_sequential_decode_on_gpu():
 
 
 @pytest.mark.parametrize("spans", [[1, 1, 1], [3, 1, 17, 2], [16, 16, 16, 16], [5, 33, 1, 1, 1, 1, 1, 2]])
-def test_batched_ragged_calls_match_per_sequence_oracle(spans):
+def test_batched_ragged_calls_match_per_sequence_oracle(spans, decode_path):
     """Several sequences in one call (ragged spans, distinct slots) against one oracle model per slot."""
     import paper_2507_17307_amd as P
     shape = W.TINY_L
@@ -142,7 +143,7 @@ def test_batched_decode_over_large_caches_matches_per_sequence_oracle():
             check_invocation(got[i], lg[i], ref, 0.6, router.SLM, where=f"step {step} seq {i}")
 
 
-def test_device_side_argument_errors_are_flagged_not_faulted():
+def test_device_side_argument_errors_are_flagged_not_faulted(decode_path):
     import paper_2507_17307_amd as P
     w = W.make_weights(W.TINY_S, 5, 0).to("cuda")
     m = P.Model(w, max_ctx=16, max_seqs=2, max_rows=8)
@@ -365,7 +366,7 @@ ODD_SHAPES = [
 
 
 @pytest.mark.parametrize("name,n_layers,d,n_q,n_kv,hd,ffn,vocab", ODD_SHAPES, ids=[s[0] for s in ODD_SHAPES])
-def test_other_head_shapes_decode_and_catchup_against_oracle(name, n_layers, d, n_q, n_kv, hd, ffn, vocab):
+def test_other_head_shapes_decode_and_catchup_against_oracle(name, n_layers, d, n_q, n_kv, hd, ffn, vocab, decode_path):
     """Head sizes and group sizes the five configurations do not use (head_dim 64, G = 1, 3, 8): a prompt fed as
     catch-up calls, single-token steps, a ragged two-sequence call and a 40-row span, each against the oracle."""
     import paper_2507_17307_amd as P
