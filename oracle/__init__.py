@@ -12,7 +12,8 @@ Modules
   router   normalised token entropy (Eq. 1), switching rule (Eq. 2)
   decoder  RMSNorm, rotary embedding, grouped-query attention over a KV cache,
            SwiGLU MLP, LM head; one forward invocation over a span of tokens
-  stitch   the inference loop of Algorithm 1 with two KV caches
+  stitch   the inference loop of Algorithm 1 with two KV caches (and its R-Stitch+ branch)
+  router_plus  the learned router of R-Stitch+ (six residual FFN blocks, LayerNorm, two outputs)
 
 Parity status: every function here is pinned by ``tests/test_oracle_*.py``
 (closed forms, brute force, an independent library implementation of the same

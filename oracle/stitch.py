@@ -104,3 +104,36 @@ def decoder_forward(models, scale_of_pos: Callable[[int], float], log: Optional[
         return router.greedy_token(logits), router.normalised_entropy(logits)
 
     return forward
+
+
+def generate_plus(prompt: Sequence[int], forward_state, router_says_llm: Callable[[object], bool], tau: float,
+                  n_tokens: int, max_invocations: Optional[int] = None) -> StitchResult:
+    """Algorithm 1 with its R-Stitch+ branch: as :func:`generate`, but a small-model step whose
+    entropy exceeds tau hands over only if the router, given that step's hidden state, picks the
+    large model; otherwise the token is kept and the small model goes on.
+
+    ``forward_state(model, span, pos0)`` returns (token, normalised entropy, state);
+    ``router_says_llm(state)`` is consulted only for small-model steps above tau.
+    """
+    seq = list(prompt)
+    n_kv = [0, 0]
+    active = SLM
+    res = StitchResult()
+    while len(res.output) < n_tokens:
+        if max_invocations is not None and len(res.trace) >= max_invocations:
+            break
+        pos0 = n_kv[active]
+        span = seq[pos0:]
+        token, h, state = forward_state(active, span, pos0)
+        n_kv[active] = len(seq)
+        hi = h > tau
+        if active == SLM and hi and router_says_llm(state):
+            res.trace.append(Invocation(active, pos0, span, token, h, True, False))
+            active = LLM
+            continue
+        res.trace.append(Invocation(active, pos0, span, token, h, hi, True))
+        if active == LLM and not hi:
+            active = SLM
+        seq.append(token)
+        res.output.append(token)
+    return res

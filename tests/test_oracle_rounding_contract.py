@@ -96,6 +96,16 @@ def test_rounding_every_matmul_input_makes_equivalent_runs_diverge_beyond_the_to
         assert min(d) >= 1e-2, f"{n_layers} layers: {d}"           # measured 1.3e-2 .. 3.4e-2
 
 
+def test_kv_rounding_alone_amplifies_fp32_sized_differences_past_a_millinat():
+    """The rounding the workload does prescribe (bf16 K/V rows) is itself an amplifier: two oracle runs of a 28-layer
+    model whose inputs differ by 3 parts in 10^6 - what fp32 accumulation over a few thousand terms leaves - end up
+    with logits 5e-4 .. 4.4e-3 apart.  A call that prefills many rows at once on a deep model therefore cannot be
+    compared with another implementation's to 1e-3 nats as a whole; the GPU parity tests compare the rows written
+    and the last row's distribution given those rows instead."""
+    d = divergences(decoder.OracleModel, 28, 3e-6)
+    assert max(d) >= 1e-3 and max(d) <= 2e-2, d
+
+
 def test_rounding_only_the_kv_rows_keeps_equivalent_runs_an_order_of_magnitude_closer():
     for (n_layers, eps), cap in zip(CASES, (5e-4, 2e-3)):
         d = divergences(decoder.OracleModel, n_layers, eps)

@@ -14,5 +14,5 @@ from .shapes import (  # noqa: F401
 )
 from .recipes import (  # noqa: F401
     Workload, WORKLOADS, ModelWeights, make_weights, make_prompt, logit_scale,
-    pick_tau,
+    pick_tau, RouterWeights, make_router_weights,
 )

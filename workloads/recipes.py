@@ -34,6 +34,7 @@ _STREAM_PROMPT = (1 << 20)               # + sequence index
 _STREAM_SCALE = (1 << 20) + 1 * 4096     # + sequence index
 _STREAM_PROMPT_LEN = (1 << 20) + 2 * 4096
 _STREAM_MISC = (1 << 20) + 3 * 4096      # + caller's tag
+_STREAM_ROUTER = (1 << 20) + 4 * 4096    # + tensor index
 
 
 def _stream(role: int, layer: int, kind: int) -> int:
@@ -171,3 +172,43 @@ def pick_tau(h_norm: Sequence[float], percentile: float, min_gap: float) -> floa
         if v[j + 1] - v[j] >= min_gap:
             return 0.5 * (v[j] + v[j + 1])
     return 0.5 * (v[k] + v[k + 1])
+
+
+@dataclass
+class RouterWeights:
+    """Weights of the R-Stitch+ router (Section "Architecture and Overhead of Router": six residual feed-forward
+    blocks, a normalisation, a two-output linear layer).  All bf16.  Data holder only."""
+    w1: List[torch.Tensor]     # 6 x [r, d]
+    b1: List[torch.Tensor]     # 6 x [r]
+    w2: List[torch.Tensor]     # 6 x [d, r]
+    b2: List[torch.Tensor]     # 6 x [d]
+    ln_gain: torch.Tensor      # [d]
+    ln_bias: torch.Tensor      # [d]
+    w_head: torch.Tensor       # [2, d]
+    b_head: torch.Tensor       # [2]
+
+    def tensors(self) -> List[torch.Tensor]:
+        return self.w1 + self.b1 + self.w2 + self.b2 + [self.ln_gain, self.ln_bias, self.w_head, self.b_head]
+
+    def n_params(self) -> int:
+        return sum(t.numel() for t in self.tensors())
+
+    def to(self, device) -> "RouterWeights":
+        mv = lambda ts: [t.to(device) for t in ts]  # noqa: E731
+        return RouterWeights(mv(self.w1), mv(self.b1), mv(self.w2), mv(self.b2), self.ln_gain.to(device),
+                             self.ln_bias.to(device), self.w_head.to(device), self.b_head.to(device))
+
+
+def make_router_weights(d: int, r: int, seed: int, device="cpu") -> RouterWeights:
+    """Seeded synthetic router (the trained one of the paper does not exist offline): matrices N(0, 0.05), biases
+    N(0, 0.05), LayerNorm gain 1 + N(0, 0.1) and bias N(0, 0.1), all rounded to bf16."""
+    def draw(idx, count, std, shift=0.0):
+        z = rng.normal(seed, _STREAM_ROUTER + idx, 0, count, device)
+        return (shift + std * z).to(torch.float32).to(torch.bfloat16)
+    w = RouterWeights([], [], [], [], draw(60, d, 0.1, 1.0), draw(61, d, 0.1), draw(62, 2 * d, 0.05).view(2, d), draw(63, 2, 0.05))
+    for i in range(6):
+        w.w1.append(draw(4 * i, r * d, 0.05).view(r, d))
+        w.b1.append(draw(4 * i + 1, r, 0.05))
+        w.w2.append(draw(4 * i + 2, d * r, 0.05).view(d, r))
+        w.b2.append(draw(4 * i + 3, d, 0.05))
+    return w
