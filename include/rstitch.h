@@ -73,6 +73,8 @@ typedef int32_t rs_status;
 #define RS_FLAG_BADARG    16u  /* a device-side position/token/slot was out of range; record invalid */
 #define RS_FLAG_ABORTED   32u  /* a bounded wait inside a kernel ran out: the step did not complete,
                                   the record is invalid and the model refuses further steps          */
+#define RS_FLAG_ROUTER_STAY 64u /* R-Stitch+: HI on the small model, but the learned router chose to
+                                  stay: ACCEPT is set and NEXT_LLM cleared (rs_route_plus)            */
 
 /* Shape rules (rs_workspace_bytes / rs_kv_bytes return 0 and rs_create_model returns
  * RS_EINVAL when one is violated; rs_last_error names it):
@@ -208,6 +210,45 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
                    const float *d_logit_scale, float tau, int32_t active,
                    rs_route_out *d_out, void *d_scratch, size_t scratch_bytes,
                    void *stream);
+
+/* The learned router of R-Stitch+ (Section "RL-based Routing with Latency-aware
+ * Reward"; Algorithm 1, R-Stitch+ branch; Section "Architecture and Overhead of
+ * Router"): when a small-model step is above tau, the hidden state of that step
+ * goes through six residual feed-forward blocks x <- x + W2 gelu(W1 x + b1) + b2
+ * (GELU in its erf form), a LayerNorm and a linear layer with two outputs, and
+ * the hand-over happens only if output 1 ("large model") exceeds output 0.
+ * All tensors DEVICE bf16; the pointer arrays are HOST arrays of 6 DEVICE pointers. */
+typedef struct rs_router_weights {
+    int32_t d;                 /* input width = d_model of the model whose state is routed; multiple of 8 */
+    int32_t r;                 /* bottleneck width of a block: multiple of 8, at most 64                  */
+    float   ln_eps;            /* > 0                                                                     */
+    const void *const *w1;     /* [r, d]  */
+    const void *const *b1;     /* [r]     */
+    const void *const *w2;     /* [d, r]  */
+    const void *const *b2;     /* [d]     */
+    const void *ln_gain;       /* [d]     */
+    const void *ln_bias;       /* [d]     */
+    const void *w_head;        /* [2, d]: row 0 = stay on the small model, row 1 = switch to the large one */
+    const void *b_head;        /* [2]     */
+} rs_router_weights;
+
+/* Apply the router to the records a forward call has just produced.
+ *   model     the model that made the call (its workspace still holds the final
+ *             hidden state, before the final RMSNorm, of the last row of every
+ *             sequence of that call), or NULL when d_hidden is given
+ *   d_hidden  DEVICE fp32 [n_seqs, w->d] hidden states, or NULL to take the model's
+ *   active    RS_SLM / RS_LLM as in the forward call; records of the large model
+ *             are never changed (Algorithm 1 consults the router on the small model only)
+ *   d_out     DEVICE (or pinned host) rs_route_out[n_seqs] of that call, updated in
+ *             place: a record with RS_FLAG_HI whose router output prefers "stay"
+ *             gets RS_FLAG_ACCEPT | RS_FLAG_ROUTER_STAY and loses RS_FLAG_NEXT_LLM
+ *   d_router_logits  DEVICE fp32 [n_seqs, 2] or NULL: the two outputs
+ * Enqueue it on the stream of the forward call, before the next call on that model.
+ * Errors: RS_EINVAL (null pointer, both or neither of model / d_hidden, d != the
+ * model's d_model, r not a multiple of 8 or above 64), RS_ECAPACITY (n_seqs). */
+rs_status rs_route_plus(rs_model *model, const float *d_hidden, int32_t n_seqs,
+                        const rs_router_weights *w, int32_t active,
+                        rs_route_out *d_out, float *d_router_logits, void *stream);
 
 /* rs_route for callers that cannot allocate device memory or hand over a
  * scratch buffer (code under HIP graph capture, tight serving loops, harnesses

@@ -16,7 +16,7 @@ from typing import List, Optional, Sequence
 import torch
 
 RS_SLM, RS_LLM = 0, 1
-FLAG_HI, FLAG_ACCEPT, FLAG_NEXT_LLM, FLAG_NONFINITE, FLAG_BADARG, FLAG_ABORTED = 1, 2, 4, 8, 16, 32
+FLAG_HI, FLAG_ACCEPT, FLAG_NEXT_LLM, FLAG_NONFINITE, FLAG_BADARG, FLAG_ABORTED, FLAG_ROUTER_STAY = 1, 2, 4, 8, 16, 32, 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -40,6 +40,12 @@ class RsConfig(C.Structure):
 class _RsWeights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + [
         (n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down")]
+
+
+class _RsRouterWeights(C.Structure):
+    _fields_ = [("d", C.c_int32), ("r", C.c_int32), ("ln_eps", C.c_float)] + [
+        (n, C.POINTER(C.c_void_p)) for n in ("w1", "b1", "w2", "b2")] + [
+        (n, C.c_void_p) for n in ("ln_gain", "ln_bias", "w_head", "b_head")]
 
 
 def _load() -> C.CDLL:
@@ -70,6 +76,8 @@ def _load() -> C.CDLL:
     lib.rs_route_scratch_bytes.argtypes = [i32, i32]
     lib.rs_route.restype = i32
     lib.rs_route.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp, sz, vp]
+    lib.rs_route_plus.restype = i32
+    lib.rs_route_plus.argtypes = [vp, vp, i32, C.POINTER(_RsRouterWeights), i32, vp, vp, vp]
     lib.rs_route_static.restype = i32
     lib.rs_route_static.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp]
     lib.rs_set_spin_limit.restype = i32
@@ -160,6 +168,27 @@ def rs_route(d_logits, n: int, vocab: int, d_logit_scale, tau: float, active: in
 
 def rs_route_static(d_logits, n: int, vocab: int, d_logit_scale, tau: float, active: int, d_out, stream=None) -> None:
     _check(lib.rs_route_static(_ptr(d_logits), n, vocab, _ptr(d_logit_scale), tau, active, _ptr(d_out), _stream(stream)))
+
+
+class RouterPlus:
+    """Marshalled rs_router_weights: keeps the device tensors and the pointer arrays alive.
+    weights: object with w1, b1, w2, b2 (lists of six bf16 device tensors), ln_gain, ln_bias, w_head, b_head."""
+
+    def __init__(self, weights, ln_eps: float = 1e-5):
+        self.weights = weights
+        self._arrs = {n: (C.c_void_p * 6)(*[t.data_ptr() for t in getattr(weights, n)]) for n in ("w1", "b1", "w2", "b2")}
+        r, d = weights.w1[0].shape
+        self.struct = _RsRouterWeights(d, r, ln_eps, *[C.cast(self._arrs[n], C.POINTER(C.c_void_p)) for n in ("w1", "b1", "w2", "b2")],
+                                       weights.ln_gain.data_ptr(), weights.ln_bias.data_ptr(), weights.w_head.data_ptr(),
+                                       weights.b_head.data_ptr())
+
+
+def rs_route_plus(handle: Optional[int], d_hidden, n_seqs: int, router: RouterPlus, active: int, d_out,
+                  d_router_logits=None, stream=None) -> None:
+    """d_out: tensor or raw address of the records to update."""
+    out = d_out if isinstance(d_out, int) else _ptr(d_out)
+    _check(lib.rs_route_plus(handle, _ptr(d_hidden), n_seqs, C.byref(router.struct), active, out,
+                             _ptr(d_router_logits), _stream(stream)))
 
 
 PHASE_QKV, PHASE_OPROJ, PHASE_GATEUP, PHASE_DOWN, PHASE_LMHEAD, PHASE_ATTN = range(6)

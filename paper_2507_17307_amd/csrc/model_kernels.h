@@ -621,6 +621,69 @@ __global__ void __launch_bounds__(512, 4) k_down_staged(GemvArgs a) {      // fo
 }
 
 // ------------------------------------------------------------------------------------------------
+// Single-row down projection (h += W_down . act) without any staging: the four waves of a workgroup
+// split K as above, and every lane reads the eight activation values of a chunk straight from
+// global memory next to the RT weight rows of that chunk.  The activation vector (tens of KB) is
+// the same for every workgroup, so those reads are served by the CU's cache and the L2; they cost
+// 32 bytes per lane and chunk against RT x 16 bytes of weights, but there is no copy into LDS, no
+// barrier before the weight stream starts and no LDS footprint that limits the workgroups per CU.
+// grid: workgroups share the ceil(N / RT) row tiles in contiguous ranges.
+// ------------------------------------------------------------------------------------------------
+template <int RT, int UNR>
+__global__ void __launch_bounds__(256) k_down_direct(GemvArgs a) {
+    __shared__ float red[2][4][RT];
+    const int K = a.K, n_chunks = K >> 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wg = blockIdx.x, nwg = gridDim.x;
+    const int n_tiles = (a.N + RT - 1) / RT;
+    const int t_lo = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)nwg), t_hi = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)nwg);
+    const int c0 = wave * 64 + lane, cstride = 256;
+    const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in);
+    int parity = 0;
+    for (int t = t_lo; t < t_hi; ++t) {
+        float acc[RT], epi[RT];
+        const uint4 *wp[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const int row = min(t * RT + r, a.N - 1);
+            wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)row * K);
+            acc[r] = 0.f;
+            epi[r] = a.h_out[row];                                         // requested ahead of the weight stream
+        }
+#pragma unroll UNR
+        for (int c = c0; c < n_chunks; c += cstride) {
+            uint4 wv[RT];
+#pragma unroll
+            for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
+            const float4 xa = x4[2 * c], xb = x4[2 * c + 1];
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const uint4 w = wv[r];
+                float v = acc[r];
+                v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
+                v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
+                acc[r] = v;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) red[parity][wave][r] = acc[r];
+        }
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const int row = t * RT + r;
+                if (row < a.N) a.h_out[row] = epi[r] + (red[parity][0][r] + red[parity][1][r] + red[parity][2][r] + red[parity][3][r]);
+            }
+        }
+        parity ^= 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Split-K grouped-query decode attention in two kernels.
 //
 // k_attn_partial: grid (n_slices, n_kv_heads, n_rows), block 256.  A workgroup owns one KV head,

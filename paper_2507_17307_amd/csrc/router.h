@@ -82,4 +82,106 @@ k_route_merge(const SoftPartial *__restrict__ parts, int n_parts, int vocab, flo
     route_merge_row(parts, n_parts, vocab, tau, active, row_bad, out, blockIdx.x, sh);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Router of R-Stitch+ (Section "Architecture and Overhead of Router"; Algorithm 1, R-Stitch+ branch):
+// six residual feed-forward blocks x <- x + W2 gelu(W1 x + b1) + b2 with a bottleneck of r channels,
+// a LayerNorm, a linear layer with two outputs (0 = stay on the small model, 1 = switch to the large
+// one).  One workgroup of 256 threads per sequence; x (fp32, d values) lives in LDS; weights are bf16,
+// accumulation fp32.  The record of the sequence is updated in place: a small-model step above tau
+// whose router output prefers "stay" keeps its token and stays (RS_FLAG_ROUTER_STAY); every other
+// record is left as the entropy rule made it.
+// ------------------------------------------------------------------------------------------------
+constexpr int ROUTER_BLOCKS = 6;
+constexpr int ROUTER_RMAX = 64;
+
+struct RouterPlusArgs {
+    const uint16_t *w1[ROUTER_BLOCKS], *b1[ROUTER_BLOCKS], *w2[ROUTER_BLOCKS], *b2[ROUTER_BLOCKS];
+    const uint16_t *ln_gain, *ln_bias, *w_head, *b_head;
+    int d, r;
+    float ln_eps;
+    const float *hidden; int ld_hidden;       // rows of d floats, ld_hidden apart
+    const int *gather;                         // row of sequence b inside `hidden`, or null (= b)
+    int active;
+    rs_route_out *out;                         // [n_seqs], updated in place
+    float *logits;                             // [n_seqs, 2] or null
+};
+
+__device__ __forceinline__ float block_sum(float v, float *sh4) {        // 256 threads; sh4: 4 floats of LDS
+    v = wave_sum(v);
+    __syncthreads();                                                      // sh4 may still be read from the last call
+    if ((threadIdx.x & 63) == 0) sh4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sh4[0] + sh4[1] + sh4[2] + sh4[3];
+}
+
+// dynamic LDS: d floats
+__global__ void __launch_bounds__(256) k_router_plus(RouterPlusArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *x = reinterpret_cast<float *>(smem);
+    __shared__ float t_sh[ROUTER_RMAX];
+    __shared__ float red[4];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int d = a.d, r = a.r;
+    const float *src = a.hidden + (size_t)(a.gather ? a.gather[b] : b) * a.ld_hidden;
+    for (int i = tid; i < d; i += 256) x[i] = src[i];
+    __syncthreads();
+    for (int blk = 0; blk < ROUTER_BLOCKS; ++blk) {
+        // t = gelu(W1 x + b1): wave w takes the rows w, w + 4, ...; lanes stride over d in chunks of 8
+        for (int row = wave; row < r; row += 4) {
+            const uint4 *wp = reinterpret_cast<const uint4 *>(a.w1[blk] + (size_t)row * d);
+            float acc = 0.f;
+            for (int c = lane; c < (d >> 3); c += 64) {
+                const uint4 w = wp[c];
+                const float4 xa = *reinterpret_cast<const float4 *>(x + 8 * c), xb = *reinterpret_cast<const float4 *>(x + 8 * c + 4);
+                acc = fmaf(bf16_lo(w.x), xa.x, acc); acc = fmaf(bf16_hi(w.x), xa.y, acc); acc = fmaf(bf16_lo(w.y), xa.z, acc); acc = fmaf(bf16_hi(w.y), xa.w, acc);
+                acc = fmaf(bf16_lo(w.z), xb.x, acc); acc = fmaf(bf16_hi(w.z), xb.y, acc); acc = fmaf(bf16_lo(w.w), xb.z, acc); acc = fmaf(bf16_hi(w.w), xb.w, acc);
+            }
+            acc = wave_sum(acc);
+            if (lane == 0) {
+                const float z = acc + bf16_to_f32(a.b1[blk][row]);
+                t_sh[row] = 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+            }
+        }
+        __syncthreads();
+        // x += W2 t + b2: one output channel per thread and round; a row of W2 is r bf16 values (r a multiple of 8)
+        for (int i = tid; i < d; i += 256) {
+            const uint4 *wp = reinterpret_cast<const uint4 *>(a.w2[blk] + (size_t)i * r);
+            float acc = bf16_to_f32(a.b2[blk][i]);
+            for (int c = 0; c < (r >> 3); ++c) {
+                const uint4 w = wp[c];
+                const float *t = t_sh + 8 * c;
+                acc = fmaf(bf16_lo(w.x), t[0], acc); acc = fmaf(bf16_hi(w.x), t[1], acc); acc = fmaf(bf16_lo(w.y), t[2], acc); acc = fmaf(bf16_hi(w.y), t[3], acc);
+                acc = fmaf(bf16_lo(w.z), t[4], acc); acc = fmaf(bf16_hi(w.z), t[5], acc); acc = fmaf(bf16_lo(w.w), t[6], acc); acc = fmaf(bf16_hi(w.w), t[7], acc);
+            }
+            x[i] += acc;
+        }
+        __syncthreads();
+    }
+    // LayerNorm (mean, then the mean of squared deviations), then the two outputs
+    float s = 0.f;
+    for (int i = tid; i < d; i += 256) s += x[i];
+    const float mu = block_sum(s, red) / (float)d;
+    float q = 0.f;
+    for (int i = tid; i < d; i += 256) { const float dv = x[i] - mu; q = fmaf(dv, dv, q); }
+    const float inv = 1.0f / sqrtf(block_sum(q, red) / (float)d + a.ln_eps);
+    float o0 = 0.f, o1 = 0.f;
+    for (int i = tid; i < d; i += 256) {
+        const float y = (x[i] - mu) * inv * bf16_to_f32(a.ln_gain[i]) + bf16_to_f32(a.ln_bias[i]);
+        o0 = fmaf(bf16_to_f32(a.w_head[i]), y, o0);
+        o1 = fmaf(bf16_to_f32(a.w_head[d + i]), y, o1);
+    }
+    o0 = block_sum(o0, red);
+    o1 = block_sum(o1, red);
+    if (tid != 0) return;
+    o0 += bf16_to_f32(a.b_head[0]);
+    o1 += bf16_to_f32(a.b_head[1]);
+    if (a.logits) { a.logits[2 * b] = o0; a.logits[2 * b + 1] = o1; }
+    rs_route_out rec = a.out[b];
+    const uint32_t untouchable = RS_FLAG_NONFINITE | RS_FLAG_BADARG | RS_FLAG_ABORTED;
+    if (a.active == RS_SLM && (rec.flags & RS_FLAG_HI) && !(rec.flags & untouchable) && !(o1 > o0)) {
+        rec.flags = (rec.flags | RS_FLAG_ACCEPT | RS_FLAG_ROUTER_STAY) & ~RS_FLAG_NEXT_LLM;
+        a.out[b] = rec;
+    }
+}
+
 }  // namespace rs

@@ -565,6 +565,23 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
+            static const int x_down = getenv("RS_X_DOWN") ? atoi(getenv("RS_X_DOWN")) : 0;      // EXPERIMENT
+            if (x_down) {
+                const int rt = x_down / 100, wpc = x_down % 100;       // e.g. 703 = seven-row tiles, 3 workgroups per CU
+                const int tiles = (c.d_model + rt - 1) / rt;
+                int blocks = wpc * m->n_cu; if (blocks > tiles) blocks = tiles;
+                switch (rt) {
+                    case 2: hipLaunchKernelGGL((k_down_direct<2, 4>), dim3(blocks), dim3(256), 0, st, g); break;
+                    case 3: hipLaunchKernelGGL((k_down_direct<3, 4>), dim3(blocks), dim3(256), 0, st, g); break;
+                    case 4: hipLaunchKernelGGL((k_down_direct<4, 2>), dim3(blocks), dim3(256), 0, st, g); break;
+                    case 6: hipLaunchKernelGGL((k_down_direct<6, 2>), dim3(blocks), dim3(256), 0, st, g); break;
+                    case 7: hipLaunchKernelGGL((k_down_direct<7, 2>), dim3(blocks), dim3(256), 0, st, g); break;
+                    case 5: hipLaunchKernelGGL((k_down_direct<5, 2>), dim3(blocks), dim3(256), 0, st, g); break;
+                    default: hipLaunchKernelGGL((k_down_direct<10, 1>), dim3(blocks), dim3(256), 0, st, g); break;
+                }
+                RS_LAUNCHED("down_direct");
+                rc = RS_OK;
+            } else
             switch (pl.down_rt) {
                 case 2: rc = launch_gemv<G_DOWN, 2, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
                 case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
@@ -935,6 +952,38 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab, const float 
     hipLaunchKernelGGL(rs::k_route_merge, dim3(n), dim3(256), 0, st, (const rs::SoftPartial *)d_scratch, parts, vocab, tau,
                        active, (const int *)nullptr, d_out);
     RS_LAUNCHED("route_merge");
+    return RS_OK;
+}
+
+rs_status rs_route_plus(rs_model *m, const float *d_hidden, int32_t n_seqs, const rs_router_weights *w, int32_t active,
+                        rs_route_out *d_out, float *d_router_logits, void *stream) {
+    if (!w || !d_out) return fail(RS_EINVAL, "null argument");
+    if ((m == nullptr) == (d_hidden == nullptr)) return fail(RS_EINVAL, "give either the model or the hidden states");
+    if (n_seqs < 1) return fail(RS_EINVAL, "n_seqs must be at least 1");
+    if (m && n_seqs > m->cfg.max_seqs) return fail(RS_ECAPACITY, "n_seqs %d exceeds max_seqs %d", n_seqs, m->cfg.max_seqs);
+    if (n_seqs > 65535) return fail(RS_ECAPACITY, "n_seqs %d exceeds 65535", n_seqs);
+    if (active != RS_SLM && active != RS_LLM) return fail(RS_EINVAL, "active must be RS_SLM or RS_LLM");
+    if (w->d < 8 || w->d % 8 || w->d > 12288) return fail(RS_EINVAL, "router width must be a multiple of 8, at most 12288");
+    if (w->r < 8 || w->r % 8 || w->r > rs::ROUTER_RMAX) return fail(RS_EINVAL, "router bottleneck must be a multiple of 8, at most 64");
+    if (!(w->ln_eps > 0.f)) return fail(RS_EINVAL, "ln_eps must be > 0");
+    if (m && w->d != m->cfg.d_model) return fail(RS_EINVAL, "router width %d differs from the model's d_model %d", w->d, m->cfg.d_model);
+    if (!w->w1 || !w->b1 || !w->w2 || !w->b2 || !w->ln_gain || !w->ln_bias || !w->w_head || !w->b_head)
+        return fail(RS_EINVAL, "null router weight pointer");
+    rs::RouterPlusArgs a{};
+    for (int i = 0; i < rs::ROUTER_BLOCKS; ++i) {
+        if (!w->w1[i] || !w->b1[i] || !w->w2[i] || !w->b2[i]) return fail(RS_EINVAL, "null router weight pointer in block %d", i);
+        if (((uintptr_t)w->w1[i] | (uintptr_t)w->w2[i]) % 16) return fail(RS_EINVAL, "router matrices must be 16-byte aligned");
+        a.w1[i] = (const uint16_t *)w->w1[i]; a.b1[i] = (const uint16_t *)w->b1[i];
+        a.w2[i] = (const uint16_t *)w->w2[i]; a.b2[i] = (const uint16_t *)w->b2[i];
+    }
+    a.ln_gain = (const uint16_t *)w->ln_gain; a.ln_bias = (const uint16_t *)w->ln_bias;
+    a.w_head = (const uint16_t *)w->w_head; a.b_head = (const uint16_t *)w->b_head;
+    a.d = w->d; a.r = w->r; a.ln_eps = w->ln_eps;
+    if (m) { a.hidden = m->at<float>(m->lay.h); a.ld_hidden = m->cfg.d_model; a.gather = m->at<int>(m->lay.out_row); }
+    else { a.hidden = d_hidden; a.ld_hidden = w->d; a.gather = nullptr; }
+    a.active = active; a.out = d_out; a.logits = d_router_logits;
+    hipLaunchKernelGGL(rs::k_router_plus, dim3(n_seqs), dim3(256), (size_t)w->d * 4, (hipStream_t)stream, a);
+    RS_LAUNCHED("router_plus");
     return RS_OK;
 }
 

@@ -111,11 +111,12 @@ class StitchedPair:
 
     def generate(self, prompt: Sequence[int], tau: float, n_tokens: int, single_model: Optional[int] = None,
                  keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None,
-                 llm_prefilled: bool = False) -> StitchRun:
+                 llm_prefilled: bool = False, router_plus: Optional[B.RouterPlus] = None) -> StitchRun:
         """Algorithm 1 until n_tokens tokens are accepted.  single_model = SLM or LLM runs that model
         alone (every token accepted) while still reporting its entropies.  llm_prefilled: the large model's
         cache already holds the prompt (prefill_prompt), so its first participation only catches up with the
-        tokens accepted since."""
+        tokens accepted since.  router_plus: the R-Stitch+ branch of Algorithm 1: after every small-model call the
+        learned router (rs_route_plus, enqueued behind the call) may turn a hand-over into "keep the token and stay"."""
         n0 = len(prompt)
         if n0 + n_tokens > self.max_ctx + 1:
             raise ValueError("prompt + tokens exceed max_ctx")
@@ -129,6 +130,8 @@ class StitchedPair:
         while len(run.output) < n_tokens:
             pos0 = n_kv[active]
             self._forward(active, pos0, length, tau)
+            if router_plus is not None and active == SLM:
+                B.rs_route_plus(self.models[SLM].handle, None, 1, router_plus, SLM, self._p_out, None, self.stream)
             sync()
             n_kv[active] = length
             token, flags = int(self.stage_i[o]), int(self.stage_i[o + 1]) & 0xFFFFFFFF

@@ -200,15 +200,16 @@ class RouterWeights:
 
 
 def make_router_weights(d: int, r: int, seed: int, device="cpu") -> RouterWeights:
-    """Seeded synthetic router (the trained one of the paper does not exist offline): matrices N(0, 0.05), biases
-    N(0, 0.05), LayerNorm gain 1 + N(0, 0.1) and bias N(0, 0.1), all rounded to bf16."""
+    """Seeded synthetic router (the trained one of the paper does not exist offline): matrices N(0, 0.05), block
+    biases N(0, 0.002) (small beside a hidden state of a random N(0, 0.02) model, so that the outputs depend on the
+    state), head bias N(0, 0.05), LayerNorm gain 1 + N(0, 0.1) and bias N(0, 0.1), all rounded to bf16."""
     def draw(idx, count, std, shift=0.0):
         z = rng.normal(seed, _STREAM_ROUTER + idx, 0, count, device)
         return (shift + std * z).to(torch.float32).to(torch.bfloat16)
     w = RouterWeights([], [], [], [], draw(60, d, 0.1, 1.0), draw(61, d, 0.1), draw(62, 2 * d, 0.05).view(2, d), draw(63, 2, 0.05))
     for i in range(6):
         w.w1.append(draw(4 * i, r * d, 0.05).view(r, d))
-        w.b1.append(draw(4 * i + 1, r, 0.05))
+        w.b1.append(draw(4 * i + 1, r, 0.002))
         w.w2.append(draw(4 * i + 2, d * r, 0.05).view(d, r))
-        w.b2.append(draw(4 * i + 3, d, 0.05))
+        w.b2.append(draw(4 * i + 3, d, 0.002))
     return w
