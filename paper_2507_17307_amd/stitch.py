@@ -142,11 +142,10 @@ class StitchedPair:
             if keep_trace:
                 run.trace.append(Invocation(active, pos0, length - pos0, token, float(self.stage_f[o + 3]), flags))
             if single_model is None:
-                if active == SLM and (flags & B.FLAG_HI):
-                    active = LLM
+                if not (flags & B.FLAG_ACCEPT):
+                    active = LLM                             # small-model token discarded; the large model redoes this position
                     continue
-                if active == LLM and not (flags & B.FLAG_HI):
-                    active = SLM
+                active = LLM if (flags & B.FLAG_NEXT_LLM) else SLM
             self.seq_np[length] = token
             length += 1
             run.output.append(token)
@@ -279,11 +278,10 @@ class StitchedBatch:
                         n_kv[model][b] = lengths[b]
                         group.remove(b)
                         if single_model is None:
-                            if model == SLM and (flags & B.FLAG_HI):
+                            if not (flags & B.FLAG_ACCEPT):
                                 active[b] = LLM            # rejected: the large model redoes this position
                                 continue
-                            if model == LLM and not (flags & B.FLAG_HI):
-                                active[b] = SLM
+                            active[b] = LLM if (flags & B.FLAG_NEXT_LLM) else SLM
                         self.seqs[b][lengths[b]] = token
                         lengths[b] += 1
                         runs[b].output.append(token)
