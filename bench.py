@@ -176,9 +176,12 @@ def oracle_sample(W, odec, wts, ctx, rows_list, k_layers=4, seed=77):
             om.v_cache[:, 0, :, :ctx] = noise
         om.forward([1], ctx)                      # untimed: first touch of the caches and of the BLAS threads
         for rows in rows_list:
-            t0 = time.perf_counter()
-            om.forward(list(range(1, rows + 1)), ctx)
-            out[(n_l, rows)] = time.perf_counter() - t0
+            best = float("inf")
+            for _ in range(2):                    # the better of two: the layer share is scaled up, and with it any hiccup
+                t0 = time.perf_counter()
+                om.forward(list(range(1, rows + 1)), ctx)
+                best = min(best, time.perf_counter() - t0)
+            out[(n_l, rows)] = best
         del om
     return {rows: out[(0, rows)] + (out[(k, rows)] - out[(0, rows)]) * shape.n_layers / k for rows in rows_list}, k
 

@@ -497,132 +497,222 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Single-row down projection (h += W_down . act) with staging waves: 512 threads.  Waves 0..3 own a
-// quarter of K each, as in the split-K GEMV above; waves 4..7 do nothing but copy the activation vector
-// (K fp32, tens of KB) from L2 into LDS.  A wave's loads return in order, so a wave that stages x cannot
-// have weight requests in flight ahead of it without stalling the copy; with the copy on waves of its
-// own the compute waves request the first PRE chunks of their tile at once and the weight stream starts
-// while x is still on its way.  Every wave executes the same barriers (one after the copy, one per
-// tile); the staging waves only wait at them.
-// grid: workgroups share the ceil(N / RT) row tiles in contiguous ranges; LDS: K * 4 + 512 bytes.
+// Single-row GEMV phases with the activation vector in REGISTERS.  K = 512 * NCH: a row of W is NCH
+// chunks of 16 bytes per lane, and lane l of every wave holds exactly the x values those chunks
+// meet (elements 8 (l + 64 u) .. + 7, u < NCH), K / 64 floats.  A wave is then self-contained: it
+// loads its own copy of h (or of the ready activation), reduces the sum of squares of an RMSNorm
+// across its lanes with DPP adds, scales, and streams its weight tiles against registers.  No LDS
+// staging, no workgroup barrier, no LDS reads in the stream; the only LDS is the LM head's
+// exchange of four softmax states.  The first UG chunks of a wave's first tile are requested
+// before the activation loads, so the weight stream's first round trip overlaps the prologue.
+// Tiles and epilogues are those of gemv_phase (KS = 1, one token row).
 // ------------------------------------------------------------------------------------------------
-__host__ __device__ constexpr size_t down_staged_lds_bytes(int K) { return (size_t)K * 4 + 512; }
-
-template <int RT, int UNR, int PRE>
-__global__ void __launch_bounds__(512, 4) k_down_staged(GemvArgs a) {      // four waves per SIMD: two workgroups per CU
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int K = a.K, n_chunks = K >> 3, plane_len = K >> 3;
-    float4 *xs = reinterpret_cast<float4 *>(smem);                          // two planes of K/8 float4
-    float *red = reinterpret_cast<float *>(smem + (size_t)K * 4);           // [2][4][RT] (RT <= 10: 320 bytes)
+template <int MODE, int RT, int NCH, int UG>
+__global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
+    static_assert(MODE != G_DOWN, "the down projection splits K over the waves");
+    static_assert(UG >= 1 && UG <= NCH, "group size");
+    constexpr bool NORM = (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD);
+    constexpr int P = RT / 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool stager = wave >= 4;
     const int wg = blockIdx.x, nwg = gridDim.x;
-    const int n_tiles = (a.N + RT - 1) / RT;
-    const int t_lo = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)nwg), t_hi = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)nwg);
-    const int c0 = (wave & 3) * 64 + lane, cstride = 256;
-
-    uint4 pre[PRE > 0 ? PRE : 1][RT];
-    if (!stager) {
-        // first tile's early chunks (a workgroup without a tile requests the last tile's and never uses them)
-        const int t0 = min(t_lo, n_tiles - 1);
-#pragma unroll
-        for (int u = 0; u < PRE; ++u) {
-            const int c = min(c0 + u * cstride, n_chunks - 1);
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                pre[u][r] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)min(t0 * RT + r, a.N - 1) * K) + c);
-        }
+    const int K = a.K;                                    // == 512 * NCH (the host checks)
+    const int half = a.head_dim >> 1;
+    int n_tiles, n_rot_tiles = 0;
+    if (MODE == G_QKV) {
+        n_rot_tiles = (a.n_q + a.n_kv) * (half / P);
+        n_tiles = n_rot_tiles + (a.n_kv * a.head_dim) / RT;
+    } else if (MODE == G_GATEUP) {
+        n_tiles = a.d_ffn / P;
     } else {
-        // x: float4 index i covers elements 4i..4i+3; even i -> plane A, odd i -> plane B
-        const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in);
-        const int n4 = K >> 2, st = tid - 256;
-        constexpr int SB = 10;
-        for (int b0 = 0; b0 < n4; b0 += 256 * SB) {
-            float4 v[SB];
+        n_tiles = (a.N + RT - 1) / RT;
+    }
+    const int t_lo = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)nwg), t_hi = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)nwg);
+    const int unit0 = t_lo + wave;
+
+    auto tile_rows = [&](int t, int (&rows)[RT], int &head, int &pair0, bool &rot) {
+        head = 0; pair0 = 0; rot = false;
+        if (MODE == G_QKV) {
+            if (t < n_rot_tiles) {
+                rot = true; head = t / (half / P); pair0 = (t % (half / P)) * P;
 #pragma unroll
-            for (int j = 0; j < SB; ++j) v[j] = x4[min(b0 + st + j * 256, n4 - 1)];
+                for (int j = 0; j < P; ++j) { rows[2 * j] = head * a.head_dim + pair0 + j; rows[2 * j + 1] = rows[2 * j] + half; }
+            } else {
 #pragma unroll
-            for (int j = 0; j < SB; ++j) {
-                const int i = b0 + st + j * 256;
-                if (i < n4) xs[(i & 1) * plane_len + (i >> 1)] = v[j];
+                for (int j = 0; j < RT; ++j) rows[j] = (a.n_q + a.n_kv) * a.head_dim + (t - n_rot_tiles) * RT + j;
+            }
+        } else if (MODE == G_GATEUP) {
+#pragma unroll
+            for (int j = 0; j < P; ++j) { rows[2 * j] = t * P + j; rows[2 * j + 1] = a.d_ffn + t * P + j; }
+        } else {
+#pragma unroll
+            for (int j = 0; j < RT; ++j) rows[j] = min(t * RT + j, a.N - 1);
+        }
+    };
+
+    // ---- first weight requests of the wave's first tile (a wave without a tile requests the last tile's, unused)
+    uint4 pre[UG][RT];
+    {
+        int rows0[RT], head0, pair00; bool rot0;
+        tile_rows(min(unit0, n_tiles - 1), rows0, head0, pair00, rot0);
+#pragma unroll
+        for (int u = 0; u < UG; ++u)
+#pragma unroll
+            for (int r = 0; r < RT; ++r) pre[u][r] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)rows0[r] * K) + lane + 64 * u);
+    }
+    int row_bad = 1, row_pos = 0, row_slot = 0;
+    if (MODE == G_QKV) { row_bad = a.row_bad[0]; row_pos = a.row_pos[0]; row_slot = a.row_slot[0]; }
+
+    // ---- x into registers
+    float xr[NCH][8];
+    {
+        const int src = (MODE == G_LMHEAD && a.gather) ? a.gather[0] : 0;
+        const float4 *x4 = reinterpret_cast<const float4 *>(NORM ? a.h_in + (size_t)src * a.ld_h : a.x_in);
+        float4 xa[NCH], xb[NCH];
+#pragma unroll
+        for (int u = 0; u < NCH; ++u) { xa[u] = x4[2 * (lane + 64 * u)]; xb[u] = x4[2 * (lane + 64 * u) + 1]; }
+        if (NORM) {
+            const uint4 *g4 = reinterpret_cast<const uint4 *>(a.gain);
+            uint4 gg[NCH];
+#pragma unroll
+            for (int u = 0; u < NCH; ++u) gg[u] = g4[lane + 64 * u];
+            float ss = 0.f;
+#pragma unroll
+            for (int u = 0; u < NCH; ++u) {
+                ss = fmaf(xa[u].x, xa[u].x, ss); ss = fmaf(xa[u].y, xa[u].y, ss); ss = fmaf(xa[u].z, xa[u].z, ss); ss = fmaf(xa[u].w, xa[u].w, ss);
+                ss = fmaf(xb[u].x, xb[u].x, ss); ss = fmaf(xb[u].y, xb[u].y, ss); ss = fmaf(xb[u].z, xb[u].z, ss); ss = fmaf(xb[u].w, xb[u].w, ss);
+            }
+            const float inv = 1.0f / sqrtf(wave_sum(ss) / (float)K + a.eps);
+#pragma unroll
+            for (int u = 0; u < NCH; ++u) {
+                xr[u][0] = xa[u].x * (inv * bf16_lo(gg[u].x)); xr[u][1] = xa[u].y * (inv * bf16_hi(gg[u].x));
+                xr[u][2] = xa[u].z * (inv * bf16_lo(gg[u].y)); xr[u][3] = xa[u].w * (inv * bf16_hi(gg[u].y));
+                xr[u][4] = xb[u].x * (inv * bf16_lo(gg[u].z)); xr[u][5] = xb[u].y * (inv * bf16_hi(gg[u].z));
+                xr[u][6] = xb[u].z * (inv * bf16_lo(gg[u].w)); xr[u][7] = xb[u].w * (inv * bf16_hi(gg[u].w));
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < NCH; ++u) {
+                xr[u][0] = xa[u].x; xr[u][1] = xa[u].y; xr[u][2] = xa[u].z; xr[u][3] = xa[u].w;
+                xr[u][4] = xb[u].x; xr[u][5] = xb[u].y; xr[u][6] = xb[u].z; xr[u][7] = xb[u].w;
             }
         }
     }
-    __syncthreads();
 
-    int parity = 0;
-    for (int t = t_lo; t < t_hi; ++t) {
-        float acc[RT];
-        float epi[RT];
+    SoftState st; st.init();
+    const float lm_scale = MODE == G_LMHEAD ? a.seq_scale[0] : 1.f;
+
+    auto fma_chunk = [&](const uint4 &w, const float (&x)[8], float v) {
+        v = fmaf(bf16_lo(w.x), x[0], v); v = fmaf(bf16_hi(w.x), x[1], v); v = fmaf(bf16_lo(w.y), x[2], v); v = fmaf(bf16_hi(w.y), x[3], v);
+        v = fmaf(bf16_lo(w.z), x[4], v); v = fmaf(bf16_hi(w.z), x[5], v); v = fmaf(bf16_lo(w.w), x[6], v); v = fmaf(bf16_hi(w.w), x[7], v);
+        return v;
+    };
+
+    for (int t = unit0; t < t_hi; t += 4) {
+        int rows[RT];
+        int head, pair0; bool rot;
+        tile_rows(t, rows, head, pair0, rot);
+        const uint4 *wp[RT];
+        float acc[RT], epi[RT];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) { acc[r] = 0.f; epi[r] = 0.f; }
-        if (!stager) {
-            const uint4 *wp[RT];
+        for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K) + lane; acc[r] = 0.f; epi[r] = 0.f; }
+        // what the epilogue needs from memory is requested ahead of the weight stream
+        if (MODE == G_QKV) {
+            if (rot && !row_bad) {
 #pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                const int row = min(t * RT + r, a.N - 1);
-                wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)row * K);
-                epi[r] = a.h_out[row];                                     // requested ahead of the weight stream
+                for (int j = 0; j < P; ++j) {
+                    epi[2 * j] = a.rope_cos[(size_t)row_pos * half + pair0 + j];
+                    epi[2 * j + 1] = a.rope_sin[(size_t)row_pos * half + pair0 + j];
+                }
             }
-            int cb = c0;
-            if (PRE > 0 && t == t_lo) {
+        } else if (MODE == G_OPROJ) {
 #pragma unroll
-                for (int u = 0; u < PRE; ++u) {
-                    const int c = c0 + u * cstride;
-                    const bool valid = c < n_chunks;
-                    const int cc = valid ? c : 0;
-                    float4 xa = xs[cc], xb = xs[plane_len + cc];
-                    if (!valid) { xa = make_float4(0.f, 0.f, 0.f, 0.f); xb = xa; }
+            for (int r = 0; r < RT; ++r) epi[r] = a.h_out[rows[r]];
+        }
+        // groups of UG chunks; the first group of the first tile is already on its way
 #pragma unroll
-                    for (int r = 0; r < RT; ++r) {
-                        const uint4 w = pre[u][r];
-                        float v = acc[r];
-                        v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
-                        v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
-                        acc[r] = v;
+        for (int u0 = 0; u0 < NCH; u0 += UG) {
+            uint4 wv[UG][RT];
+            if (u0 == 0 && t == unit0) {
+#pragma unroll
+                for (int u = 0; u < UG; ++u)
+#pragma unroll
+                    for (int r = 0; r < RT; ++r) wv[u][r] = pre[u][r];
+            } else {
+#pragma unroll
+                for (int u = 0; u < UG; ++u)
+#pragma unroll
+                    for (int r = 0; r < RT; ++r)
+                        if (u0 + u < NCH) wv[u][r] = load_stream(wp[r] + 64 * (u0 + u));
+            }
+#pragma unroll
+            for (int u = 0; u < UG; ++u)
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+                    if (u0 + u < NCH) acc[r] = fma_chunk(wv[u][r], xr[u0 + u], acc[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+        if (lane != 0) continue;
+
+        // ---- epilogue (one lane)
+        if (MODE == G_QKV) {
+            if (row_bad) continue;
+            if (rot) {
+#pragma unroll
+                for (int j = 0; j < P; ++j) {
+                    const int i = pair0 + j;
+                    const float c = epi[2 * j], sn = epi[2 * j + 1], x0 = acc[2 * j], x1 = acc[2 * j + 1];
+                    const float y0 = x0 * c - x1 * sn, y1 = x1 * c + x0 * sn;
+                    if (head < a.n_q) {
+                        float *q = a.qbuf + head * a.head_dim;
+                        q[i] = y0; q[i + half] = y1;
+                    } else {
+                        const size_t base = ((((size_t)a.layer * a.max_seqs + row_slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + row_pos) * a.head_dim;
+                        a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
                     }
                 }
-                cb = c0 + PRE * cstride;
-            }
-#pragma unroll UNR
-            for (int c = cb; c < n_chunks; c += cstride) {
-                uint4 wv[RT];
+            } else {
 #pragma unroll
-                for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
-                const float4 xa = xs[c], xb = xs[plane_len + c];
-#pragma unroll
-                for (int r = 0; r < RT; ++r) {
-                    const uint4 w = wv[r];
-                    float v = acc[r];
-                    v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
-                    v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
-                    acc[r] = v;
+                for (int j = 0; j < RT; ++j) {
+                    const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
+                    const int vh = vr / a.head_dim, e = vr % a.head_dim;
+                    const size_t base = (((size_t)a.layer * a.max_seqs + row_slot) * a.n_kv + vh) * (size_t)a.max_ctx * a.head_dim;
+                    a.vcache[base + (size_t)e * a.max_ctx + row_pos] = f32_to_bf16(acc[j]);     // V is stored [hd][position]
                 }
             }
+        } else if (MODE == G_GATEUP) {
 #pragma unroll
-            for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
-            if (lane == 0) {
+            for (int j = 0; j < P; ++j) {
+                const float g = acc[2 * j], up = acc[2 * j + 1];
+                a.act[t * P + j] = g / (1.0f + expf(-g)) * up;
+            }
+        } else if (MODE == G_OPROJ) {
 #pragma unroll
-                for (int r = 0; r < RT; ++r) red[(parity * 4 + wave) * RT + r] = acc[r];
+            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[t * RT + j] = epi[j] + acc[j];
+        } else {   // G_LMHEAD
+#pragma unroll
+            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
+                const float lg = acc[j] * lm_scale;
+                st.push(lg, t * RT + j);
+                if (a.logits) a.logits[t * RT + j] = lg;
             }
         }
+    }
+    if (MODE == G_LMHEAD) {
+        __shared__ SoftPartial sp[4];
+        if (lane == 0) sp[wave] = to_partial(st);
         __syncthreads();
         if (tid == 0) {
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                const int row = t * RT + r;
-                if (row < a.N)
-                    a.h_out[row] = epi[r] + (red[(parity * 4 + 0) * RT + r] + red[(parity * 4 + 1) * RT + r] +
-                                             red[(parity * 4 + 2) * RT + r] + red[(parity * 4 + 3) * RT + r]);
-            }
+            SoftState s0 = from_partial(sp[0]);
+            for (int w = 1; w < 4; ++w) s0.merge(from_partial(sp[w]));
+            a.parts[wg] = to_partial(s0);
         }
-        parity ^= 1;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // Single-row down projection (h += W_down . act) without any staging: the four waves of a workgroup
-// split K as above, and every lane reads the eight activation values of a chunk straight from
+// split K (wave w takes the chunks w * 64 + lane, + 256, ...), and every lane reads the eight activation values of a chunk straight from
 // global memory next to the RT weight rows of that chunk.  The activation vector (tens of KB) is
 // the same for every workgroup, so those reads are served by the CU's cache and the L2; they cost
 // 32 bytes per lane and chunk against RT x 16 bytes of weights, but there is no copy into LDS, no

@@ -193,23 +193,6 @@ rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *na
     return RS_OK;
 }
 
-template <int RT, int UNR, int PRE>
-rs_status launch_down_staged(GemvArgs &a, int blocks, hipStream_t st) {
-    const size_t lds = down_staged_lds_bytes(a.K);
-    if (lds > 64 * 1024) {
-        static std::atomic<bool> raised{false};           // per instantiation; setting the attribute twice is harmless
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_down_staged<RT, UNR, PRE>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
-            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of the down projection: %s", hipGetErrorString(e));
-            raised = true;
-        }
-    }
-    hipLaunchKernelGGL((k_down_staged<RT, UNR, PRE>), dim3(blocks), dim3(512), lds, st, a);
-    RS_LAUNCHED("down_staged");
-    return RS_OK;
-}
-
 // Single-row launches.  (gemv_phase can be compiled for 2, 4 or 8 token rows as well; on this chip the
 // matrix-core path overtakes those variants already at two rows, so only the one-row form is built.)
 // PRE: early weight request.
@@ -219,6 +202,20 @@ rs_status launch_gemv(const rs_model *m, GemvArgs &a, int mp, int blocks, hipStr
     if (mp != 1) return fail(RS_EINVAL, "internal: %s launched for %d rows", name, mp);
     return launch_gemv_mp<MODE, RT, KS, UNR, 1, PRE>(a, blocks, st, name);
 }
+
+// register-resident x (k_gemv_reg): K must be 512 * NCH with NCH one of 3, 7, 10 (d_model 1536, 3584, 5120)
+template <int MODE, int RT>
+rs_status launch_gemv_reg(GemvArgs &a, int blocks, hipStream_t st, const char *name) {
+    switch (a.K) {
+        case 1536: hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 3, 3>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 3584: hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 7, (RT >= 8 ? 2 : 4)>), dim3(blocks), dim3(256), 0, st, a); break;
+        case 5120: hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 10, (RT >= 8 ? 2 : 5)>), dim3(blocks), dim3(256), 0, st, a); break;
+        default: return fail(RS_EINVAL, "internal: %s with K = %d", name, a.K);
+    }
+    RS_LAUNCHED(name);
+    return RS_OK;
+}
+inline bool reg_k(int K) { return K == 1536 || K == 3584 || K == 5120; }
 
 // Launch shapes from sweeps on MI355X: about three workgroups per CU for matrices under ~128 MB,
 // two above; the down projection gets one tile per workgroup.
@@ -244,13 +241,9 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
     const size_t o_bytes = (size_t)c.d_model * c.n_q_heads * hd * 2;
     p.o_all_early = o_bytes >= ((size_t)16 << 20) && o_bytes < ((size_t)40 << 20) && c.n_q_heads * hd <= 3584;
     if (p.o_all_early) p.o_blocks = clamp_blocks(2 * n_cu, ((c.d_model + 1) / 2 + 3) / 4);
-    // down: split-K workgroups, rows per workgroup chosen so that ~2 workgroups per CU have one tile each
-    const int want = (c.d_model + 2 * n_cu - 1) / (2 * n_cu);
-    const int opts[] = {2, 4, 5, 7, 8, 10};
-    p.down_rt = 10;
-    for (int o : opts) if (o >= want) { p.down_rt = o; break; }
-    if (c.d_model <= 2048) p.down_rt = 2;
-    p.down_blocks = clamp_blocks(3 * n_cu, (c.d_model + p.down_rt - 1) / p.down_rt);
+    // down (k_down_direct): rows per tile by width, see the launch
+    p.down_rt = c.d_model <= 2048 ? 2 : (c.d_model <= 4096 ? 7 : 5);
+    p.down_blocks = clamp_blocks((c.d_model <= 2048 ? 3 : 4) * n_cu, (c.d_model + p.down_rt - 1) / p.down_rt);
     p.lm_blocks = clamp_blocks(4 * n_cu, ((c.vocab + 7) / 8 + 3) / 4);
     if (p.lm_blocks > LM_PARTS_CAP) p.lm_blocks = LM_PARTS_CAP;
     return p;
@@ -524,6 +517,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             // QKV (+ RMSNorm, RoPE, KV write)
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
             tic(RS_PHASE_QKV, l);
+            // d_model 1536 or 3584: the activation vector in registers, no LDS (1.5B decode step -2 %, 7B -0.2 %)
+            if (reg_k(c.d_model) && c.d_model <= 3584) rc = launch_gemv_reg<G_QKV, 2>(g, pl.qkv_blocks, st, "gemv_reg_qkv");
+            else
             if (pl.qkv_rt == 4) rc = launch_gemv<G_QKV, 4, 1, 2, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
             // d_model <= 1536: a row is three chunks per lane, all requested before the prologue (1.5B step -1 %)
             else if (c.d_model <= 1536) rc = launch_gemv<G_QKV, 2, 1, 1, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
@@ -544,6 +540,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.x_in = m->at<float>(L.attn_out);
             tic(RS_PHASE_OPROJ, l);
             // 7B shape (25.7 MB, seven chunks per lane and row): all seven early at two workgroups per CU, step -0.5 %
+            // 1536, 3584 or 5120 input channels: the attention output in registers (1.5B decode step -2 %, 7B -0.8 %)
+            if (reg_k(qdim)) rc = launch_gemv_reg<G_OPROJ, 2>(g, pl.o_blocks, st, "gemv_reg_oproj");
+            else
             if (pl.o_all_early) rc = launch_gemv<G_OPROJ, 2, 1, 1, 7>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
             else rc = launch_gemv<G_OPROJ, 2, 1, 2, 4>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
             toc(RS_PHASE_OPROJ, l);
@@ -565,41 +564,21 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
             g.x_in = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
-            static const int x_down = getenv("RS_X_DOWN") ? atoi(getenv("RS_X_DOWN")) : 0;      // EXPERIMENT
-            if (x_down) {
-                const int rt = x_down / 100, wpc = x_down % 100;       // e.g. 703 = seven-row tiles, 3 workgroups per CU
-                const int tiles = (c.d_model + rt - 1) / rt;
-                int blocks = wpc * m->n_cu; if (blocks > tiles) blocks = tiles;
-                switch (rt) {
+            // x is read straight from global memory next to the weights (no LDS staging); rows per tile by width,
+            // from same-process A/B runs of whole decode steps: two-row tiles at three workgroups per CU up to
+            // d_model 2048 (1.5B step 1.153 -> 1.082 ms against the LDS-staged kernel), seven-row tiles for 3584
+            // (7B: 2.994 -> 2.850 ms), five-row tiles at four workgroups per CU above (14B: 6.08 -> 5.86 ms,
+            // 32B: 13.16 -> 11.80 ms)
+            {
+                const int tiles = (c.d_model + pl.down_rt - 1) / pl.down_rt;
+                const int blocks = pl.down_blocks < tiles ? pl.down_blocks : tiles;
+                switch (pl.down_rt) {
                     case 2: hipLaunchKernelGGL((k_down_direct<2, 4>), dim3(blocks), dim3(256), 0, st, g); break;
-                    case 3: hipLaunchKernelGGL((k_down_direct<3, 4>), dim3(blocks), dim3(256), 0, st, g); break;
-                    case 4: hipLaunchKernelGGL((k_down_direct<4, 2>), dim3(blocks), dim3(256), 0, st, g); break;
-                    case 6: hipLaunchKernelGGL((k_down_direct<6, 2>), dim3(blocks), dim3(256), 0, st, g); break;
                     case 7: hipLaunchKernelGGL((k_down_direct<7, 2>), dim3(blocks), dim3(256), 0, st, g); break;
-                    case 5: hipLaunchKernelGGL((k_down_direct<5, 2>), dim3(blocks), dim3(256), 0, st, g); break;
-                    default: hipLaunchKernelGGL((k_down_direct<10, 1>), dim3(blocks), dim3(256), 0, st, g); break;
+                    default: hipLaunchKernelGGL((k_down_direct<5, 2>), dim3(blocks), dim3(256), 0, st, g); break;
                 }
                 RS_LAUNCHED("down_direct");
                 rc = RS_OK;
-            } else
-            switch (pl.down_rt) {
-                case 2: rc = launch_gemv<G_DOWN, 2, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
-                case 4: rc = launch_gemv<G_DOWN, 4, 4, 2>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
-                case 5: rc = launch_gemv<G_DOWN, 5, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
-                // seven-row tiles (7B shape): the variant with staging waves, as long as two workgroups of it fit a CU
-                // (x in LDS <= 76 KB); 7B decode step -0.024 ms.  With ten-row tiles or a second unrolled round it would spill registers, with
-                // two-row tiles (1.5B shape) it measured no gain.
-                case 7:
-                    if (mp == 1 && (size_t)c.d_ffn <= (size_t)GEMV_LDS_FLOATS / 2) rc = launch_down_staged<7, 1, 1>(g, pl.down_blocks, st);
-                    else rc = launch_gemv<G_DOWN, 7, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down");
-                    break;
-                case 8: rc = launch_gemv<G_DOWN, 8, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down"); break;
-                // ten-row tiles (14B/32B shapes): where two workgroups with x in LDS fit a CU (14B: 54 KB each), the
-                // staging-wave kernel with five-row tiles, two per workgroup; 14B decode step 6.035 -> 5.947 ms
-                default:
-                    if (mp == 1 && (size_t)c.d_ffn <= (size_t)GEMV_LDS_FLOATS / 2) rc = launch_down_staged<5, 2, 1>(g, pl.down_blocks, st);
-                    else rc = launch_gemv<G_DOWN, 10, 4, 1>(m, g, mp, pl.down_blocks, st, "gemv_down");
-                    break;
             }
             toc(RS_PHASE_DOWN, l);
             if (rc) return rc;
