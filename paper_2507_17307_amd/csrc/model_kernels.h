@@ -505,17 +505,19 @@ __global__ void __launch_bounds__(256) k_gemv(GemvArgs a) {
 // staging, no workgroup barrier, no LDS reads in the stream; the only LDS is the LM head's
 // exchange of four softmax states.  The first UG chunks of a wave's first tile are requested
 // before the activation loads, so the weight stream's first round trip overlaps the prologue.
-// Tiles and epilogues are those of gemv_phase (KS = 1, one token row).
+// Tiles and epilogues are those of gemv_phase (KS = 1).  MP token rows (a call of a few rows: short catch-up
+// spans, small batches) share every weight chunk: each row's x lives in its own registers.
 // ------------------------------------------------------------------------------------------------
-template <int MODE, int RT, int NCH, int UG>
+template <int MODE, int RT, int NCH, int UG, int MP = 1>
 __global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
     static_assert(MODE != G_DOWN, "the down projection splits K over the waves");
     static_assert(UG >= 1 && UG <= NCH, "group size");
+    static_assert(MODE != G_LMHEAD || MP == 1, "the LM head runs on one row per sequence; batches take the LDS-staged kernel");
     constexpr bool NORM = (MODE == G_QKV || MODE == G_GATEUP || MODE == G_LMHEAD);
     constexpr int P = RT / 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x, nwg = gridDim.x;
-    const int K = a.K;                                    // == 512 * NCH (the host checks)
+    const int K = a.K, M = a.m_rows;                      // K == 512 * NCH (the host checks); M <= MP token rows
     const int half = a.head_dim >> 1;
     int n_tiles, n_rot_tiles = 0;
     if (MODE == G_QKV) {
@@ -559,14 +561,19 @@ __global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
 #pragma unroll
             for (int r = 0; r < RT; ++r) pre[u][r] = load_stream(reinterpret_cast<const uint4 *>(a.W + (size_t)rows0[r] * K) + lane + 64 * u);
     }
-    int row_bad = 1, row_pos = 0, row_slot = 0;
-    if (MODE == G_QKV) { row_bad = a.row_bad[0]; row_pos = a.row_pos[0]; row_slot = a.row_slot[0]; }
+    int row_bad[MP], row_pos[MP], row_slot[MP];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) {
+        row_bad[m] = 1; row_pos[m] = 0; row_slot[m] = 0;
+        if (MODE == G_QKV && m < M) { row_bad[m] = a.row_bad[m]; row_pos[m] = a.row_pos[m]; row_slot[m] = a.row_slot[m]; }
+    }
 
-    // ---- x into registers
-    float xr[NCH][8];
-    {
-        const int src = (MODE == G_LMHEAD && a.gather) ? a.gather[0] : 0;
-        const float4 *x4 = reinterpret_cast<const float4 *>(NORM ? a.h_in + (size_t)src * a.ld_h : a.x_in);
+    // ---- x into registers: token row m, chunk u of this lane (a row past the call's count is a copy of row 0, never written)
+    float xr[MP][NCH][8];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) {
+        const int src = (MODE == G_LMHEAD && a.gather) ? a.gather[0] : (m < M ? m : 0);
+        const float4 *x4 = reinterpret_cast<const float4 *>(NORM ? a.h_in + (size_t)src * a.ld_h : a.x_in + (size_t)src * K);
         float4 xa[NCH], xb[NCH];
 #pragma unroll
         for (int u = 0; u < NCH; ++u) { xa[u] = x4[2 * (lane + 64 * u)]; xb[u] = x4[2 * (lane + 64 * u) + 1]; }
@@ -584,16 +591,16 @@ __global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
             const float inv = 1.0f / sqrtf(wave_sum(ss) / (float)K + a.eps);
 #pragma unroll
             for (int u = 0; u < NCH; ++u) {
-                xr[u][0] = xa[u].x * (inv * bf16_lo(gg[u].x)); xr[u][1] = xa[u].y * (inv * bf16_hi(gg[u].x));
-                xr[u][2] = xa[u].z * (inv * bf16_lo(gg[u].y)); xr[u][3] = xa[u].w * (inv * bf16_hi(gg[u].y));
-                xr[u][4] = xb[u].x * (inv * bf16_lo(gg[u].z)); xr[u][5] = xb[u].y * (inv * bf16_hi(gg[u].z));
-                xr[u][6] = xb[u].z * (inv * bf16_lo(gg[u].w)); xr[u][7] = xb[u].w * (inv * bf16_hi(gg[u].w));
+                xr[m][u][0] = xa[u].x * (inv * bf16_lo(gg[u].x)); xr[m][u][1] = xa[u].y * (inv * bf16_hi(gg[u].x));
+                xr[m][u][2] = xa[u].z * (inv * bf16_lo(gg[u].y)); xr[m][u][3] = xa[u].w * (inv * bf16_hi(gg[u].y));
+                xr[m][u][4] = xb[u].x * (inv * bf16_lo(gg[u].z)); xr[m][u][5] = xb[u].y * (inv * bf16_hi(gg[u].z));
+                xr[m][u][6] = xb[u].z * (inv * bf16_lo(gg[u].w)); xr[m][u][7] = xb[u].w * (inv * bf16_hi(gg[u].w));
             }
         } else {
 #pragma unroll
             for (int u = 0; u < NCH; ++u) {
-                xr[u][0] = xa[u].x; xr[u][1] = xa[u].y; xr[u][2] = xa[u].z; xr[u][3] = xa[u].w;
-                xr[u][4] = xb[u].x; xr[u][5] = xb[u].y; xr[u][6] = xb[u].z; xr[u][7] = xb[u].w;
+                xr[m][u][0] = xa[u].x; xr[m][u][1] = xa[u].y; xr[m][u][2] = xa[u].z; xr[m][u][3] = xa[u].w;
+                xr[m][u][4] = xb[u].x; xr[m][u][5] = xb[u].y; xr[m][u][6] = xb[u].z; xr[m][u][7] = xb[u].w;
             }
         }
     }
@@ -601,32 +608,35 @@ __global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
     SoftState st; st.init();
     const float lm_scale = MODE == G_LMHEAD ? a.seq_scale[0] : 1.f;
 
-    auto fma_chunk = [&](const uint4 &w, const float (&x)[8], float v) {
-        v = fmaf(bf16_lo(w.x), x[0], v); v = fmaf(bf16_hi(w.x), x[1], v); v = fmaf(bf16_lo(w.y), x[2], v); v = fmaf(bf16_hi(w.y), x[3], v);
-        v = fmaf(bf16_lo(w.z), x[4], v); v = fmaf(bf16_hi(w.z), x[5], v); v = fmaf(bf16_lo(w.w), x[6], v); v = fmaf(bf16_hi(w.w), x[7], v);
-        return v;
-    };
-
     for (int t = unit0; t < t_hi; t += 4) {
         int rows[RT];
         int head, pair0; bool rot;
         tile_rows(t, rows, head, pair0, rot);
         const uint4 *wp[RT];
-        float acc[RT], epi[RT];
+        float acc[RT][MP], epi[RT][MP];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) { wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K) + lane; acc[r] = 0.f; epi[r] = 0.f; }
+        for (int r = 0; r < RT; ++r) {
+            wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)rows[r] * K) + lane;
+#pragma unroll
+            for (int m = 0; m < MP; ++m) { acc[r][m] = 0.f; epi[r][m] = 0.f; }
+        }
         // what the epilogue needs from memory is requested ahead of the weight stream
         if (MODE == G_QKV) {
-            if (rot && !row_bad) {
+            if (rot) {
 #pragma unroll
-                for (int j = 0; j < P; ++j) {
-                    epi[2 * j] = a.rope_cos[(size_t)row_pos * half + pair0 + j];
-                    epi[2 * j + 1] = a.rope_sin[(size_t)row_pos * half + pair0 + j];
+                for (int m = 0; m < MP; ++m) if (!row_bad[m]) {
+#pragma unroll
+                    for (int j = 0; j < P; ++j) {
+                        epi[2 * j][m] = a.rope_cos[(size_t)row_pos[m] * half + pair0 + j];
+                        epi[2 * j + 1][m] = a.rope_sin[(size_t)row_pos[m] * half + pair0 + j];
+                    }
                 }
             }
         } else if (MODE == G_OPROJ) {
 #pragma unroll
-            for (int r = 0; r < RT; ++r) epi[r] = a.h_out[rows[r]];
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int m = 0; m < MP; ++m) if (m < M) epi[r][m] = a.h_out[(size_t)m * a.ld_h + rows[r]];
         }
         // groups of UG chunks; the first group of the first tile is already on its way
 #pragma unroll
@@ -648,53 +658,72 @@ __global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
             for (int u = 0; u < UG; ++u)
 #pragma unroll
                 for (int r = 0; r < RT; ++r)
-                    if (u0 + u < NCH) acc[r] = fma_chunk(wv[u][r], xr[u0 + u], acc[r]);
+                    if (u0 + u < NCH) {
+                        const uint4 w = wv[u][r];
+                        const float w0 = bf16_lo(w.x), w1 = bf16_hi(w.x), w2 = bf16_lo(w.y), w3 = bf16_hi(w.y);
+                        const float w4 = bf16_lo(w.z), w5 = bf16_hi(w.z), w6 = bf16_lo(w.w), w7 = bf16_hi(w.w);
+#pragma unroll
+                        for (int m = 0; m < MP; ++m) {
+                            const float (&x)[8] = xr[m][u0 + u];
+                            float v = acc[r][m];
+                            v = fmaf(w0, x[0], v); v = fmaf(w1, x[1], v); v = fmaf(w2, x[2], v); v = fmaf(w3, x[3], v);
+                            v = fmaf(w4, x[4], v); v = fmaf(w5, x[5], v); v = fmaf(w6, x[6], v); v = fmaf(w7, x[7], v);
+                            acc[r][m] = v;
+                        }
+                    }
         }
 #pragma unroll
-        for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int m = 0; m < MP; ++m) acc[r][m] = wave_sum(acc[r][m]);
         if (lane != 0) continue;
 
         // ---- epilogue (one lane)
-        if (MODE == G_QKV) {
-            if (row_bad) continue;
-            if (rot) {
 #pragma unroll
-                for (int j = 0; j < P; ++j) {
-                    const int i = pair0 + j;
-                    const float c = epi[2 * j], sn = epi[2 * j + 1], x0 = acc[2 * j], x1 = acc[2 * j + 1];
-                    const float y0 = x0 * c - x1 * sn, y1 = x1 * c + x0 * sn;
-                    if (head < a.n_q) {
-                        float *q = a.qbuf + head * a.head_dim;
-                        q[i] = y0; q[i + half] = y1;
-                    } else {
-                        const size_t base = ((((size_t)a.layer * a.max_seqs + row_slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + row_pos) * a.head_dim;
-                        a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
+        for (int m = 0; m < MP; ++m) {
+            if (m >= M) continue;
+            if (MODE == G_QKV) {
+                if (row_bad[m]) continue;
+                const int pos = row_pos[m], slot = row_slot[m];
+                if (rot) {
+#pragma unroll
+                    for (int j = 0; j < P; ++j) {
+                        const int i = pair0 + j;
+                        const float c = epi[2 * j][m], sn = epi[2 * j + 1][m], x0 = acc[2 * j][m], x1 = acc[2 * j + 1][m];
+                        const float y0 = x0 * c - x1 * sn, y1 = x1 * c + x0 * sn;
+                        if (head < a.n_q) {
+                            float *q = a.qbuf + (size_t)m * a.n_q * a.head_dim + head * a.head_dim;
+                            q[i] = y0; q[i + half] = y1;
+                        } else {
+                            const size_t base = ((((size_t)a.layer * a.max_seqs + slot) * a.n_kv + (head - a.n_q)) * a.max_ctx + pos) * a.head_dim;
+                            a.kcache[base + i] = f32_to_bf16(y0); a.kcache[base + i + half] = f32_to_bf16(y1);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < RT; ++j) {
+                        const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
+                        const int vh = vr / a.head_dim, e = vr % a.head_dim;
+                        const size_t base = (((size_t)a.layer * a.max_seqs + slot) * a.n_kv + vh) * (size_t)a.max_ctx * a.head_dim;
+                        a.vcache[base + (size_t)e * a.max_ctx + pos] = f32_to_bf16(acc[j][m]);     // V is stored [hd][position]
                     }
                 }
-            } else {
+            } else if (MODE == G_GATEUP) {
 #pragma unroll
-                for (int j = 0; j < RT; ++j) {
-                    const int vr = rows[j] - (a.n_q + a.n_kv) * a.head_dim;      // index inside the V section
-                    const int vh = vr / a.head_dim, e = vr % a.head_dim;
-                    const size_t base = (((size_t)a.layer * a.max_seqs + row_slot) * a.n_kv + vh) * (size_t)a.max_ctx * a.head_dim;
-                    a.vcache[base + (size_t)e * a.max_ctx + row_pos] = f32_to_bf16(acc[j]);     // V is stored [hd][position]
+                for (int j = 0; j < P; ++j) {
+                    const float g = acc[2 * j][m], up = acc[2 * j + 1][m];
+                    a.act[(size_t)m * a.d_ffn + t * P + j] = g / (1.0f + expf(-g)) * up;
                 }
-            }
-        } else if (MODE == G_GATEUP) {
+            } else if (MODE == G_OPROJ) {
 #pragma unroll
-            for (int j = 0; j < P; ++j) {
-                const float g = acc[2 * j], up = acc[2 * j + 1];
-                a.act[t * P + j] = g / (1.0f + expf(-g)) * up;
-            }
-        } else if (MODE == G_OPROJ) {
+                for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[(size_t)m * a.ld_h + t * RT + j] = epi[j][m] + acc[j][m];
+            } else {   // G_LMHEAD (MP == 1)
 #pragma unroll
-            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) a.h_out[t * RT + j] = epi[j] + acc[j];
-        } else {   // G_LMHEAD
-#pragma unroll
-            for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
-                const float lg = acc[j] * lm_scale;
-                st.push(lg, t * RT + j);
-                if (a.logits) a.logits[t * RT + j] = lg;
+                for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
+                    const float lg = acc[j][m] * lm_scale;
+                    st.push(lg, t * RT + j);
+                    if (a.logits) a.logits[t * RT + j] = lg;
+                }
             }
         }
     }
@@ -719,54 +748,75 @@ __global__ void __launch_bounds__(256) k_gemv_reg(GemvArgs a) {
 // barrier before the weight stream starts and no LDS footprint that limits the workgroups per CU.
 // grid: workgroups share the ceil(N / RT) row tiles in contiguous ranges.
 // ------------------------------------------------------------------------------------------------
-template <int RT, int UNR>
+template <int RT, int UNR, int MP = 1>
 __global__ void __launch_bounds__(256) k_down_direct(GemvArgs a) {
-    __shared__ float red[2][4][RT];
-    const int K = a.K, n_chunks = K >> 3;
+    __shared__ float red[2][4][RT * MP];
+    const int K = a.K, n_chunks = K >> 3, M = a.m_rows;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x, nwg = gridDim.x;
     const int n_tiles = (a.N + RT - 1) / RT;
     const int t_lo = (int)(((unsigned)n_tiles * (unsigned)wg) / (unsigned)nwg), t_hi = (int)(((unsigned)n_tiles * (unsigned)(wg + 1)) / (unsigned)nwg);
     const int c0 = wave * 64 + lane, cstride = 256;
-    const float4 *x4 = reinterpret_cast<const float4 *>(a.x_in);
+    // token row m reads its own activation row; a row past the call's count reads row 0 again and is never written
+    const float4 *x4[MP];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) x4[m] = reinterpret_cast<const float4 *>(a.x_in + (size_t)(m < M ? m : 0) * K);
     int parity = 0;
     for (int t = t_lo; t < t_hi; ++t) {
-        float acc[RT], epi[RT];
+        float acc[RT][MP], epi[RT][MP];
         const uint4 *wp[RT];
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
             const int row = min(t * RT + r, a.N - 1);
             wp[r] = reinterpret_cast<const uint4 *>(a.W + (size_t)row * K);
-            acc[r] = 0.f;
-            epi[r] = a.h_out[row];                                         // requested ahead of the weight stream
+#pragma unroll
+            for (int m = 0; m < MP; ++m) {
+                acc[r][m] = 0.f;
+                epi[r][m] = a.h_out[(size_t)(m < M ? m : 0) * a.ld_h + row];   // requested ahead of the weight stream
+            }
         }
 #pragma unroll UNR
         for (int c = c0; c < n_chunks; c += cstride) {
             uint4 wv[RT];
 #pragma unroll
             for (int r = 0; r < RT; ++r) wv[r] = load_stream(wp[r] + c);
-            const float4 xa = x4[2 * c], xb = x4[2 * c + 1];
+            float4 xa[MP], xb[MP];
+#pragma unroll
+            for (int m = 0; m < MP; ++m) { xa[m] = x4[m][2 * c]; xb[m] = x4[m][2 * c + 1]; }
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
                 const uint4 w = wv[r];
-                float v = acc[r];
-                v = fmaf(bf16_lo(w.x), xa.x, v); v = fmaf(bf16_hi(w.x), xa.y, v); v = fmaf(bf16_lo(w.y), xa.z, v); v = fmaf(bf16_hi(w.y), xa.w, v);
-                v = fmaf(bf16_lo(w.z), xb.x, v); v = fmaf(bf16_hi(w.z), xb.y, v); v = fmaf(bf16_lo(w.w), xb.z, v); v = fmaf(bf16_hi(w.w), xb.w, v);
-                acc[r] = v;
+                const float w0 = bf16_lo(w.x), w1 = bf16_hi(w.x), w2 = bf16_lo(w.y), w3 = bf16_hi(w.y);
+                const float w4 = bf16_lo(w.z), w5 = bf16_hi(w.z), w6 = bf16_lo(w.w), w7 = bf16_hi(w.w);
+#pragma unroll
+                for (int m = 0; m < MP; ++m) {
+                    float v = acc[r][m];
+                    v = fmaf(w0, xa[m].x, v); v = fmaf(w1, xa[m].y, v); v = fmaf(w2, xa[m].z, v); v = fmaf(w3, xa[m].w, v);
+                    v = fmaf(w4, xb[m].x, v); v = fmaf(w5, xb[m].y, v); v = fmaf(w6, xb[m].z, v); v = fmaf(w7, xb[m].w, v);
+                    acc[r][m] = v;
+                }
             }
         }
 #pragma unroll
-        for (int r = 0; r < RT; ++r) acc[r] = wave_sum(acc[r]);
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int m = 0; m < MP; ++m) acc[r][m] = wave_sum(acc[r][m]);
         if (lane == 0) {
 #pragma unroll
-            for (int r = 0; r < RT; ++r) red[parity][wave][r] = acc[r];
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int m = 0; m < MP; ++m) red[parity][wave][r * MP + m] = acc[r][m];
         }
         __syncthreads();
         if (tid == 0) {
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
                 const int row = t * RT + r;
-                if (row < a.N) a.h_out[row] = epi[r] + (red[parity][0][r] + red[parity][1][r] + red[parity][2][r] + red[parity][3][r]);
+#pragma unroll
+                for (int m = 0; m < MP; ++m)
+                    if (row < a.N && m < M)
+                        a.h_out[(size_t)m * a.ld_h + row] = epi[r][m] + (red[parity][0][r * MP + m] + red[parity][1][r * MP + m] +
+                                                                        red[parity][2][r * MP + m] + red[parity][3][r * MP + m]);
             }
         }
         parity ^= 1;

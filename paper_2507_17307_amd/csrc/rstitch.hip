@@ -92,6 +92,7 @@ int attn_pairs_cap(const rs_config &c) {
 }
 
 constexpr int LM_PARTS_CAP = 4096;
+constexpr int FMA_MAX_ROWS = 4;                     // calls of up to this many token rows run on the FMA GEMV kernels
 constexpr int GEMM_KSPLIT_MAX = rs::KSPLIT_MAX;     // workgroup-level K splits of the multi-row projections, at most
 
 Layout make_layout(const rs_config &c) {
@@ -114,7 +115,7 @@ Layout make_layout(const rs_config &c) {
     L.qbuf = take((size_t)c.max_rows * qdim * 4);
     L.attn_out = take((size_t)c.max_rows * qdim * 4);
     L.attn_pl = take((size_t)3 * c.max_rows * qdim * 2);
-    L.act = take((size_t)c.d_ffn * 4);
+    L.act = take((size_t)(c.max_rows < FMA_MAX_ROWS ? c.max_rows : FMA_MAX_ROWS) * c.d_ffn * 4);
     L.act_pl = take((size_t)3 * c.max_rows * c.d_ffn * 2);
     L.attn_rows_x_splits = attn_pairs_cap(c);
     L.attn_part = take((size_t)L.attn_rows_x_splits * c.n_q_heads * (c.head_dim + 4) * 4);
@@ -193,29 +194,21 @@ rs_status launch_gemv_mp(GemvArgs &a, int blocks, hipStream_t st, const char *na
     return RS_OK;
 }
 
-// Single-row launches.  (gemv_phase can be compiled for 2, 4 or 8 token rows as well; on this chip the
-// matrix-core path overtakes those variants already at two rows, so only the one-row form is built.)
-// PRE: early weight request.
-template <int MODE, int RT, int KS, int UNR, int PRE = 0>
-rs_status launch_gemv(const rs_model *m, GemvArgs &a, int mp, int blocks, hipStream_t st, const char *name) {
-    (void)m;
-    if (mp != 1) return fail(RS_EINVAL, "internal: %s launched for %d rows", name, mp);
-    return launch_gemv_mp<MODE, RT, KS, UNR, 1, PRE>(a, blocks, st, name);
-}
 
-// register-resident x (k_gemv_reg): K must be 512 * NCH with NCH one of 3, 7, 10 (d_model 1536, 3584, 5120)
-template <int MODE, int RT>
+// register-resident x (k_gemv_reg): K must be 512 * NCH with NCH one of 3, 7, 10 (d_model 1536, 3584, 5120);
+// MP token rows need MP * K / 64 registers per lane for x, so MP * NCH stays at or below 14
+template <int MODE, int RT, int MP = 1>
 rs_status launch_gemv_reg(GemvArgs &a, int blocks, hipStream_t st, const char *name) {
-    switch (a.K) {
-        case 1536: hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 3, 3>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 3584: hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 7, (RT >= 8 ? 2 : 4)>), dim3(blocks), dim3(256), 0, st, a); break;
-        case 5120: hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 10, (RT >= 8 ? 2 : 5)>), dim3(blocks), dim3(256), 0, st, a); break;
-        default: return fail(RS_EINVAL, "internal: %s with K = %d", name, a.K);
-    }
+    if (a.K == 1536) hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 3, 3, MP>), dim3(blocks), dim3(256), 0, st, a);
+    else if (a.K == 3584 && MP <= 2) {
+        if constexpr (MP <= 2) hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 7, (RT >= 8 ? 2 : 4), MP>), dim3(blocks), dim3(256), 0, st, a);
+    } else if (a.K == 5120 && MP == 1) {
+        if constexpr (MP == 1) hipLaunchKernelGGL((k_gemv_reg<MODE, RT, 10, (RT >= 8 ? 2 : 5), MP>), dim3(blocks), dim3(256), 0, st, a);
+    } else return fail(RS_EINVAL, "internal: %s with K = %d and %d rows", name, a.K, MP);
     RS_LAUNCHED(name);
     return RS_OK;
 }
-inline bool reg_k(int K) { return K == 1536 || K == 3584 || K == 5120; }
+inline bool reg_fits(int K, int mp) { return (K == 1536 && mp <= 4) || (K == 3584 && mp <= 2) || (K == 5120 && mp == 1); }
 
 // Launch shapes from sweeps on MI355X: about three workgroups per CU for matrices under ~128 MB,
 // two above; the down projection gets one tile per workgroup.
@@ -455,6 +448,99 @@ rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_to
     return RS_OK;
 }
 
+// One decoder layer on the FMA kernels for a call of MP (1, 2 or 4) token-row slots: QKV, attention, O-proj,
+// gate/up, down.  Every phase reads the weights once and carries the rows side by side.
+template <int MP, typename Tic, typename Toc>
+rs_status fma_layer(rs_model *m, int l, GemvArgs &g, AttnArgs &aa, int n_rows, int n_splits, bool spans, hipStream_t st,
+                    Tic tic, Toc toc) {
+    const rs_config &c = m->cfg;
+    const Layout &L = m->lay;
+    const GemvPlan &pl = m->plan;
+    const int hd = c.head_dim, qdim = c.n_q_heads * hd, qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * hd;
+    float *h = m->at<float>(L.h);
+    rs_status rc;
+    // QKV (+ RMSNorm, RoPE, KV write)
+    g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
+    tic(RS_PHASE_QKV, l);
+    // d_model 1536 or 3584: the activation vectors in registers, no LDS (one row: 1.5B decode step -2 %, 7B -0.2 %)
+    if (reg_fits(c.d_model, MP) && c.d_model <= 3584) rc = launch_gemv_reg<G_QKV, 2, MP>(g, pl.qkv_blocks, st, "gemv_reg_qkv");
+    else if constexpr (MP == 1) {
+        if (pl.qkv_rt == 4) rc = launch_gemv_mp<G_QKV, 4, 1, 2, 1, 3>(g, pl.qkv_blocks, st, "gemv_qkv");
+        // d_model <= 1536: a row is three chunks per lane, all requested before the prologue
+        else if (c.d_model <= 1536) rc = launch_gemv_mp<G_QKV, 2, 1, 1, 1, 3>(g, pl.qkv_blocks, st, "gemv_qkv");
+        else rc = launch_gemv_mp<G_QKV, 2, 1, 2, 1, 0>(g, pl.qkv_blocks, st, "gemv_qkv");
+    } else {
+        if (pl.qkv_rt == 4) rc = launch_gemv_mp<G_QKV, 4, 1, 2, MP, 0>(g, pl.qkv_blocks, st, "gemv_qkv");
+        else rc = launch_gemv_mp<G_QKV, 2, 1, 2, MP, 0>(g, pl.qkv_blocks, st, "gemv_qkv");
+    }
+    toc(RS_PHASE_QKV, l);
+    if (rc) return rc;
+    // attention
+    tic(RS_PHASE_ATTN, l);
+    switch (hd) {
+        case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+        case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+        default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+    }
+    toc(RS_PHASE_ATTN, l);
+    if (rc) return rc;
+    // O projection + residual
+    g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
+    g.x_in = m->at<float>(L.attn_out);
+    tic(RS_PHASE_OPROJ, l);
+    // 1536, 3584 or 5120 input channels: the attention output in registers (one row: 1.5B decode step -2 %, 7B -0.8 %)
+    if (reg_fits(qdim, MP)) rc = launch_gemv_reg<G_OPROJ, 2, MP>(g, pl.o_blocks, st, "gemv_reg_oproj");
+    else if constexpr (MP == 1) {
+        if (pl.o_all_early) rc = launch_gemv_mp<G_OPROJ, 2, 1, 1, 1, 7>(g, pl.o_blocks, st, "gemv_oproj");
+        else rc = launch_gemv_mp<G_OPROJ, 2, 1, 2, 1, 4>(g, pl.o_blocks, st, "gemv_oproj");
+    } else rc = launch_gemv_mp<G_OPROJ, 2, 1, 2, MP, 0>(g, pl.o_blocks, st, "gemv_oproj");
+    toc(RS_PHASE_OPROJ, l);
+    if (rc) return rc;
+    // gate/up (+ RMSNorm, SwiGLU)
+    g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
+    tic(RS_PHASE_GATEUP, l);
+    if constexpr (MP == 1) {
+        // large matrices run two workgroups per CU, which leaves registers for the early weight request; the
+        // early chunks and the unroll are picked so that the chunks left per lane (d_model / 512 minus the
+        // early ones) are a whole number of unrolled rounds: 7 = 3 + 4 (7B shape), 10 = 4 + 3 * 2 (14B/32B shapes,
+        // 48 us against 51 us with the other variant)
+        if (pl.gu_early && (c.d_model / 512 - 3) % 4 != 0 && (c.d_model / 512 - 4) % 2 == 0)
+            rc = launch_gemv_mp<G_GATEUP, 4, 1, 2, 1, 4>(g, pl.gu_blocks, st, "gemv_gateup");
+        else if (pl.gu_early) rc = launch_gemv_mp<G_GATEUP, 4, 1, 4, 1, 3>(g, pl.gu_blocks, st, "gemv_gateup");
+        else rc = launch_gemv_mp<G_GATEUP, 2, 1, 1, 1, 3>(g, pl.gu_blocks, st, "gemv_gateup");
+    } else {
+        // several rows: with the rows' activation vectors in registers there is no LDS traffic that grows with the
+        // row count (two rows: 1.5B call 1.24 -> 1.22 ms, 7B 3.26 -> 3.14 ms against the LDS-staged kernel)
+        if (reg_fits(c.d_model, MP)) rc = launch_gemv_reg<G_GATEUP, 2, MP>(g, pl.gu_blocks, st, "gemv_reg_gateup");
+        else
+        if (pl.gu_early) rc = launch_gemv_mp<G_GATEUP, 4, 1, 2, MP, 0>(g, pl.gu_blocks, st, "gemv_gateup");
+        else rc = launch_gemv_mp<G_GATEUP, 2, 1, 2, MP, 0>(g, pl.gu_blocks, st, "gemv_gateup");
+    }
+    toc(RS_PHASE_GATEUP, l);
+    if (rc) return rc;
+    // down + residual
+    g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
+    g.x_in = m->at<float>(L.act);
+    tic(RS_PHASE_DOWN, l);
+    // x is read straight from global memory next to the weights (no LDS staging); rows per tile by width,
+    // from same-process A/B runs of whole decode steps: two-row tiles at three workgroups per CU up to
+    // d_model 2048 (1.5B step 1.153 -> 1.082 ms against the LDS-staged kernel), seven-row tiles for 3584
+    // (7B: 2.994 -> 2.850 ms), five-row tiles at four workgroups per CU above (14B: 6.08 -> 5.86 ms,
+    // 32B: 13.16 -> 11.80 ms)
+    {
+        const int tiles = (c.d_model + pl.down_rt - 1) / pl.down_rt;
+        const int blocks = pl.down_blocks < tiles ? pl.down_blocks : tiles;
+        switch (pl.down_rt) {
+            case 2: hipLaunchKernelGGL((k_down_direct<2, 4, MP>), dim3(blocks), dim3(256), 0, st, g); break;
+            case 7: hipLaunchKernelGGL((k_down_direct<7, (MP > 1 ? 1 : 2), MP>), dim3(blocks), dim3(256), 0, st, g); break;
+            default: hipLaunchKernelGGL((k_down_direct<5, (MP > 1 ? 1 : 2), MP>), dim3(blocks), dim3(256), 0, st, g); break;
+        }
+        RS_LAUNCHED("down_direct");
+    }
+    toc(RS_PHASE_DOWN, l);
+    return RS_OK;
+}
+
 // One forward invocation over n_rows token rows of n_seqs sequences, one kernel per phase.
 rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, const int *d_tokens,
                           const int *d_span_off, const int *d_pos0, const float *d_scale, float tau, int active,
@@ -480,10 +566,15 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
     const int n_splits = attn_splits(c, L, n_rows);
     const bool spans = n_rows > n_seqs;
 
-    // a single row goes through the FMA GEMV kernels; two rows or more go through the MFMA kernels
-    // (measured: 3.5 ms against 3.8 ms for a two-row call of the 7B shape)
-    const int mp = 1;
-    const bool single = n_rows == 1 && (size_t)c.d_model <= (size_t)GEMV_LDS_FLOATS && (size_t)qdim <= (size_t)GEMV_LDS_FLOATS;
+    // up to four token rows go through the FMA GEMV kernels (six kernels per layer, rows side by side against one
+    // weight stream); more rows go through the matrix-core kernels
+    // Measured per call (GPU time, context ~4570): two rows 1.22 ms against 1.63 on the matrix-core path for the 1.5B
+    // shape, 3.14 against 3.52 for the 7B shape, 6.93 / 7.37 for the 14B, 13.46 / 14.02 for the 32B; three and four
+    // rows 1.55 / 1.59 against 1.69 / 1.71 for the 1.5B shape but 4.10 / 4.35 against 3.67 / 3.72 for the 7B shape
+    // (the four-row variants of a 3584-wide model no longer fit the registers and fall back to LDS staging).
+    const int mp = n_rows == 1 ? 1 : (n_rows == 2 ? 2 : 4);
+    const bool few = n_rows <= 2 || (n_rows <= FMA_MAX_ROWS && c.d_model <= 2048);
+    const bool single = few && (size_t)c.d_model * mp <= (size_t)GEMV_LDS_FLOATS && (size_t)qdim * mp <= (size_t)GEMV_LDS_FLOATS;
     rs_status rc;
     float *pend_part = nullptr; int pend_ks = 0; size_t pend_stride = 0;   // multi-row path: partial sums of the last down projection
     // optional event pair around one chosen kernel (rs_set_phase_timer)
@@ -512,75 +603,11 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.rope_cos = m->at<float>(L.rope_cos); g.rope_sin = m->at<float>(L.rope_sin);
             g.qbuf = m->at<float>(L.qbuf); g.kcache = m->kv_k; g.vcache = m->kv_v;
             g.act = m->at<float>(L.act); g.h_out = h;
-
-            const GemvPlan &pl = m->plan;
-            // QKV (+ RMSNorm, RoPE, KV write)
-            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.h_in = h; g.gain = m->attn_norm[l]; g.x_in = nullptr;
-            tic(RS_PHASE_QKV, l);
-            // d_model 1536 or 3584: the activation vector in registers, no LDS (1.5B decode step -2 %, 7B -0.2 %)
-            if (reg_k(c.d_model) && c.d_model <= 3584) rc = launch_gemv_reg<G_QKV, 2>(g, pl.qkv_blocks, st, "gemv_reg_qkv");
-            else
-            if (pl.qkv_rt == 4) rc = launch_gemv<G_QKV, 4, 1, 2, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
-            // d_model <= 1536: a row is three chunks per lane, all requested before the prologue (1.5B step -1 %)
-            else if (c.d_model <= 1536) rc = launch_gemv<G_QKV, 2, 1, 1, 3>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
-            else rc = launch_gemv<G_QKV, 2, 1, 2>(m, g, mp, pl.qkv_blocks, st, "gemv_qkv");
-            toc(RS_PHASE_QKV, l);
-            if (rc) return rc;
-            // attention
-            tic(RS_PHASE_ATTN, l);
-            switch (hd) {
-                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
-                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
-                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+            switch (mp) {
+                case 1: rc = fma_layer<1>(m, l, g, aa, n_rows, n_splits, spans, st, tic, toc); break;
+                case 2: rc = fma_layer<2>(m, l, g, aa, n_rows, n_splits, spans, st, tic, toc); break;
+                default: rc = fma_layer<4>(m, l, g, aa, n_rows, n_splits, spans, st, tic, toc); break;
             }
-            toc(RS_PHASE_ATTN, l);
-            if (rc) return rc;
-            // O projection + residual
-            g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim; g.h_in = nullptr; g.gain = nullptr;
-            g.x_in = m->at<float>(L.attn_out);
-            tic(RS_PHASE_OPROJ, l);
-            // 7B shape (25.7 MB, seven chunks per lane and row): all seven early at two workgroups per CU, step -0.5 %
-            // 1536, 3584 or 5120 input channels: the attention output in registers (1.5B decode step -2 %, 7B -0.8 %)
-            if (reg_k(qdim)) rc = launch_gemv_reg<G_OPROJ, 2>(g, pl.o_blocks, st, "gemv_reg_oproj");
-            else
-            if (pl.o_all_early) rc = launch_gemv<G_OPROJ, 2, 1, 1, 7>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
-            else rc = launch_gemv<G_OPROJ, 2, 1, 2, 4>(m, g, mp, pl.o_blocks, st, "gemv_oproj");
-            toc(RS_PHASE_OPROJ, l);
-            if (rc) return rc;
-            // gate/up (+ RMSNorm, SwiGLU)
-            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.h_in = h; g.gain = m->mlp_norm[l]; g.x_in = nullptr;
-            tic(RS_PHASE_GATEUP, l);
-            // large matrices run two workgroups per CU, which leaves registers for the early weight request; the
-            // early chunks and the unroll are picked so that the chunks left per lane (d_model / 512 minus the
-            // early ones) are a whole number of unrolled rounds: 7 = 3 + 4 (7B shape), 10 = 4 + 3 * 2 (14B/32B shapes,
-            // 48 us against 51 us with the other variant)
-            if (pl.gu_early && mp == 1 && (c.d_model / 512 - 3) % 4 != 0 && (c.d_model / 512 - 4) % 2 == 0)
-                rc = launch_gemv<G_GATEUP, 4, 1, 2, 4>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
-            else if (pl.gu_early && mp == 1) rc = launch_gemv<G_GATEUP, 4, 1, 4, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
-            else rc = launch_gemv<G_GATEUP, 2, 1, 1, 3>(m, g, mp, pl.gu_blocks, st, "gemv_gateup");
-            toc(RS_PHASE_GATEUP, l);
-            if (rc) return rc;
-            // down + residual
-            g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn; g.h_in = nullptr; g.gain = nullptr;
-            g.x_in = m->at<float>(L.act);
-            tic(RS_PHASE_DOWN, l);
-            // x is read straight from global memory next to the weights (no LDS staging); rows per tile by width,
-            // from same-process A/B runs of whole decode steps: two-row tiles at three workgroups per CU up to
-            // d_model 2048 (1.5B step 1.153 -> 1.082 ms against the LDS-staged kernel), seven-row tiles for 3584
-            // (7B: 2.994 -> 2.850 ms), five-row tiles at four workgroups per CU above (14B: 6.08 -> 5.86 ms,
-            // 32B: 13.16 -> 11.80 ms)
-            {
-                const int tiles = (c.d_model + pl.down_rt - 1) / pl.down_rt;
-                const int blocks = pl.down_blocks < tiles ? pl.down_blocks : tiles;
-                switch (pl.down_rt) {
-                    case 2: hipLaunchKernelGGL((k_down_direct<2, 4>), dim3(blocks), dim3(256), 0, st, g); break;
-                    case 7: hipLaunchKernelGGL((k_down_direct<7, 2>), dim3(blocks), dim3(256), 0, st, g); break;
-                    default: hipLaunchKernelGGL((k_down_direct<5, 2>), dim3(blocks), dim3(256), 0, st, g); break;
-                }
-                RS_LAUNCHED("down_direct");
-                rc = RS_OK;
-            }
-            toc(RS_PHASE_DOWN, l);
             if (rc) return rc;
         } else {
             uint16_t *xn = m->at<uint16_t>(L.xn);
@@ -647,10 +674,13 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
         n_parts = m->plan.lm_blocks; g.n_parts = n_parts;
-        const int mp_lm = 1;
         tic(RS_PHASE_LMHEAD, 0);
-        if ((rc = launch_gemv<G_LMHEAD, 8, 1, 2>(m, g, mp_lm, m->plan.lm_blocks, st, "gemv_lmhead"))) return rc;
+        // one output row per sequence (the last row of its span)
+        if (n_seqs == 1) rc = launch_gemv_mp<G_LMHEAD, 8, 1, 2, 1, 0>(g, m->plan.lm_blocks, st, "gemv_lmhead");
+        else if (n_seqs == 2) rc = launch_gemv_mp<G_LMHEAD, 8, 1, 2, 2, 0>(g, m->plan.lm_blocks, st, "gemv_lmhead");
+        else rc = launch_gemv_mp<G_LMHEAD, 8, 1, 1, 4, 0>(g, m->plan.lm_blocks, st, "gemv_lmhead");
         toc(RS_PHASE_LMHEAD, 0);
+        if (rc) return rc;
     } else {
         uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
         const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
