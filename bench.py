@@ -298,12 +298,12 @@ def bench_batched(args, wl) -> int:
     log(f"[bench] weights generated on the GPU in {time.time() - t0:.1f}s")
     prompts = [W.make_prompt(wl, seq=b).tolist() for b in range(nb)]
     n_total = args.warmup + args.steps
-    max_ctx = max(len(p) for p in prompts) + max(n_total, args.tau_steps or 0) + 8
+    n_tau = args.tau_steps or 128
+    max_ctx = max(len(p) for p in prompts) + max(n_total, n_tau) + 8
     slm = P.Model(w_s, max_ctx=max_ctx, max_seqs=nb, max_rows=64)
     llm = P.Model(w_l, max_ctx=max_ctx, max_seqs=nb, max_rows=64)
     batch = StitchedBatch(slm, llm, max_ctx, [W.logit_scale(wl, 0, max_ctx + 1, seq=b) for b in range(nb)])
     ln_v = math.log(wl.slm.vocab)
-    n_tau = args.tau_steps or 128
     solo = batch.generate(prompts, 2.0, n_tau, single_model=SLM)
     tau = W.pick_tau([t.h_norm for r in solo for t in r.trace], wl.tau_percentile, 4e-3 / ln_v)
     log(f"[bench] small-model-only run of {n_tau} tokens per sequence; tau = {tau:.6f}")

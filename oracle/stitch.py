@@ -137,3 +137,27 @@ def generate_plus(prompt: Sequence[int], forward_state, router_says_llm: Callabl
         seq.append(token)
         res.output.append(token)
     return res
+
+
+def generate_random(prompt: Sequence[int], forward: Forward, p_slm: float, u_of_pos: Callable[[int], float],
+                    n_tokens: int) -> StitchResult:
+    """Random-routing baseline (Section "Experiments", paragraph "Latency-accuracy trade-off"): every
+    token is assigned to the small model with a fixed probability p_slm and to the large model
+    otherwise, whatever the distributions look like.  The token at absolute position t goes to the
+    small model iff u_of_pos(t) < p_slm (u uniform in (0, 1), drawn per position); the assigned model
+    first catches up with the tokens it has not seen (same cache bookkeeping as Algorithm 1) and its
+    token is always kept: nothing is discarded, since the assignment does not look at the step.
+    """
+    seq = list(prompt)
+    n_kv = [0, 0]
+    res = StitchResult()
+    while len(res.output) < n_tokens:
+        model = SLM if u_of_pos(len(seq)) < p_slm else LLM
+        pos0 = n_kv[model]
+        span = seq[pos0:]
+        token, h = forward(model, span, pos0)
+        n_kv[model] = len(seq)
+        res.trace.append(Invocation(model, pos0, span, token, h, False, True))
+        seq.append(token)
+        res.output.append(token)
+    return res

@@ -109,6 +109,31 @@ class StitchedPair:
         self._forward(model, 0, n0, tau)
         self.stream.synchronize()
 
+    def generate_random(self, prompt: Sequence[int], p_slm: float, u_table: Sequence[float], n_tokens: int) -> StitchRun:
+        """Random-routing baseline (Section "Experiments", "Latency-accuracy trade-off"): the token at absolute
+        position t is produced by the small model iff u_table[t] < p_slm, by the large model otherwise; the
+        assigned model catches up with what it has not seen, its token is always kept.  The assignment uses no
+        output of the step, so it is made here before the call; tau is set so that no record is flagged HI."""
+        n0 = len(prompt)
+        if n0 + n_tokens > self.max_ctx + 1:
+            raise ValueError("prompt + tokens exceed max_ctx")
+        self.seq_np[:n0] = np.asarray(prompt, dtype=np.int32)
+        length, n_kv, run, o = n0, [0, 0], StitchRun(), self._o
+        while len(run.output) < n_tokens:
+            model = SLM if float(u_table[length]) < p_slm else LLM
+            pos0 = n_kv[model]
+            self._forward(model, pos0, length, 2.0)
+            self.stream.synchronize()
+            n_kv[model] = length
+            token, flags = int(self.stage_i[o]), int(self.stage_i[o + 1]) & 0xFFFFFFFF
+            if flags & (B.FLAG_BADARG | B.FLAG_NONFINITE | B.FLAG_ABORTED):
+                raise RuntimeError(f"router flagged the step: flags={flags} model={model} pos0={pos0}")
+            run.trace.append(Invocation(model, pos0, length - pos0, token, float(self.stage_f[o + 3]), flags))
+            self.seq_np[length] = token
+            length += 1
+            run.output.append(token)
+        return run
+
     def generate(self, prompt: Sequence[int], tau: float, n_tokens: int, single_model: Optional[int] = None,
                  keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None,
                  llm_prefilled: bool = False, router_plus: Optional[B.RouterPlus] = None) -> StitchRun:
@@ -122,7 +147,9 @@ class StitchedPair:
             raise ValueError("prompt + tokens exceed max_ctx")
         self.seq_np[:n0] = np.asarray(prompt, dtype=np.int32)
         length = n0
-        n_kv = [0, n0 if llm_prefilled else 0]
+        # a prefilled large model still has to produce a distribution the first time it is asked, which may be before
+        # any token was accepted: it re-runs the last prompt token then (the same K/V row is written again)
+        n_kv = [0, n0 - 1 if llm_prefilled else 0]
         active = SLM if single_model is None else single_model
         run = StitchRun()
         sync = self.stream.synchronize
@@ -248,7 +275,8 @@ class StitchedBatch:
                 raise ValueError("prompt + tokens exceed max_ctx")
             self.seqs[b][:len(p)] = np.asarray(p, dtype=np.int32)
             lengths.append(len(p))
-        n_kv = [[0] * nb, list(lengths) if llm_prefilled else [0] * nb]
+        # (a prefilled large model re-runs the last prompt token at its first participation, see StitchedPair.generate)
+        n_kv = [[0] * nb, [n - 1 for n in lengths] if llm_prefilled else [0] * nb]
         active = [SLM if single_model is None else single_model] * nb
         runs = [StitchRun() for _ in range(nb)]
         live = set(range(nb))

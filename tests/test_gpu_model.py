@@ -258,6 +258,28 @@ def test_live_stitched_run_through_the_host_driver_matches_the_oracle_run(decode
     assert again.output == run.output and [t.flags for t in again.trace] == [t.flags for t in run.trace]
 
 
+def test_random_routing_baseline_run_matches_the_oracle_run():
+    """The random-routing baseline (each token assigned to the small model with probability p) live on the GPU
+    against the oracle's run of it on config 1: same model, first position and span per invocation, same tokens,
+    entropies within tolerance."""
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedPair
+    wl = W.WORKLOADS["cfg1_tiny_pair"]
+    ws, wl_ = W.make_weights(wl.slm, wl.seed, 0), W.make_weights(wl.llm, wl.seed, 1)
+    prompt = W.make_prompt(wl).tolist()
+    scales = W.logit_scale(wl, 0, wl.max_ctx + 2)
+    u = W.uniform01(wl.seed, 4242, 0, wl.max_ctx + 2).tolist()
+    models = [decoder.OracleModel(ws, wl.max_ctx + 1), decoder.OracleModel(wl_, wl.max_ctx + 1)]
+    res = stitch.generate_random(prompt, stitch.decoder_forward(models, lambda p: float(scales[p])), 0.7, lambda t: u[t], wl.n_decode)
+    n_llm = sum(1 for t in res.trace if t.model == 1)
+    assert 5 < n_llm < wl.n_decode - 5 and any(len(t.span) > 2 and t.pos0 > 0 for t in res.trace)
+    gpu = [P.Model(x.to("cuda"), max_ctx=wl.max_ctx + 1, max_rows=64) for x in (ws, wl_)]
+    run = StitchedPair(gpu[0], gpu[1], wl.max_ctx, scales).generate_random(prompt, 0.7, u, wl.n_decode)
+    assert run.output == res.output
+    assert [(t.model, t.pos0, t.n_rows) for t in run.trace] == [(t.model, t.pos0, len(t.span)) for t in res.trace]
+    assert max(abs(a.h_norm - b.h_norm) for a, b in zip(run.trace, res.trace)) <= 1e-3 / math.log(1024)
+
+
 def test_batched_stitched_run_with_per_sequence_routing_matches_per_sequence_oracle_runs(decode_path):
     """Four sequences with different prompt lengths share the two tiny models (one KV slot each) and are
     routed independently by the batched host driver; each must reproduce the oracle's single-sequence

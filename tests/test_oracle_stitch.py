@@ -140,3 +140,40 @@ def test_stitched_run_is_independent_of_how_catchup_spans_are_fed():
     assert alt.output == ref.output
     assert [(t.model, t.accept) for t in alt.trace] == [(t.model, t.accept) for t in ref.trace]
     assert max(abs(a.h_norm - b.h_norm) for a, b in zip(alt.trace, ref.trace)) < 1e-9
+
+
+def test_random_routing_assigns_each_token_by_its_own_draw():
+    # u per absolute position; p = 0.5: positions 3, 4 -> small, 5, 6 -> large, 7 -> small.  By hand:
+    #  t=3 SLM over the prompt [10,11,12]          -> 100
+    #  t=4 SLM decodes [100]                       -> 101
+    #  t=5 LLM first participation, 5 tokens       -> 200
+    #  t=6 LLM decodes [200]                       -> 201
+    #  t=7 SLM catches up with [101?]...: it has seen 4 tokens (0..3), the sequence has 7 -> span [101, 200, 201]
+    u = {3: 0.1, 4: 0.4, 5: 0.9, 6: 0.5, 7: 0.49}
+    sc = Script([100, 101, 200, 201, 102], [0.9, 0.9, 0.1, 0.1, 0.9])          # entropies are ignored
+    r = stitch.generate_random([10, 11, 12], sc, 0.5, lambda t: u[t], 5)
+    assert r.output == [100, 101, 200, 201, 102] and r.n_rejected == 0
+    assert sc.calls == [(SLM, [10, 11, 12], 0), (SLM, [100], 3), (LLM, [10, 11, 12, 100, 101], 0), (LLM, [200], 5),
+                        (SLM, [101, 200, 201], 4)]
+
+
+def test_random_routing_special_cases_and_share():
+    toks = list(range(500, 900))
+    ent = [0.5] * 400
+    all_slm = Script(toks, ent)
+    a = stitch.generate_random([1, 2], all_slm, 1.0, lambda t: 0.999999, 50)
+    assert all(m == SLM for m, _, _ in all_slm.calls) and a.output == toks[:50]
+    all_llm = Script(toks, ent)
+    stitch.generate_random([1, 2], all_llm, 0.0, lambda t: 1e-9, 50)
+    assert all(m == LLM for m, _, _ in all_llm.calls)
+    # the share of small-model tokens follows p
+    us = W.uniform01(3, 77, 0, 402).tolist()
+    sc = Script(toks, ent)
+    r = stitch.generate_random([1, 2], sc, 0.3, lambda t: us[t], 400)
+    share = sum(1 for t in r.trace if t.model == SLM) / 400
+    assert abs(share - 0.3) < 0.07
+    # every token of prompt + output is seen exactly once by each model that ran at or after it
+    seen = {SLM: 0, LLM: 0}
+    for m, span, pos0 in sc.calls:
+        assert pos0 == seen[m]
+        seen[m] += len(span)
