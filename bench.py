@@ -137,7 +137,9 @@ def gateup_roofline(ev, P, model, shape, run_once, sync, rows, overhead_ms, over
     bracket_ms = time_phase(ev, P, model, P.binding.PHASE_GATEUP, shape.n_layers // 2, run_once, sync, n, e0, e1)
     avg_s = (bracket_ms - overhead_ms) * 1e-3
     nbytes = 2 * shape.d_ffn * shape.d_model * 2
-    name = f"k_gemv<GATEUP> ({shape.name}, 1 token row)" if rows == 1 else f"k_gemm_rows<GATEUP> ({shape.name}, {rows} token rows)"
+    fma = rows <= 2 or (rows <= 4 and shape.d_model <= 2048)         # the library's own rule for the FMA kernels
+    name = (f"k_gemv<GATEUP> ({shape.name}, {rows} token row{'s' if rows > 1 else ''})" if fma
+            else f"k_gemm_rows<GATEUP> ({shape.name}, {rows} token rows)")
     return {"bound": "hbm", "kernel": name, "launches": n, "avg_us": round(avg_s * 1e6, 2),
             "avg_us_between_events": round(bracket_ms * 1e3, 2),
             "event_pair_overhead_us": round(overhead_ms * 1e3, 2) if overhead_ok else None,
@@ -290,7 +292,7 @@ def bench_batched(args, wl) -> int:
     import paper_2507_17307_amd as P
     from paper_2507_17307_amd.stitch import StitchedBatch, SLM, LLM
 
-    nb = wl.n_seqs
+    nb = args.seqs or wl.n_seqs
     t0 = time.time()
     w_s = W.make_weights(wl.slm, wl.seed, 0, device="cuda")
     w_l = W.make_weights(wl.llm, wl.seed, 1, device="cuda")
@@ -358,8 +360,8 @@ def bench_batched(args, wl) -> int:
         "value": round(accepted / elapsed, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / max(accepted, 1) * nb * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
-        "config": {"workload": args.workload, "slm": wl.slm.name, "llm": wl.llm.name, "batch": nb,
-                   "prompt_lens": [len(p) for p in prompts], "tau": round(tau, 6), "tau_percentile": wl.tau_percentile,
+        "config": {"workload": args.workload + (f" with {nb} sequences" if nb != wl.n_seqs else ""), "slm": wl.slm.name,
+                   "llm": wl.llm.name, "batch": nb, "prompt_lens": [len(p) for p in prompts], "tau": round(tau, 6), "tau_percentile": wl.tau_percentile,
                    "max_ctx": max_ctx},
         "roofline": roofline, "cpu_baseline": cpu,
         "setup": {"llm_prompt_prefill_ms": round(setup_ms, 2)},
@@ -381,6 +383,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency-fit", action="store_true")
     ap.add_argument("--tau-steps", type=int, default=None, help="small-model-only tokens used to place tau")
+    ap.add_argument("--seqs", type=int, default=None, help="batched workload only: number of sequences (1..16) instead of the workload's")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, three times: the "
                          "known-size dispatch that hardware byte counters of a profiler run are scaled by")
@@ -400,6 +403,9 @@ def main() -> int:
     if wl.llm is None:
         return bench_single_model(args, wl)
     if wl.n_seqs > 1:
+        if args.seqs is not None and not 1 <= args.seqs <= 16:
+            print("bench.py: --seqs must be in 1..16", file=sys.stderr)
+            return 2
         return bench_batched(args, wl)
     if args.warmup + args.steps > wl.n_decode:
         print(f"bench.py: warmup + steps must not exceed {wl.n_decode}", file=sys.stderr)

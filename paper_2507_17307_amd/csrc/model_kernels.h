@@ -26,16 +26,17 @@ struct PrepArgs {
     float *h;
 };
 
-constexpr int PREP_LDS_INTS = 128;
+constexpr int PREP_LDS_INTS = 144;
+constexpr int MAX_SEQS = 16;      // sequences one call may carry (the LM-head kernels hold one softmax state per sequence and lane group)
 
 // sh: PREP_LDS_INTS ints of LDS.  The control values may live in pinned host memory, where every
 // dependent read costs a bus round trip: each one is requested by its own thread, all at once,
 // and the validation then runs out of LDS.
 __device__ __forceinline__ void prepare_row(const PrepArgs &a, int r, int *sh) {
     const int tid = threadIdx.x;
-    int *s_off = sh + 4, *s_slot = sh + 16, *s_pos = sh + 24, *s_tok = sh + 40;     // [9], [8], [8], [64]
-    float *s_scale = reinterpret_cast<float *>(sh + 32);                             // [8]
-    const int ns = min(a.n_seqs, 8), nr = min(a.n_rows, 64);                         // the host enforces both bounds
+    int *s_off = sh + 4, *s_slot = sh + 24, *s_pos = sh + 40, *s_tok = sh + 72;     // [17], [16], [16], [64]
+    float *s_scale = reinterpret_cast<float *>(sh + 56);                             // [16]
+    const int ns = min(a.n_seqs, MAX_SEQS), nr = min(a.n_rows, 64);                  // the host enforces both bounds
     if (a.span_off != nullptr && tid <= ns) s_off[tid] = a.span_off[tid];
     if (tid >= 64 && tid < 64 + ns) {
         const int i = tid - 64;

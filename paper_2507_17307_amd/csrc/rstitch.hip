@@ -60,7 +60,7 @@ const char *check_config(const rs_config *c) {
     if (c->d_ffn < 128) return "d_ffn too small";
     if (c->vocab < 2) return "vocab must be at least 2";
     if (c->max_ctx < 8 || c->max_ctx % 8) return "max_ctx must be a positive multiple of 8";
-    if (c->max_seqs < 1 || c->max_seqs > 8) return "max_seqs must be in 1..8";
+    if (c->max_seqs < 1 || c->max_seqs > rs::MAX_SEQS) return "max_seqs must be in 1..16";
     if (c->max_rows < 1 || c->max_rows > 64) return "max_rows must be in 1..64";
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return "rms_eps must be > 0 and rope_theta > 1";
     if (c->d_model > 12288 || c->n_q_heads * c->head_dim > 12288)

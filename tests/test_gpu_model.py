@@ -82,17 +82,19 @@ def test_catchup_equals_sequential_decode_on_gpu(decode_path):
     assert float((ka - kb).abs().max()) <= 2 ** -7 * float(ka.abs().max())
 
 
-@pytest.mark.parametrize("spans", [[1, 1, 1], [3, 1, 17, 2], [16, 16, 16, 16], [5, 33, 1, 1, 1, 1, 1, 2]])
+@pytest.mark.parametrize("spans", [[1, 1, 1], [3, 1, 17, 2], [16, 16, 16, 16], [5, 33, 1, 1, 1, 1, 1, 2],
+                                   [1] * 16, [2, 1, 7, 1, 1, 3, 1, 1, 9, 1, 1, 2, 1, 5, 1, 4]])
 def test_batched_ragged_calls_match_per_sequence_oracle(spans, decode_path):
     """Several sequences in one call (ragged spans, distinct slots) against one oracle model per slot."""
     import paper_2507_17307_amd as P
     shape = W.TINY_L
     w = W.make_weights(shape, 4, 1)
     n = len(spans)
-    gpu = P.Model(w.to("cuda"), max_ctx=96, max_seqs=8, max_rows=64)
+    n_slots = 8 if n <= 8 else 16
+    gpu = P.Model(w.to("cuda"), max_ctx=96, max_seqs=n_slots, max_rows=64)
     refs = [decoder.OracleModel(w, 96) for _ in range(n)]
-    slots = [(3 * i + 1) % 8 for i in range(n)]
-    pre = [7 + 5 * i for i in range(n)]                       # every sequence already holds a different prefix
+    slots = [(3 * i + 1) % n_slots for i in range(n)]
+    pre = [7 + (5 * i) % 61 for i in range(n)]                # every sequence already holds a different prefix
     toks = [W.rng.randint(4, 200 + i, 0, pre[i] + spans[i] + 1, shape.vocab).tolist() for i in range(n)]
     for i in range(n):
         refs[i].forward(toks[i][:pre[i]], 0)
