@@ -75,3 +75,13 @@ def route(logits: torch.Tensor, tau: float, active: int) -> dict:
     m = float(x.max())
     return dict(token=greedy_token(x), flags=flags, h_nats=h, h_norm=hn, max_logit=m,
                 log_z=m + float(torch.log(torch.exp(x - m).sum())))
+
+
+def sample_token(logits: torch.Tensor, uniforms: torch.Tensor) -> int:
+    """A token drawn from softmax(logits) (Section "Preliminary": the next token is sampled from the
+    distribution the active model outputs), by the Gumbel-max construction: with u_i independent
+    uniforms in (0, 1), argmax_i (logit_i - ln(-ln u_i)) is distributed as softmax(logits).  The
+    uniforms are inputs (one per vocabulary entry, drawn by the caller per position); the lowest
+    index wins among equal maxima."""
+    x = logits.to(torch.float64) - torch.log(-torch.log(uniforms.to(torch.float64)))
+    return int(torch.nonzero(x == x.max())[0, 0])

@@ -89,11 +89,15 @@ def generate(prompt: Sequence[int], forward: Forward, tau: float, n_tokens: int,
     return res
 
 
-def decoder_forward(models, scale_of_pos: Callable[[int], float], log: Optional[list] = None) -> Forward:
+def decoder_forward(models, scale_of_pos: Callable[[int], float], log: Optional[list] = None,
+                    uniforms_of_pos: Optional[Callable[[int], object]] = None) -> Forward:
     """Bind two ``oracle.decoder.OracleModel`` objects (index SLM, LLM) into the
     ``forward`` callable of :func:`generate`.  ``scale_of_pos(p)`` is the logit
     scale used when predicting the token at absolute position p.  When ``log``
-    is a list, the scaled logits of every invocation are appended to it."""
+    is a list, the scaled logits of every invocation are appended to it.
+    ``uniforms_of_pos(p)``: when given, the token at position p is SAMPLED from
+    the distribution with these uniforms (one per vocabulary entry) instead of
+    taken greedily."""
     from . import router
 
     def forward(model: int, span: List[int], pos0: int) -> Tuple[int, float]:
@@ -101,7 +105,11 @@ def decoder_forward(models, scale_of_pos: Callable[[int], float], log: Optional[
         logits = out["logits"]
         if log is not None:
             log.append(logits)
-        return router.greedy_token(logits), router.normalised_entropy(logits)
+        if uniforms_of_pos is not None:
+            token = router.sample_token(logits, uniforms_of_pos(pos0 + len(span)))
+        else:
+            token = router.greedy_token(logits)
+        return token, router.normalised_entropy(logits)
 
     return forward
 

@@ -119,3 +119,39 @@ def test_nonfinite_logits_are_flagged_uncertain():
     r = router.route(x, tau=0.9, active=router.SLM)
     assert r["flags"] & router.FLAG_NONFINITE and r["flags"] & router.FLAG_HI
     assert not (r["flags"] & router.FLAG_ACCEPT)
+
+
+def test_sample_token_follows_the_softmax_distribution():
+    """Gumbel-max draws against the probabilities themselves, and against the same draws made another way: the
+    exponential race (the index with the smallest -ln(u_i) / p_i wins), which is the same event written without
+    logarithms of logarithms."""
+    import workloads as W
+    logits = torch.tensor([2.0, 0.5, -1.0, 1.2, 0.0], dtype=torch.float64)
+    p = router.softmax(logits)
+    n = 40000
+    key = W.stream_key(7, 99)
+    u = W.uniform23(key, 0, n * 5).view(n, 5)
+    counts = torch.zeros(5)
+    for t in range(n):
+        tok = router.sample_token(logits, u[t])
+        if t < 2000:
+            race = int(torch.argmin(-torch.log(u[t]) / p))
+            assert tok == race
+        counts[tok] += 1
+    freq = counts / n
+    sigma = torch.sqrt(p * (1 - p) / n)
+    assert bool(((freq - p).abs() <= 4.5 * sigma).all()), (freq, p)
+
+
+def test_sample_token_special_cases():
+    import workloads as W
+    u = W.uniform23(W.stream_key(1, 2), 0, 64)
+    peaked = torch.zeros(64, dtype=torch.float64)
+    peaked[17] = 200.0
+    assert router.sample_token(peaked, u) == 17                       # a certain token is always drawn
+    flat = torch.zeros(64, dtype=torch.float64)
+    assert router.sample_token(flat, u) == int(torch.argmax(u))       # equal logits: the largest uniform wins
+    same = torch.full((64,), 0.5, dtype=torch.float64)
+    assert router.sample_token(flat, same) == 0                       # all equal: the lowest index
+    assert float(u.min()) > 0 and float(u.max()) < 1
+    assert torch.equal(u.to(torch.float32).double(), u)               # an fp32 holds these uniforms exactly

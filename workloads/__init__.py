@@ -7,7 +7,7 @@ code) so that both the CPU oracle and the HIP path can be fed the very same
 buffers without sharing any compute code.
 """
 
-from .rng import uniform01, normal, randint  # noqa: F401
+from .rng import uniform01, normal, randint, uniform23, stream_key  # noqa: F401
 from .shapes import (  # noqa: F401
     ModelShape, TINY_S, TINY_L, S15, M7, M14, M32, SHAPES,
     kv_bytes_per_token, weight_bytes_read_per_step, weight_bytes_resident,

@@ -76,3 +76,17 @@ def randint(seed: int, stream: int, start: int, count: int, high: int, device="c
     """int64 integers uniform in [0, high)."""
     u = uniform01(seed, stream, start, count, device)
     return torch.clamp((u * high).to(torch.int64), max=high - 1)
+
+
+def stream_key(seed: int, stream: int) -> int:
+    """The 64-bit key of (seed, stream) as an unsigned integer: what a consumer that implements this generator
+    itself (counter -> hashed bits) needs besides the counter."""
+    return _key(seed, stream) & _MASK64
+
+
+def uniform23(key: int, start: int, count: int, device="cpu") -> torch.Tensor:
+    """fp64 uniforms in (0, 1) with 23 random bits each, (n + 0.5) * 2^-23, for counters start .. start+count-1 of
+    the stream with the given 64-bit key: values an fp32 holds exactly, so an fp32 consumer sees the same numbers."""
+    idx = torch.arange(start, start + count, dtype=torch.int64, device=device)
+    top23 = _lsr(_mix(idx * _GOLDEN + _s64(key)), 41)
+    return (top23.to(torch.float64) + 0.5) * (2.0 ** -23)
