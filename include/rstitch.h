@@ -211,6 +211,22 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab,
                    rs_route_out *d_out, void *d_scratch, size_t scratch_bytes,
                    void *stream);
 
+/* Sampling instead of greedy decoding (Section "Preliminary": the next token is
+ * sampled from the distribution the active model outputs).  While enabled, the
+ * `token` of every record this model produces is a draw from softmax(scaled
+ * logits) instead of their arg max; entropy and flags are unchanged.  The draw
+ * is the arg max of logit_i - ln(-ln u_i) (Gumbel-max), u_i = (n + 0.5) 2^-23
+ * with n the top 23 bits of a 64-bit hash of the counter p * vocab + i under
+ * `key`, p the position of the token being predicted (the last row's position
+ * + 1): x = counter * 0x9E3779B97F4A7C15 + key; x = (x ^ x >> 30) *
+ * 0xBF58476D1CE4E5B9; x = (x ^ x >> 27) * 0x94D049BB133111EB; x ^= x >> 31.  The
+ * draw therefore depends on (key, position) only, not on which call, model or
+ * batch slot produces it.  Changing the setting drains the device and drops the
+ * model's cached launch graphs.  rs_route / rs_route_static (no positions) and
+ * the experimental single-kernel step do not sample.
+ * Errors: RS_EINVAL (null model). */
+rs_status rs_set_sampling(rs_model *model, int32_t enabled, uint64_t key);
+
 /* The learned router of R-Stitch+ (Section "RL-based Routing with Latency-aware
  * Reward"; Algorithm 1, R-Stitch+ branch; Section "Architecture and Overhead of
  * Router"): when a small-model step is above tau, the hidden state of that step

@@ -76,6 +76,8 @@ def _load() -> C.CDLL:
     lib.rs_route_scratch_bytes.argtypes = [i32, i32]
     lib.rs_route.restype = i32
     lib.rs_route.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp, sz, vp]
+    lib.rs_set_sampling.restype = i32
+    lib.rs_set_sampling.argtypes = [vp, i32, C.c_uint64]
     lib.rs_route_plus.restype = i32
     lib.rs_route_plus.argtypes = [vp, vp, i32, C.POINTER(_RsRouterWeights), i32, vp, vp, vp]
     lib.rs_route_static.restype = i32
@@ -189,6 +191,10 @@ def rs_route_plus(handle: Optional[int], d_hidden, n_seqs: int, router: RouterPl
     out = d_out if isinstance(d_out, int) else _ptr(d_out)
     _check(lib.rs_route_plus(handle, _ptr(d_hidden), n_seqs, C.byref(router.struct), active, out,
                              _ptr(d_router_logits), _stream(stream)))
+
+
+def rs_set_sampling(handle: int, enabled: bool, key: int = 0) -> None:
+    _check(lib.rs_set_sampling(handle, int(bool(enabled)), key & 0xFFFFFFFFFFFFFFFF))
 
 
 PHASE_QKV, PHASE_OPROJ, PHASE_GATEUP, PHASE_DOWN, PHASE_LMHEAD, PHASE_ATTN = range(6)

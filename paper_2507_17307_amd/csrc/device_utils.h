@@ -77,12 +77,34 @@ __device__ __forceinline__ float wave_max(float v) {
 // Entropy of softmax(x) in nats is ln z - s / z  (the quantity of Eq. 1 before
 // it is divided by ln V).  merge() is associative and commutative up to
 // rounding, so partial states can be combined in any tree.
+// Sampling (Section "Preliminary": the next token is drawn from the step's distribution): the state also carries
+// the running argmax of logit + Gumbel noise, whose arg max over the vocabulary is a draw from softmax(logits).
+// The noise of vocabulary entry i at a position is -ln(-ln u) with u = (n + 0.5) 2^-23, n the top 23 bits of a
+// 64-bit hash of the counter position * V + i under the caller's key (a finaliser of the splitmix family on a
+// keyed counter: the generator of the synthetic workloads, so a CPU check can draw the same numbers).
+__device__ __forceinline__ float gumbel_noise(unsigned long long key, unsigned long long counter) {
+    unsigned long long x = counter * 0x9E3779B97F4A7C15ull + key;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    const float u = ((float)(unsigned int)(x >> 41) + 0.5f) * 1.1920928955078125e-07f;      // 2^-23; exact in fp32
+    return -logf(-logf(u));
+}
+
 struct SoftState {
     float m, z, s, best;
     int idx, bad;
+    float gbest; int gidx;            // sampling only: largest logit + noise so far and its index
 
     __device__ __forceinline__ void init() {
         m = -INFINITY; z = 0.f; s = 0.f; best = -INFINITY; idx = 0x7fffffff; bad = 0;
+        gbest = -INFINITY; gidx = 0x7fffffff;
+    }
+    // x has been (or will be) pushed as well; i is its vocabulary index, base = position * V
+    __device__ __forceinline__ void push_noisy(float x, int i, unsigned long long key, unsigned long long base) {
+        if (!(fabsf(x) <= 3.0e38f)) return;
+        const float v = x + gumbel_noise(key, base + (unsigned long long)i);
+        if (v > gbest || (v == gbest && i < gidx)) { gbest = v; gidx = i; }
     }
     __device__ __forceinline__ void push(float x, int i) {
         if (!(fabsf(x) <= 3.0e38f)) { bad = 1; return; }     // NaN or +-Inf
@@ -99,6 +121,7 @@ struct SoftState {
     __device__ __forceinline__ void merge(const SoftState &o) {
         bad |= o.bad;
         if (o.best > best || (o.best == best && o.idx < idx)) { best = o.best; idx = o.idx; }
+        if (o.gbest > gbest || (o.gbest == gbest && o.gidx < gidx)) { gbest = o.gbest; gidx = o.gidx; }
         if (o.z <= 0.f) return;
         if (z <= 0.f) { m = o.m; z = o.z; s = o.s; return; }
         float mm = fmaxf(m, o.m);
@@ -118,6 +141,8 @@ __device__ __forceinline__ SoftState shfl_xor_state(const SoftState &a, int o) {
     b.best = __shfl_xor(a.best, o, RS_WAVE);
     b.idx = __shfl_xor(a.idx, o, RS_WAVE);
     b.bad = __shfl_xor(a.bad, o, RS_WAVE);
+    b.gbest = __shfl_xor(a.gbest, o, RS_WAVE);
+    b.gidx = __shfl_xor(a.gidx, o, RS_WAVE);
     return b;
 }
 
@@ -135,14 +160,15 @@ __device__ __forceinline__ void wave_merge_state(SoftState &a, int span = RS_WAV
 // What a workgroup (or wave) leaves in global memory for the final merge: 32 bytes.
 struct __align__(16) SoftPartial {
     float m, z, s, best;
-    int idx, bad, pad0, pad1;
+    int idx, bad;
+    float gbest; int gidx;
 };
 __device__ __forceinline__ SoftPartial to_partial(const SoftState &a) {
-    SoftPartial p; p.m = a.m; p.z = a.z; p.s = a.s; p.best = a.best; p.idx = a.idx; p.bad = a.bad; p.pad0 = 0; p.pad1 = 0;
+    SoftPartial p; p.m = a.m; p.z = a.z; p.s = a.s; p.best = a.best; p.idx = a.idx; p.bad = a.bad; p.gbest = a.gbest; p.gidx = a.gidx;
     return p;
 }
 __device__ __forceinline__ SoftState from_partial(const SoftPartial &p) {
-    SoftState a; a.m = p.m; a.z = p.z; a.s = p.s; a.best = p.best; a.idx = p.idx; a.bad = p.bad;
+    SoftState a; a.m = p.m; a.z = p.z; a.s = p.s; a.best = p.best; a.idx = p.idx; a.bad = p.bad; a.gbest = p.gbest; a.gidx = p.gidx;
     return a;
 }
 

@@ -125,6 +125,7 @@ struct GemvArgs {
     int n_q, n_kv, head_dim, max_ctx, max_seqs, layer, d_ffn;
     const int *row_pos, *row_slot, *row_bad;
     const float *seq_scale; SoftPartial *parts; int n_parts; float *logits;   // LM head
+    int sample_on; unsigned long long sample_key;         // LM head: also track the arg max of logit + Gumbel noise (needs row_pos)
 };
 
 // elements of K one LDS segment holds for MP rows
@@ -302,8 +303,14 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
 
     SoftState st[MP];
     float lm_scale[MP];
+    unsigned long long noise_base[MP];                   // sampling: (position of the token being predicted) * V
 #pragma unroll
-    for (int m = 0; m < MP; ++m) { st[m].init(); lm_scale[m] = (MODE == G_LMHEAD && m < M) ? a.seq_scale[m] : 1.f; }
+    for (int m = 0; m < MP; ++m) {
+        st[m].init(); lm_scale[m] = (MODE == G_LMHEAD && m < M) ? a.seq_scale[m] : 1.f;
+        noise_base[m] = 0;
+        if (MODE == G_LMHEAD && a.sample_on && m < M)
+            noise_base[m] = (unsigned long long)(a.row_pos[a.gather ? a.gather[m] : m] + 1) * (unsigned long long)a.N;
+    }
     int parity = 0;
 
     // accumulate chunks [c_begin, c_end) of the tile; the LDS segment starts at chunk seg_c0
@@ -464,6 +471,7 @@ __device__ __forceinline__ void gemv_phase(const GemvArgs &a, unsigned char *sme
                 for (int j = 0; j < RT; ++j) if (t * RT + j < a.N) {
                     const float lg = acc[j][m] * lm_scale[m];
                     st[m].push(lg, t * RT + j);
+                    if (a.sample_on) st[m].push_noisy(lg, t * RT + j, a.sample_key, noise_base[m]);
                     if (a.logits) a.logits[(size_t)m * a.N + t * RT + j] = lg;
                 }
             }

@@ -179,6 +179,8 @@ struct GemmArgs {
     float *h_out; int ld_h;               // residual accumulate
     uint16_t *act; size_t act_plane; int d_ffn;   // gate/up output planes
     const float *seq_scale; SoftPartial *parts; float *logits; int n_parts;   // LM head
+    int sample_on; unsigned long long sample_key;         // LM head: also track the arg max of logit + Gumbel noise
+    const int *row_pos, *out_row;                         // sampling: position of the row that feeds output row m is row_pos[out_row[m]]
 };
 
 constexpr int GEMM_KW = 64;                       // k elements per window: K must be a multiple
@@ -237,6 +239,8 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     }
     SoftState st; st.init();
     const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
+    unsigned long long noise_base = 0;                    // sampling: (position of the token being predicted) * V
+    if (MODE == G_LMHEAD && a.sample_on && i16 < a.M) noise_base = (unsigned long long)(a.row_pos[a.out_row[i16]] + 1) * (unsigned long long)a.N;
 
     for (int unit = unit_first; unit < n_units; unit += unit_step) {
         const int grp = unit / KSP, ksp = unit - grp * KSP;
@@ -375,6 +379,7 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
                 else {
                     const float lg = val * lm_scale;
                     st.push(lg, n);
+                    if (a.sample_on) st.push_noisy(lg, n, a.sample_key, noise_base);
                     if (a.logits) a.logits[(size_t)m * a.N + n] = lg;
                 }
             }

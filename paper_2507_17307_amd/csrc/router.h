@@ -40,9 +40,10 @@ k_route_partials(const float *__restrict__ logits, int vocab, const float *__res
 
 // Final merge and routing decision for one row by one 256-thread workgroup.
 // row_bad: optional per-row flag (nonzero = the row's inputs were out of range); sh: 4 SoftPartial of LDS.
+// sample: the record's token is the arg max of logit + Gumbel noise (a draw from the distribution) instead of the arg max
 __device__ __forceinline__ void route_merge_row(const SoftPartial *__restrict__ parts, int n_parts, int vocab, float tau,
                                                 int active, const int *__restrict__ row_bad, rs_route_out *__restrict__ out,
-                                                int row, SoftPartial *sh) {
+                                                int row, SoftPartial *sh, int sample = 0) {
     const int tid = threadIdx.x;
     SoftState st; st.init();
     for (int p = tid; p < n_parts; p += 256) st.merge(from_partial(parts[(size_t)row * n_parts + p]));
@@ -68,7 +69,7 @@ __device__ __forceinline__ void route_merge_row(const SoftPartial *__restrict__ 
         const bool hi = hn > tau;
         flags = (hi ? (RS_FLAG_HI | RS_FLAG_NEXT_LLM) : 0u);
         if (!(active == RS_SLM && hi)) flags |= RS_FLAG_ACCEPT;
-        r.token = st.idx; r.h_nats = h; r.h_norm = hn; r.max_logit = st.m; r.log_z = st.m + lz;
+        r.token = sample ? st.gidx : st.idx; r.h_nats = h; r.h_norm = hn; r.max_logit = st.m; r.log_z = st.m + lz;
     }
     r.flags = flags;
     out[row] = r;
@@ -77,9 +78,9 @@ __device__ __forceinline__ void route_merge_row(const SoftPartial *__restrict__ 
 // grid n_rows, block 256
 __global__ void __launch_bounds__(256)
 k_route_merge(const SoftPartial *__restrict__ parts, int n_parts, int vocab, float tau, int active,
-              const int *__restrict__ row_bad, rs_route_out *__restrict__ out) {
+              const int *__restrict__ row_bad, rs_route_out *__restrict__ out, int sample) {
     __shared__ SoftPartial sh[4];
-    route_merge_row(parts, n_parts, vocab, tau, active, row_bad, out, blockIdx.x, sh);
+    route_merge_row(parts, n_parts, vocab, tau, active, row_bad, out, blockIdx.x, sh, sample);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -155,6 +155,8 @@ struct rs_model {
     std::vector<size_t> seen_once;                 // signatures launched eagerly once (ring buffer)
     size_t seen_next = 0;
     bool use_graphs = true;
+    int sample_on = 0;                             // rs_set_sampling
+    unsigned long long sample_key = 0;
     // single-kernel decode step (experimental: slower than one kernel per phase on MI355X, where a
     // grid-wide software barrier costs more than a kernel boundary)
     bool use_persistent = false;
@@ -673,6 +675,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         g.m_rows = n_seqs; g.ld_h = c.d_model; g.gather = m->at<int>(L.out_row);
         g.eps = c.rms_eps; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.h_in = h; g.gain = m->final_norm;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
+        g.sample_on = m->sample_on; g.sample_key = m->sample_key; g.row_pos = row_pos;
         n_parts = m->plan.lm_blocks; g.n_parts = n_parts;
         tic(RS_PHASE_LMHEAD, 0);
         // one output row per sequence (the last row of its span)
@@ -690,6 +693,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         GemmArgs g{};
         g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane;
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
+        g.sample_on = m->sample_on; g.sample_key = m->sample_key; g.row_pos = row_pos; g.out_row = m->at<int>(L.out_row);
         tic(RS_PHASE_LMHEAD, 0);
         if ((rc = launch_gemm<G_LMHEAD>(m, g, (c.vocab + 15) / 16, st, "gemm_lmhead"))) return rc;
         toc(RS_PHASE_LMHEAD, 0);
@@ -697,7 +701,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
     }
     if (n_parts > L.lm_parts_cap) return fail(RS_EINVAL, "internal: %d router partials exceed capacity", n_parts);
     hipLaunchKernelGGL(k_route_merge, dim3(n_seqs), dim3(256), 0, st, (const SoftPartial *)parts, n_parts, c.vocab, tau,
-                       active, (const int *)m->at<int>(L.seq_bad), d_out);
+                       active, (const int *)m->at<int>(L.seq_bad), d_out, m->sample_on);
     RS_LAUNCHED("route_merge");
     return RS_OK;
 }
@@ -712,7 +716,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
 rs_status forward(rs_model *m, int n_seqs, int n_rows, const int *d_seq_slot, const int *d_tokens,
                   const int *d_span_off, const int *d_pos0, const float *d_scale, float tau, int active,
                   rs_route_out *d_out, float *d_logits, hipStream_t st) {
-    if (n_rows == 1 && m->use_persistent && m->timer_phase < 0)
+    if (n_rows == 1 && m->use_persistent && m->timer_phase < 0 && !m->sample_on)
         return forward_persistent(m, d_seq_slot, d_tokens, d_pos0, d_scale, tau, active, d_out, d_logits, st);
     auto eager = [&]() {
         return forward_kernels(m, n_seqs, n_rows, d_seq_slot, d_tokens, d_span_off, d_pos0, d_scale, tau, active, d_out,
@@ -916,6 +920,21 @@ rs_status rs_catchup_prefill(rs_model *m, int32_t n_seqs, int32_t n_rows, const 
                    d_logits, (hipStream_t)stream);
 }
 
+rs_status rs_set_sampling(rs_model *m, int32_t enabled, uint64_t key) {
+    if (!m) return fail(RS_EINVAL, "null model");
+    const int on = enabled ? 1 : 0;
+    if (on == m->sample_on && key == m->sample_key) return RS_OK;
+    // the cached launch graphs carry the old setting in their kernel arguments
+    if (!m->graphs.empty()) {
+        (void)hipDeviceSynchronize();
+        for (auto &g : m->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
+        m->graphs.clear();
+    }
+    m->seen_once.clear(); m->seen_next = 0;
+    m->sample_on = on; m->sample_key = key;
+    return RS_OK;
+}
+
 rs_status rs_set_spin_limit(rs_model *m, uint32_t polls) {
     if (!m) return fail(RS_EINVAL, "null model");
     m->spin_limit = polls ? polls : (1u << 22);
@@ -959,7 +978,7 @@ rs_status rs_route(const float *d_logits, int32_t n, int32_t vocab, const float 
                        (rs::SoftPartial *)d_scratch);
     RS_LAUNCHED("route_partials");
     hipLaunchKernelGGL(rs::k_route_merge, dim3(n), dim3(256), 0, st, (const rs::SoftPartial *)d_scratch, parts, vocab, tau,
-                       active, (const int *)nullptr, d_out);
+                       active, (const int *)nullptr, d_out, 0);
     RS_LAUNCHED("route_merge");
     return RS_OK;
 }
@@ -1052,7 +1071,7 @@ extern "C" rs_status rs_route_static(const float *d_logits, int32_t n, int32_t v
                        (rs::SoftPartial *)ptr);
     RS_LAUNCHED("route_partials");
     hipLaunchKernelGGL(rs::k_route_merge, dim3(n), dim3(256), 0, st, (const rs::SoftPartial *)ptr, parts, vocab, tau,
-                       active, (const int *)nullptr, d_out);
+                       active, (const int *)nullptr, d_out, 0);
     RS_LAUNCHED("route_merge");
     return RS_OK;
 }

@@ -136,12 +136,18 @@ class StitchedPair:
 
     def generate(self, prompt: Sequence[int], tau: float, n_tokens: int, single_model: Optional[int] = None,
                  keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None,
-                 llm_prefilled: bool = False, router_plus: Optional[B.RouterPlus] = None) -> StitchRun:
+                 llm_prefilled: bool = False, router_plus: Optional[B.RouterPlus] = None,
+                 sampling_key: Optional[int] = None) -> StitchRun:
         """Algorithm 1 until n_tokens tokens are accepted.  single_model = SLM or LLM runs that model
         alone (every token accepted) while still reporting its entropies.  llm_prefilled: the large model's
         cache already holds the prompt (prefill_prompt), so its first participation only catches up with the
         tokens accepted since.  router_plus: the R-Stitch+ branch of Algorithm 1: after every small-model call the
-        learned router (rs_route_plus, enqueued behind the call) may turn a hand-over into "keep the token and stay"."""
+        learned router (rs_route_plus, enqueued behind the call) may turn a hand-over into "keep the token and stay".
+        sampling_key: tokens are sampled from each step's distribution (rs_set_sampling with this 64-bit key on both
+        models) instead of taken greedily."""
+        for mdl in self.models:
+            if mdl is not None:
+                B.rs_set_sampling(mdl.handle, sampling_key is not None, sampling_key or 0)
         n0 = len(prompt)
         if n0 + n_tokens > self.max_ctx + 1:
             raise ValueError("prompt + tokens exceed max_ctx")
