@@ -302,8 +302,9 @@ def bench_batched(args, wl) -> int:
     n_total = args.warmup + args.steps
     n_tau = args.tau_steps or 128
     max_ctx = max(len(p) for p in prompts) + max(n_total, n_tau) + 8
-    slm = P.Model(w_s, max_ctx=max_ctx, max_seqs=nb, max_rows=64)
-    llm = P.Model(w_l, max_ctx=max_ctx, max_seqs=nb, max_rows=64)
+    max_rows = 64 if nb <= 64 else 128
+    slm = P.Model(w_s, max_ctx=max_ctx, max_seqs=nb, max_rows=max_rows)
+    llm = P.Model(w_l, max_ctx=max_ctx, max_seqs=nb, max_rows=max_rows)
     batch = StitchedBatch(slm, llm, max_ctx, [W.logit_scale(wl, 0, max_ctx + 1, seq=b) for b in range(nb)])
     ln_v = math.log(wl.slm.vocab)
     solo = batch.generate(prompts, 2.0, n_tau, single_model=SLM)
@@ -341,6 +342,17 @@ def bench_batched(args, wl) -> int:
     ideal_s = sum(S.step_bytes(shapes[m], ctxs, rows) for m, ctxs, rows in calls_log) / HBM_PEAK
     frac = llm_tok / max(all_tok, 1)
 
+    # the large model alone on the same prompts (the row the paper's batch-size table compares with): a short run,
+    # after the timed region
+    batch.on_call = None
+    n_llm = min(n_total, 24)
+    batch.generate(prompts, tau, 4, single_model=LLM, llm_prefilled=True)          # captures the launch graphs
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    batch.generate(prompts, tau, n_llm, single_model=LLM, llm_prefilled=True)
+    torch.cuda.synchronize()
+    llm_only_s = time.perf_counter() - t0
+
     ev = HipEvents()
     e0, e1 = ev.create(), ev.create()
     over, ok = event_pair_overhead_ms(ev, batch.stream, e0, e1)
@@ -365,6 +377,8 @@ def bench_batched(args, wl) -> int:
                    "max_ctx": max_ctx},
         "roofline": roofline, "cpu_baseline": cpu,
         "setup": {"llm_prompt_prefill_ms": round(setup_ms, 2)},
+        "llm_only": {"tokens_per_s": round(nb * n_llm / llm_only_s, 2), "ms_per_step": round(llm_only_s / n_llm * 1e3, 4),
+                     "tokens_per_sequence": n_llm, "stitched_speedup": round(accepted / elapsed / (nb * n_llm / llm_only_s), 3)},
         "stitched": {"accepted_tokens": accepted, "library_calls": calls, "llm_token_frac": round(frac, 4),
                      "ms_per_call": round(elapsed / max(calls, 1) * 1e3, 4),
                      "rejected_slm_steps": sum(1 for r in runs for t in r.trace if not t.accept),
@@ -383,7 +397,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency-fit", action="store_true")
     ap.add_argument("--tau-steps", type=int, default=None, help="small-model-only tokens used to place tau")
-    ap.add_argument("--seqs", type=int, default=None, help="batched workload only: number of sequences (1..16) instead of the workload's")
+    ap.add_argument("--seqs", type=int, default=None, help="run a two-model workload over this many sequences (1..128) with per-sequence routing, through the batched driver")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, three times: the "
                          "known-size dispatch that hardware byte counters of a profiler run are scaled by")
@@ -402,9 +416,9 @@ def main() -> int:
     wl = W.WORKLOADS[args.workload]
     if wl.llm is None:
         return bench_single_model(args, wl)
-    if wl.n_seqs > 1:
-        if args.seqs is not None and not 1 <= args.seqs <= 16:
-            print("bench.py: --seqs must be in 1..16", file=sys.stderr)
+    if wl.n_seqs > 1 or args.seqs is not None:
+        if args.seqs is not None and not 1 <= args.seqs <= 128:
+            print("bench.py: --seqs must be in 1..128", file=sys.stderr)
             return 2
         return bench_batched(args, wl)
     if args.warmup + args.steps > wl.n_decode:

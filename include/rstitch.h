@@ -81,7 +81,7 @@ typedef int32_t rs_status;
  *   d_model, d_ffn and n_q_heads*head_dim are multiples of 128; d_model and
  *   n_q_heads*head_dim are at most 12288; d_ffn >= 128; head_dim is 32, 64 or 128;
  *   n_kv_heads divides n_q_heads with at most 8 query heads per KV head; vocab >= 2;
- *   max_ctx is a multiple of 8, at least 8; 1 <= max_seqs <= 16; 1 <= max_rows <= 64;
+ *   max_ctx is a multiple of 8, at least 8; 1 <= max_seqs <= 128; 1 <= max_rows <= 128;
  *   rms_eps > 0; rope_theta > 1. */
 typedef struct rs_config {
     int32_t n_layers;      /* >= 1                                                            */
@@ -93,8 +93,8 @@ typedef struct rs_config {
     int32_t vocab;         /* >= 2                                                           */
     int32_t tied_lm_head;  /* informational; lm_head may simply alias embed                  */
     int32_t max_ctx;       /* positions per sequence slot in the KV cache; multiple of 8, >= 8 */
-    int32_t max_seqs;      /* sequence slots in the KV cache (1..16)                         */
-    int32_t max_rows;      /* most token rows one call may carry (1..64)                     */
+    int32_t max_seqs;      /* sequence slots in the KV cache (1..128)                        */
+    int32_t max_rows;      /* most token rows one call may carry (1..128)                    */
     float   rms_eps;       /* > 0                                                            */
     float   rope_theta;    /* > 1                                                            */
 } rs_config;

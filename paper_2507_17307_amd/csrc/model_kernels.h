@@ -26,23 +26,25 @@ struct PrepArgs {
     float *h;
 };
 
-constexpr int PREP_LDS_INTS = 144;
-constexpr int MAX_SEQS = 16;      // sequences one call may carry (the LM-head kernels hold one softmax state per sequence and lane group)
+constexpr int MAX_SEQS = 128;     // sequences one call may carry
+constexpr int MAX_ROWS = 128;     // token rows one call may carry
+constexpr int PREP_LDS_INTS = 8 + 5 * MAX_SEQS;
 
 // sh: PREP_LDS_INTS ints of LDS.  The control values may live in pinned host memory, where every
 // dependent read costs a bus round trip: each one is requested by its own thread, all at once,
 // and the validation then runs out of LDS.
 __device__ __forceinline__ void prepare_row(const PrepArgs &a, int r, int *sh) {
+    static_assert(MAX_ROWS <= MAX_SEQS && 2 * MAX_SEQS <= 256, "one thread per control value");
     const int tid = threadIdx.x;
-    int *s_off = sh + 4, *s_slot = sh + 24, *s_pos = sh + 40, *s_tok = sh + 72;     // [17], [16], [16], [64]
-    float *s_scale = reinterpret_cast<float *>(sh + 56);                             // [16]
-    const int ns = min(a.n_seqs, MAX_SEQS), nr = min(a.n_rows, 64);                  // the host enforces both bounds
+    int *s_off = sh + 4, *s_slot = sh + 8 + MAX_SEQS, *s_pos = sh + 8 + 2 * MAX_SEQS, *s_tok = sh + 8 + 4 * MAX_SEQS;   // [MAX_SEQS + 1], [MAX_SEQS] ...
+    float *s_scale = reinterpret_cast<float *>(sh + 8 + 3 * MAX_SEQS);
+    const int ns = min(a.n_seqs, MAX_SEQS), nr = min(a.n_rows, MAX_ROWS);            // the host enforces both bounds
     if (a.span_off != nullptr && tid <= ns) s_off[tid] = a.span_off[tid];
-    if (tid >= 64 && tid < 64 + ns) {
-        const int i = tid - 64;
+    if (tid < nr) s_tok[tid] = a.tokens[tid];
+    if (tid >= 128 && tid < 128 + ns) {
+        const int i = tid - 128;
         s_slot[i] = a.seq_slot[i]; s_pos[i] = a.pos0[i]; s_scale[i] = a.scale ? a.scale[i] : 1.f;
     }
-    if (tid >= 128 && tid < 128 + nr) s_tok[tid - 128] = a.tokens[tid - 128];
     __syncthreads();
     if (tid == 0) {
         int b = -1, lo = 0, hi = 0, bad = 0;

@@ -1,4 +1,4 @@
-// Multi-row kernels (2..64 token rows per call): the catch-up prefill of the
+// Multi-row kernels (2..128 token rows per call): the catch-up prefill of the
 // tokens a model has not seen, and batched decode.  The weights are still read
 // once per call, so the phases stay HBM-bound; the contraction over tokens runs
 // on the matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate) so that ALU
@@ -221,11 +221,13 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     int unit_first, unit_step, yb;
     if (Y == 1) { unit_first = blockIdx.x; unit_step = gridDim.x; yb = 0; }
     else {
+        // the launch has 8 * Y * n_cs workgroups: column slot cs (of n_cs) on XCD x walks the units cs * 8 + x, + n_cs * 8, ...
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
         yb = slot % Y;
         unit_first = (slot / Y) * 8 + xcd;
-        unit_step = n_units + 8;                                          // one unit per workgroup
+        unit_step = (int)(gridDim.x / (8 * Y)) * 8;
     }
+    const int part_id = Y == 1 ? (int)blockIdx.x : unit_first;            // LM head: this workgroup's place among its rows' partial states
     const int m_base = yb * 16 * NB;
 
     // token side: rows past M read row 0 and are cleared after the load
@@ -238,9 +240,10 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
         xp[nb] = a.X + (size_t)(xok[nb] ? m : 0) * K + g * 8;
     }
     SoftState st; st.init();
-    const float lm_scale = (MODE == G_LMHEAD && i16 < a.M) ? a.seq_scale[i16] : 1.f;
+    const int lm_row = m_base + i16;                      // LM head (NB = 1): the output row this lane's state follows
+    const float lm_scale = (MODE == G_LMHEAD && lm_row < a.M) ? a.seq_scale[lm_row] : 1.f;
     unsigned long long noise_base = 0;                    // sampling: (position of the token being predicted) * V
-    if (MODE == G_LMHEAD && a.sample_on && i16 < a.M) noise_base = (unsigned long long)(a.row_pos[a.out_row[i16]] + 1) * (unsigned long long)a.N;
+    if (MODE == G_LMHEAD && a.sample_on && lm_row < a.M) noise_base = (unsigned long long)(a.row_pos[a.out_row[lm_row]] + 1) * (unsigned long long)a.N;
 
     for (int unit = unit_first; unit < n_units; unit += unit_step) {
         const int grp = unit / KSP, ksp = unit - grp * KSP;
@@ -395,10 +398,10 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
         SoftPartial *sp = reinterpret_cast<SoftPartial *>(smem);          // [GEMM_NW][16]
         if (g == 0) sp[wave * 16 + i16] = to_partial(st);
         __syncthreads();
-        if (wave == 0 && g == 0 && i16 < a.M) {
+        if (wave == 0 && g == 0 && lm_row < a.M) {
             SoftState s0 = from_partial(sp[i16]);
             for (int w = 1; w < GEMM_NW; ++w) s0.merge(from_partial(sp[w * 16 + i16]));
-            a.parts[(size_t)i16 * a.n_parts + blockIdx.x] = to_partial(s0);
+            a.parts[(size_t)lm_row * a.n_parts + part_id] = to_partial(s0);
         }
     }
 }

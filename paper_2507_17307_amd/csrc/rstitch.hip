@@ -60,8 +60,8 @@ const char *check_config(const rs_config *c) {
     if (c->d_ffn < 128) return "d_ffn too small";
     if (c->vocab < 2) return "vocab must be at least 2";
     if (c->max_ctx < 8 || c->max_ctx % 8) return "max_ctx must be a positive multiple of 8";
-    if (c->max_seqs < 1 || c->max_seqs > rs::MAX_SEQS) return "max_seqs must be in 1..16";
-    if (c->max_rows < 1 || c->max_rows > 64) return "max_rows must be in 1..64";
+    if (c->max_seqs < 1 || c->max_seqs > rs::MAX_SEQS) return "max_seqs must be in 1..128";
+    if (c->max_rows < 1 || c->max_rows > rs::MAX_ROWS) return "max_rows must be in 1..128";
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return "rms_eps must be > 0 and rope_theta > 1";
     if (c->d_model > 12288 || c->n_q_heads * c->head_dim > 12288)
         return "d_model and n_q_heads*head_dim must not exceed 12288";
@@ -91,7 +91,7 @@ int attn_pairs_cap(const rs_config &c) {
     return want > 512 ? want : 512;
 }
 
-constexpr int LM_PARTS_CAP = 4096;
+constexpr int LM_PARTS_CAP = 4096;                  // multiple of 8
 constexpr int FMA_MAX_ROWS = 4;                     // calls of up to this many token rows run on the FMA GEMV kernels
 constexpr int GEMM_KSPLIT_MAX = rs::KSPLIT_MAX;     // workgroup-level K splits of the multi-row projections, at most
 
@@ -351,7 +351,8 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
         const int r = (n_tiles + 1) / 2 >= target ? 2 : 1;
         int blocks = (n_tiles + r - 1) / r;
         if (MODE == G_LMHEAD) {
-            if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;             // one partial per workgroup
+            if (blocks > LM_PARTS_CAP) blocks = LM_PARTS_CAP;             // one partial per workgroup and row block
+            if (a.yblocks > 1) blocks = ((blocks + 7) / 8) * 8;           // LM_PARTS_CAP is a multiple of 8
             a.n_parts = blocks;
         }
         blocks = gemm_grid(blocks, a.yblocks);
@@ -365,8 +366,11 @@ template <int MODE>
 rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     if (a.K % GEMM_KW) return fail(RS_EINVAL, "internal: K = %d is not a multiple of %d", a.K, GEMM_KW);
     a.yblocks = 1;
-    if constexpr (MODE == G_LMHEAD) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
-    else {
+    if constexpr (MODE == G_LMHEAD) {
+        // more than 16 sequences: 16-row blocks, each with workgroups of its own (a lane's softmax state follows one row)
+        a.yblocks = (a.M + 15) / 16;
+        return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
+    } else {
         // up to 16 rows: one 16-row block; more: blocks of 32 rows (two 16-row blocks per workgroup), each
         // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.0 ms, 64 rows 9.1 ms this
         // way; 64-row blocks are no faster (9.7 ms) and 16-row blocks slower.

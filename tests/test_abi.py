@@ -41,7 +41,7 @@ def test_config_validation_on_the_host():
     ok = P.binding.make_config(W.S15, 4608)
     assert P.rs_workspace_bytes(ok) > 0
     assert P.rs_kv_bytes(ok) == 28 * 1 * 2 * 4608 * 128 * 2
-    for field, value, word in [("max_seqs", 17, "max_seqs"), ("max_rows", 65, "max_rows"), ("head_dim", 48, "head_dim"),
+    for field, value, word in [("max_seqs", 129, "max_seqs"), ("max_rows", 129, "max_rows"), ("head_dim", 48, "head_dim"),
                                ("n_kv_heads", 5, "divide"), ("vocab", 1, "vocab"), ("d_model", 1000, "multiples")]:
         cfg = P.binding.make_config(W.S15, 4608)
         setattr(cfg, field, value)

@@ -275,3 +275,49 @@ def test_cfg5_eight_sequences_ragged_catchup_and_batched_decode_at_real_layer_sh
         check_invocation(got[k], lg[k], want, tau, router.LLM, where=f"{name} partial batch, sequence {i}")
     del gpu, ref, w_gpu
     release()
+
+
+# ------------------------------------------------------------------------------------------------ batches beyond 16
+BIG_BATCH = [("s15_128seqs", W.S15, 0, 128, 40), ("m7_48seqs", W.M7, 1, 48, 20)]
+
+
+@pytest.mark.parametrize("name,shape,role,n,n_ragged", BIG_BATCH, ids=[b[0] for b in BIG_BATCH])
+def test_batches_beyond_sixteen_sequences_at_real_layer_shapes(name, shape, role, n, n_ragged):
+    """The batch sizes of the paper's batch-size analysis (Section "Batch Size Analysis": up to 128 sequences) at real
+    layer shapes: a ragged catch-up over some of the sequences, then one decode step of all of them (several 16-row
+    blocks in the LM head, several 32-row blocks in the layers), each sequence against its own oracle cache."""
+    import paper_2507_17307_amd as P
+    shape = two_layers(shape)
+    max_ctx = 1024
+    w_gpu = W.make_weights(shape, 6, role, device="cuda")
+    ref = decoder.OracleModel(w_gpu.to("cpu"), max_ctx, n_slots=n)
+    gpu = P.Model(w_gpu, max_ctx=max_ctx, max_seqs=n, max_rows=128)
+    slots = [(5 * i + 3) % n for i in range(n)]                  # 5 is coprime with 128 and 48
+    assert len(set(slots)) == n
+    ctx = [40 + (37 * i) % 900 for i in range(n)]
+    for i in range(n):
+        noise_cache(gpu, ref, slots[i], ctx[i], seed=100 + i)
+    spans = [1 + (i * i) % 5 for i in range(n_ragged)]           # 1..5 rows per sequence
+    while sum(spans) > 128:
+        spans[spans.index(max(spans))] -= 1
+    toks = [W.rng.randint(6, 800 + i, 0, 8, shape.vocab).tolist() for i in range(n)]
+    scales = [1.0 + 0.5 * (i % 12) for i in range(n)]
+    tau = 0.7
+    sub = list(range(0, n, n // n_ragged))[:n_ragged]            # the sequences of the ragged call
+    got, lg = gpu.catchup_prefill([toks[i][:spans[k]] for k, i in enumerate(sub)], [ctx[i] for i in sub], tau, P.RS_LLM,
+                                  [scales[i] for i in sub], [slots[i] for i in sub], want_logits=True)
+    torch.cuda.synchronize()
+    fed = [0] * n
+    for k, i in enumerate(sub):
+        want = ref.forward(toks[i][:spans[k]], ctx[i], slot=slots[i], logit_scale=scales[i])["logits"]
+        check_invocation(got[k], lg[k], want, tau, router.LLM, where=f"{name} ragged catch-up, sequence {i} ({spans[k]} rows at {ctx[i]})")
+        fed[i] = spans[k]
+    pos = [ctx[i] + fed[i] for i in range(n)]
+    nxt = [toks[i][fed[i]] for i in range(n)]
+    got, lg = gpu.decode_step(nxt, pos, tau, P.RS_SLM, scales, slots, want_logits=True)
+    torch.cuda.synchronize()
+    for i in range(n):
+        want = ref.forward([nxt[i]], pos[i], slot=slots[i], logit_scale=scales[i])["logits"]
+        check_invocation(got[i], lg[i], want, tau, router.SLM, where=f"{name} decode of {n} sequences, sequence {i} at {pos[i]}")
+    del gpu, ref, w_gpu
+    release()
