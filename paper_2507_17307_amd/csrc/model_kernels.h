@@ -22,6 +22,7 @@ struct PrepArgs {
     const float *scale;
     const uint16_t *embed;
     int *row_slot, *row_pos, *row_bad, *out_row, *seq_bad;
+    int4 *seq_info;                // per sequence {first row, end row, cache slot, first row's position}; first row = -1 for an invalid one
     float *seq_scale;
     float *h;
 };
@@ -75,10 +76,11 @@ __device__ __forceinline__ void prepare_row(const PrepArgs &a, int r, int *sh) {
         if (b >= 0 && r == hi - 1 && b < ns) {
             a.out_row[b] = r; a.seq_bad[b] = bad;
             a.seq_scale[b] = s_scale[b];
+            a.seq_info[b] = bad ? make_int4(-1, 0, 0, 0) : make_int4(lo, hi, s_slot[b], s_pos[b]);
         }
         // a malformed offset table can leave sequences without any row: flag them all
         if (bad && a.span_off != nullptr && r == 0)
-            for (int i = 0; i < ns; ++i) { a.seq_bad[i] = 1; a.out_row[i] = 0; a.seq_scale[i] = 1.f; }
+            for (int i = 0; i < ns; ++i) { a.seq_bad[i] = 1; a.out_row[i] = 0; a.seq_scale[i] = 1.f; a.seq_info[i] = make_int4(-1, 0, 0, 0); }
     }
     __syncthreads();
     const int bad = sh[3];
@@ -870,6 +872,8 @@ struct AttnArgs {
     const int *row_pos, *row_slot, *row_bad;
     int n_q, n_kv, max_ctx, max_seqs, layer, n_slices;
     int n_rows;                    // token rows in the call (k_attn_partial_rows)
+    int slot_split;                // k_attn_span: workgroups per sequence, slice and KV head
+    const int4 *seq_info;          // per sequence {first row, end row, cache slot, first row's position}, first row < 0: invalid (k_attn_span)
 };
 
 constexpr int ATT_GMAX = 8;       // query heads per kv head, at most
@@ -1258,6 +1262,170 @@ __global__ void __launch_bounds__(256, MINW) k_attn_partial_rows(AttnArgs a) {
             }
         }
         r0 = r1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_attn_span: the partial records of k_attn_partial_rows for calls whose slices are one 64-position
+// pass, with the K/V tile shared through LDS.  grid (n_slices, n_kv_heads, n_seqs * ZS), block 256
+// (ZS = a.slot_split workgroups share a sequence's row slots: workgroup zs takes the slots w + 4 zs, + 4 ZS, ...
+// of wave w; long spans are spread over more CUs that way).
+// A workgroup owns one context slice of one KV head of one SEQUENCE of the call and all of that
+// sequence's rows: the four waves fetch the slice's K rows (64 x HD, contiguous in the cache) and V^T
+// rows (HD pieces of 128 bytes) once, with whole-line 16-byte loads, into LDS; then wave w takes the row
+// slots w, w + 4, ... (a slot = 16 / G consecutive rows in the 16 matrix-core columns, as above) and reads
+// its operands from LDS.  Measured against k_attn_partial_rows, where every wave fetches the tile
+// itself with one 16-byte (K) or 8-byte (V) piece per lane and row, 16 cache lines per instruction:
+// that kernel is bound by the CU's vector-memory request rate (its loads alone take as long as the
+// whole kernel) and re-reads the tile once per four slots.
+// V positions at or past the sequence's last row may hold anything (never written): they are cleared
+// when the tile is written to LDS; K rows there only feed scores that the causal mask discards.
+// ------------------------------------------------------------------------------------------------
+template <int HD>
+__host__ __device__ constexpr size_t attn_span_lds_bytes() { return (size_t)64 * (HD * 2 + 16) + (size_t)HD * (64 * 2 + 16); }
+
+template <int HD>
+__global__ void __launch_bounds__(256) k_attn_span(AttnArgs a) {
+    constexpr int NDS = HD / 32, NDB = HD / 16, PS = HD + 4;
+    constexpr int KP = HD * 2 + 16, VP = 64 * 2 + 16;           // LDS row pitches in bytes (padded against bank conflicts)
+    constexpr int KQ = 64 * HD * 2 / 4096, VQ = HD * 128 / 4096; // 16-byte loads per thread for each tile
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *sK = smem, *sV = smem + (size_t)64 * KP;
+    const int split = blockIdx.x, S = gridDim.x, kvh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, kg = lane >> 4;
+    const int G = a.n_q / a.n_kv, RP = 16 / G;
+    const int rr = j / G, gh = j - rr * G;                     // this lane's column: row rr of the slot, head gh
+    const int ZS = a.slot_split > 1 ? a.slot_split : 1, zs = blockIdx.z % ZS;
+    const int4 info = a.seq_info[blockIdx.z / ZS];             // {first row, end row, cache slot, position of the first row}, first row < 0: skip
+    if (info.x < 0) return;
+    const int r_lo = info.x, r_hi = info.y, t_begin = split * 64;
+    const int ctx_max = info.w + (r_hi - r_lo);                // positions the last row attends to
+    const int n_slots = (r_hi - r_lo + RP - 1) / RP;
+    if (t_begin >= ctx_max || 4 * zs >= n_slots) return;
+    const int kv_slot = min(max(info.z, 0), a.max_seqs - 1);
+    const size_t kv_base = (((size_t)a.layer * a.max_seqs + kv_slot) * a.n_kv + kvh) * (size_t)a.max_ctx * HD;
+    const float scale = 1.0f / sqrtf((float)HD);
+
+    // the tile: requests first, the first slot's q next, then the LDS writes
+    uint4 kq[KQ], vq[VQ];
+#pragma unroll
+    for (int i = 0; i < KQ; ++i) {
+        const int off = (tid + 256 * i) * 16, row = off / (HD * 2), col = off - row * (HD * 2);
+        const int tok = min(t_begin + row, a.max_ctx - 1);
+        kq[i] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(a.kcache + kv_base + (size_t)tok * HD) + col);
+    }
+#pragma unroll
+    for (int i = 0; i < VQ; ++i) {
+        const int off = (tid + 256 * i) * 16, d = off >> 7, c8 = (off & 127) >> 4;
+        const int tv = min(t_begin + 8 * c8, a.max_ctx - 8);
+        vq[i] = *reinterpret_cast<const uint4 *>(a.vcache + kv_base + (size_t)d * a.max_ctx + tv);
+    }
+    auto load_q = [&](int slot, float4 (&q)[NDS][2]) {
+        const int r0 = r_lo + slot * RP, my_row = r0 + rr;
+        const bool ok = rr < RP && my_row < r_hi;
+        const float4 *qp = reinterpret_cast<const float4 *>(a.qbuf + ((size_t)(ok ? my_row : r_lo) * a.n_q + kvh * G + (ok ? gh : 0)) * HD + 8 * kg);
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) { q[ds][0] = qp[8 * ds]; q[ds][1] = qp[8 * ds + 1]; }
+    };
+    float4 qn[NDS][2];
+    if (wave + 4 * zs < n_slots) load_q(wave + 4 * zs, qn);
+#pragma unroll
+    for (int i = 0; i < KQ; ++i) {
+        const int off = (tid + 256 * i) * 16, row = off / (HD * 2), col = off - row * (HD * 2);
+        *reinterpret_cast<uint4 *>(sK + (size_t)row * KP + col) = kq[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VQ; ++i) {
+        const int off = (tid + 256 * i) * 16, d = off >> 7, c8 = (off & 127) >> 4;
+        const int t0 = t_begin + 8 * c8;                       // position of the first of this piece's 8 values
+        uint4 v = vq[i];
+        if (t0 + 7 >= ctx_max) {
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (t0 + 2 * e >= ctx_max) w[e] = 0;
+                else if (t0 + 2 * e + 1 >= ctx_max) w[e] &= 0x0000ffffu;
+            }
+            v = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        *reinterpret_cast<uint4 *>(sV + (size_t)d * VP + c8 * 16) = v;
+    }
+    __syncthreads();
+
+    for (int slot = wave + 4 * zs; slot < n_slots; slot += 4 * ZS) {
+        const int r0 = r_lo + slot * RP, my_row = r0 + rr;
+        const bool col_ok = rr < RP && my_row < r_hi;
+        const int ctx_col = col_ok ? info.w + (my_row - r_lo) + 1 : 0;
+        const int t_end_col = min(ctx_col, t_begin + 64);
+        bf16x8_t qB[NDS][3];
+#pragma unroll
+        for (int ds = 0; ds < NDS; ++ds) {
+            float qv[8] = {qn[ds][0].x, qn[ds][0].y, qn[ds][0].z, qn[ds][0].w, qn[ds][1].x, qn[ds][1].y, qn[ds][1].z, qn[ds][1].w};
+            if (!col_ok) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qv[e] = 0.f;
+            }
+            split3(qv, qB[ds]);
+        }
+        if (slot + 4 * ZS < n_slots) load_q(slot + 4 * ZS, qn);   // the next slot's q is in flight during this slot's products
+        // scores: lane holds positions t_begin + 16 tb + 4 kg + r of its column
+        f32x4_t sc[4];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            sc[tb] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ds = 0; ds < NDS; ++ds) {
+                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(sK + (size_t)(16 * tb + j) * KP + 64 * ds + 16 * kg));
+#pragma unroll
+                for (int pl = 2; pl >= 0; --pl) sc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, qB[ds][pl], sc[tb], 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float v = (t_begin + 16 * tb + 4 * kg + r) < t_end_col ? sc[tb][r] * scale : -INFINITY;
+                sc[tb][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, RS_WAVE));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, RS_WAVE));            // -inf for a column without positions in this slice
+        float l_run = 0.f;
+        f32x4_t acc[NDB];
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) acc[db] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            float pv[8];
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float s_ = sc[2 * ks + hf][r];
+                    const float p = (s_ == -INFINITY) ? 0.f : __expf(s_ - mx);
+                    pv[4 * hf + r] = p;
+                    l_run += p;
+                }
+            bf16x8_t pB[3];
+            split3(pv, pB);
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) {
+                const unsigned char *vr = sV + (size_t)(16 * db + j) * VP + 64 * ks + 8 * kg;
+                const uint2 lo = *reinterpret_cast<const uint2 *>(vr), hi = *reinterpret_cast<const uint2 *>(vr + 32);
+                const bf16x8_t A = __builtin_bit_cast(bf16x8_t, make_uint4(lo.x, lo.y, hi.x, hi.y));
+#pragma unroll
+                for (int pl = 2; pl >= 0; --pl) acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, pB[pl], acc[db], 0, 0, 0);
+            }
+        }
+        l_run += __shfl_xor(l_run, 16, RS_WAVE);
+        l_run += __shfl_xor(l_run, 32, RS_WAVE);
+        if (col_ok && t_begin < t_end_col) {
+            float *p = a.partials + (((size_t)my_row * a.n_q + kvh * G + gh) * S + split) * PS;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                *reinterpret_cast<float4 *>(p + 4 + 16 * db + 4 * kg) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+            if (kg == 0) { p[0] = mx; p[1] = l_run; }
+        }
     }
 }
 

@@ -69,7 +69,7 @@ const char *check_config(const rs_config *c) {
 }
 
 struct Layout {
-    size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, h, xn, qkv_raw, qbuf,
+    size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, seq_info, h, xn, qkv_raw, qbuf,
         attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, gemm_part, total;
     int attn_rows_x_splits;   // capacity of attn_part in (row, split) pairs
     int lm_parts_cap;         // partial states per sequence
@@ -109,6 +109,7 @@ Layout make_layout(const rs_config &c) {
     L.out_row = take(c.max_seqs * 4);
     L.seq_bad = take(c.max_seqs * 4);
     L.seq_scale = take(c.max_seqs * 4);
+    L.seq_info = take((size_t)c.max_seqs * 16);
     L.h = take((size_t)c.max_rows * c.d_model * 4);
     L.xn = take((size_t)3 * c.max_rows * c.d_model * 2);
     L.qkv_raw = take((size_t)c.max_rows * qkv * 4);
@@ -245,7 +246,8 @@ GemvPlan make_plan(const rs_config &c, int n_cu) {
 }
 
 template <int HD>
-rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool spans, hipStream_t st) {
+rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, int n_seqs, int n_cu, hipStream_t st) {
+    const bool spans = n_rows > n_seqs;
     a.n_slices = n_splits;
     a.n_rows = n_rows;
     if (spans) {
@@ -254,13 +256,34 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, bool span
         // only as many waves as it has slots (up to four): with idle waves in it, a CU held one workgroup at a
         // time and a two-row call on eight KV heads at 5000 positions took 17.5 us instead of ~7
         const int rp = 16 / (a.n_q / n_kv);
+        const long base = (long)n_splits * n_kv * n_seqs;
+        if (n_splits * ATT_BT >= a.max_ctx && (n_rows >= 3 || base <= n_cu)) {
+            // every slice is one 64-position pass: one workgroup per (slice, KV head, sequence), K/V tile through LDS
+            // (two-row calls with more workgroups than CUs stay on the kernel below: 7B shape 7.6 us against 9.6).
+            // Measured per call, 7B shape: 5 rows 3.91 -> 3.84 ms, 16 rows 5.03 -> 4.83, 64 rows 10.26 -> 9.61; 1.5B shape: 8 rows
+            // 1.92 -> 1.82, 16 rows 2.43 -> 2.19.
+            // A sequence's row slots are dealt to ZS workgroups where that shortens the busiest CU's queue: cost in slot
+            // turns = workgroups per CU x (slots per wave + 1/2 for the tile), at most (n_rows - n_seqs + 1) rows in a span
+            const int spw = ((n_rows - n_seqs + 1 + rp - 1) / rp + 3) / 4;
+            int zs_best = 1; long cost_best = -1;
+            for (int zs = 1; zs <= 8 && zs <= spw; zs *= 2) {
+                const long cost = ((base * zs + n_cu - 1) / n_cu) * (2 * ((spw + zs - 1) / zs) + 1);
+                if (cost_best < 0 || cost < cost_best) { cost_best = cost; zs_best = zs; }
+            }
+            a.slot_split = zs_best;
+            hipLaunchKernelGGL((k_attn_span<HD>), dim3(n_splits, n_kv, n_seqs * zs_best), dim3(256), attn_span_lds_bytes<HD>(), st, a);
+            RS_LAUNCHED("attn_span");
+        } else {
         const int slots = (n_rows + rp - 1) / rp, wpb = slots < 4 ? slots : 4;
         const dim3 grid(n_splits, n_kv, (slots + wpb - 1) / wpb);
-        if ((size_t)n_kv * a.max_ctx * HD * 4 <= ((size_t)16 << 20))
+        // the one-wave-per-SIMD build schedules best, but only while every wave of the launch is resident at once
+        const bool one = (long)grid.x * grid.y * grid.z * wpb <= 4L * n_cu && (size_t)n_kv * a.max_ctx * HD * 4 <= ((size_t)16 << 20);
+        if (one)
             hipLaunchKernelGGL((k_attn_partial_rows<HD, 1>), grid, dim3(64 * wpb), 0, st, a);
         else
             hipLaunchKernelGGL((k_attn_partial_rows<HD, 2>), grid, dim3(64 * wpb), 0, st, a);
         RS_LAUNCHED("attn_partial_rows");
+        }
     } else {
         // requesting every slice's K and V before the context length is known reads the rows' whole caches up to
         // max_ctx.  That saves a dependent round trip, but on a decode run that walks a 4608-position cache the
@@ -418,6 +441,7 @@ rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_to
     p.prep.embed = m->embed;
     p.prep.row_slot = m->at<int>(L.row_slot); p.prep.row_pos = m->at<int>(L.row_pos); p.prep.row_bad = m->at<int>(L.row_bad);
     p.prep.out_row = m->at<int>(L.out_row); p.prep.seq_bad = m->at<int>(L.seq_bad); p.prep.seq_scale = m->at<float>(L.seq_scale);
+    p.prep.seq_info = m->at<int4>(L.seq_info);
     p.prep.h = m->at<float>(L.h);
 
     GemvArgs &g = p.gemv;
@@ -457,7 +481,7 @@ rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_to
 // One decoder layer on the FMA kernels for a call of MP (1, 2 or 4) token-row slots: QKV, attention, O-proj,
 // gate/up, down.  Every phase reads the weights once and carries the rows side by side.
 template <int MP, typename Tic, typename Toc>
-rs_status fma_layer(rs_model *m, int l, GemvArgs &g, AttnArgs &aa, int n_rows, int n_splits, bool spans, hipStream_t st,
+rs_status fma_layer(rs_model *m, int l, GemvArgs &g, AttnArgs &aa, int n_rows, int n_splits, int n_seqs, hipStream_t st,
                     Tic tic, Toc toc) {
     const rs_config &c = m->cfg;
     const Layout &L = m->lay;
@@ -484,9 +508,9 @@ rs_status fma_layer(rs_model *m, int l, GemvArgs &g, AttnArgs &aa, int n_rows, i
     // attention
     tic(RS_PHASE_ATTN, l);
     switch (hd) {
-        case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
-        case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
-        default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+        case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, n_seqs, m->n_cu, st); break;
+        case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, n_seqs, m->n_cu, st); break;
+        default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, n_seqs, m->n_cu, st); break;
     }
     toc(RS_PHASE_ATTN, l);
     if (rc) return rc;
@@ -564,13 +588,13 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
     pa.embed = m->embed;
     pa.row_slot = row_slot; pa.row_pos = row_pos; pa.row_bad = row_bad;
     pa.out_row = m->at<int>(L.out_row); pa.seq_bad = m->at<int>(L.seq_bad); pa.seq_scale = m->at<float>(L.seq_scale);
+    pa.seq_info = m->at<int4>(L.seq_info);
     pa.h = h;
     hipLaunchKernelGGL(k_prepare, dim3(n_rows), dim3(256), 0, st, pa);
     RS_LAUNCHED("prepare");
 
     // attention launch shape; calls in which some sequence brings several rows share K/V tiles between rows
     const int n_splits = attn_splits(c, L, n_rows);
-    const bool spans = n_rows > n_seqs;
 
     // up to four token rows go through the FMA GEMV kernels (six kernels per layer, rows side by side against one
     // weight stream); more rows go through the matrix-core kernels
@@ -597,7 +621,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         aa.out = m->at<float>(L.attn_out);
         aa.out_planes = single ? nullptr : m->at<uint16_t>(L.attn_pl);
         aa.out_plane = (size_t)c.max_rows * qdim;
-        aa.row_pos = row_pos; aa.row_slot = row_slot; aa.row_bad = row_bad;
+        aa.row_pos = row_pos; aa.row_slot = row_slot; aa.row_bad = row_bad; aa.seq_info = m->at<int4>(L.seq_info);
         aa.n_q = c.n_q_heads; aa.n_kv = c.n_kv_heads; aa.max_ctx = c.max_ctx; aa.max_seqs = c.max_seqs; aa.layer = l;
 
         if (single) {
@@ -610,9 +634,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.qbuf = m->at<float>(L.qbuf); g.kcache = m->kv_k; g.vcache = m->kv_v;
             g.act = m->at<float>(L.act); g.h_out = h;
             switch (mp) {
-                case 1: rc = fma_layer<1>(m, l, g, aa, n_rows, n_splits, spans, st, tic, toc); break;
-                case 2: rc = fma_layer<2>(m, l, g, aa, n_rows, n_splits, spans, st, tic, toc); break;
-                default: rc = fma_layer<4>(m, l, g, aa, n_rows, n_splits, spans, st, tic, toc); break;
+                case 1: rc = fma_layer<1>(m, l, g, aa, n_rows, n_splits, n_seqs, st, tic, toc); break;
+                case 2: rc = fma_layer<2>(m, l, g, aa, n_rows, n_splits, n_seqs, st, tic, toc); break;
+                default: rc = fma_layer<4>(m, l, g, aa, n_rows, n_splits, n_seqs, st, tic, toc); break;
             }
             if (rc) return rc;
         } else {
@@ -641,9 +665,9 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             RS_LAUNCHED("rope_kv_rows");
             tic(RS_PHASE_ATTN, l);
             switch (hd) {
-                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
-                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
-                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, spans, st); break;
+                case 32: rc = launch_attn<32>(aa, n_splits, c.n_kv_heads, n_rows, n_seqs, m->n_cu, st); break;
+                case 64: rc = launch_attn<64>(aa, n_splits, c.n_kv_heads, n_rows, n_seqs, m->n_cu, st); break;
+                default: rc = launch_attn<128>(aa, n_splits, c.n_kv_heads, n_rows, n_seqs, m->n_cu, st); break;
             }
             toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
