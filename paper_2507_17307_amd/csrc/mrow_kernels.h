@@ -406,4 +406,184 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// k_gemm_tile: the same products for 33 .. 128 token rows, one workgroup per block of output columns.
+// A workgroup of four waves owns CT tiles of 16 output columns (gate/up: CT gate tiles and the CT matching
+// up tiles) and ALL token rows: wave w holds the rows 16 TB w .. 16 TB (w + 1) - 1 (TB = 1 or 2 blocks of
+// 16) against every column of the workgroup, so nothing has to be summed across waves and W is read from
+// HBM once per call, whatever the row count.  Per 64-element k window the four waves fetch the window's W
+// rows together (whole 128-byte row pieces, into registers, three windows ahead), park them in one of two
+// LDS buffers and every wave reads all of them back in A-operand layout; its X pieces (three planes,
+// B-operand layout, XD - 1 windows ahead) come straight from global memory because no other wave needs
+// them.  One barrier per window, and it is the bare instruction behind a wait for the LDS writes only:
+// __syncthreads() carries a fence that waits for every outstanding load, i.e. for the windows requested
+// ahead, and a window would cost a full memory round trip.
+// X costs (workgroups) x (rows) x K x 6 bytes of L2 traffic, which is why a workgroup takes as many column
+// tiles as the launch can afford (launch_gemm_tile picks CT and the split of K over workgroups so that the
+// workgroups are close to a whole number of rounds of the machine).
+// Modes: G_GATEUP (whole K, SwiGLU epilogue into the activation planes) and G_PART (K split ksplit >= 1
+// ways over workgroups, raw partial sums part[ks][row][n] for the next kernel to add up in a fixed order).
+// ------------------------------------------------------------------------------------------------
+constexpr int G_PART = 5;
+
+// windows per step: a step fetches 128 SW contiguous bytes of every W row.  One everywhere: two windows per step
+// (256-byte row pieces, two register slots each for W and X) measured slower (7B shape, 64 rows, gate/up 108 us
+// against 91)
+template <int TB> constexpr int tile_sw() { return 1; }
+
+template <int MODE, int TB, int CT>
+__host__ __device__ constexpr size_t gemm_tile_lds_bytes() {
+    return (size_t)2 * ((MODE == G_GATEUP) ? 2 : 1) * CT * 16 * (128 * tile_sw<TB>() + 16);
+}
+
+// workgroup barrier for LDS hand-over that leaves global loads in flight: the LDS accesses issued so far complete
+// (lgkmcnt(0); expcnt and vmcnt are left alone), then the barrier; the compiler moves no memory access across it
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int MODE, int TB, int CT>
+__global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
+    static_assert(MODE == G_GATEUP || MODE == G_PART, "gate/up or raw partial sums");
+    constexpr int NT = (MODE == G_GATEUP) ? 2 : 1;
+    constexpr int NS = GEMM_KW / 32;
+    constexpr int SW = tile_sw<TB>();                         // windows per step
+    constexpr int KSTEP = GEMM_KW * SW;                       // k elements per step: K must be a multiple
+    constexpr int PITCH = 128 * SW + 16;                      // bytes per parked row (padded against LDS bank conflicts)
+    constexpr int WROWS = NT * CT * 16;                       // W rows of a step
+    constexpr int RPR = 32 / SW;                              // rows per round of 256 16-byte loads
+    constexpr int WQ = (WROWS + RPR - 1) / RPR;               // loads per thread and step
+    constexpr size_t BUF = (size_t)WROWS * PITCH;
+    constexpr int XD = TB == 1 ? 3 : 2;                       // register slots of X (each holds a step's pieces)
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i16 = lane & 15, g = lane >> 4;
+    const int lrow = tid / (8 * SW), lchunk = tid % (8 * SW); // W load role: row RPR q + lrow of the step, bytes 16 lchunk ..
+    const int K = a.K;
+    const int n_out = (MODE == G_GATEUP) ? a.d_ffn : a.N;
+    const int n_tiles = (n_out + 15) / 16, n_groups = (n_tiles + CT - 1) / CT;
+    const int KSP = a.ksplit > 1 ? a.ksplit : 1;
+    const int n_st = K / KSTEP;                               // steps over the whole of K
+    const int unit = blockIdx.x;                              // one unit per workgroup
+    if (unit >= n_groups * KSP) return;
+    const int grp = unit / KSP, ksp = unit - grp * KSP;
+    const int s_lo = (int)(((long long)n_st * ksp) / KSP), s_hi = (int)(((long long)n_st * (ksp + 1)) / KSP);
+    const int n0 = grp * CT * 16;
+    if (s_hi <= s_lo) return;                                 // (the launch never splits K finer than its steps)
+
+    // W rows this thread fetches: step row j < CT * 16 is output column n0 + j (gate), the others the matching up rows
+    const uint16_t *wp[WQ];
+    bool wok[WQ];
+#pragma unroll
+    for (int q = 0; q < WQ; ++q) {
+        const int j = RPR * q + lrow;
+        wok[q] = j < WROWS;
+        const int jj = wok[q] ? j : 0, half = jj / (CT * 16), col = jj - half * (CT * 16);
+        const int row = min(n0 + col, n_out - 1) + (half ? a.d_ffn : 0);
+        wp[q] = a.W + (size_t)row * K + lchunk * 8;
+    }
+    // token rows of this wave; a row past the call's rows repeats row 0: its products fill matrix-core columns that
+    // belong to no row and are never stored
+    const uint16_t *xp[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int m = (wave * TB + tb) * 16 + i16;
+        xp[tb] = a.X + (size_t)(m < a.M ? m : 0) * K + g * 8;
+    }
+    f32x4_t acc[TB][NT][CT];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[tb][nt][ct] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+    // a step past the last is replaced by the last (fetched again, never used): requests are unconditional
+    auto request_w = [&](int st, uint4 (&wr)[WQ]) {
+        const int k0 = min(st, s_hi - 1) * KSTEP;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q) wr[q] = load_stream(reinterpret_cast<const uint4 *>(wp[q] + k0));
+    };
+    auto request_x = [&](int st, uint4 (&xb)[SW][TB][NS][3]) {
+        const int k0 = min(st, s_hi - 1) * KSTEP;
+#pragma unroll
+        for (int sw = 0; sw < SW; ++sw)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                for (int s_ = 0; s_ < NS; ++s_)
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl)
+                        xb[sw][tb][s_][pl] = *reinterpret_cast<const uint4 *>(xp[tb] + pl * a.x_plane + k0 + GEMM_KW * sw + 32 * s_);
+    };
+    auto park = [&](int buf, const uint4 (&wr)[WQ]) {
+        unsigned char *base = smem + (size_t)buf * BUF;
+#pragma unroll
+        for (int q = 0; q < WQ; ++q)
+            if (wok[q]) *reinterpret_cast<uint4 *>(base + (size_t)(RPR * q + lrow) * PITCH + lchunk * 16) = wr[q];
+    };
+    auto multiply = [&](int buf, const uint4 (&xb)[SW][TB][NS][3]) {
+        const unsigned char *base = smem + (size_t)buf * BUF;
+#pragma unroll
+        for (int sw = 0; sw < SW; ++sw)
+#pragma unroll
+            for (int s_ = 0; s_ < NS; ++s_)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(
+                            base + (size_t)((nt * CT + ct) * 16 + i16) * PITCH + (4 * (NS * sw + s_) + g) * 16));
+#pragma unroll
+                        for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                            for (int pl = 2; pl >= 0; --pl)           // smallest plane first
+                                acc[tb][nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    A, __builtin_bit_cast(bf16x8_t, xb[sw][tb][s_][pl]), acc[tb][nt][ct], 0, 0, 0);
+                    }
+    };
+
+    // register slots: WD for W, XD for X.  When step t is multiplied, the W rows of t + 1 .. t + WD and the X pieces
+    // of t + 1 .. t + XD - 1 are in flight or have arrived; every request goes into the slot that the step before
+    // has just consumed, before this step's products.
+    constexpr int WD = SW == 1 ? 3 : 2;
+    constexpr int UNR = WD == XD ? WD : WD * XD;              // steps after which both slot patterns repeat (2 and 3 are coprime)
+    uint4 wr[WD][WQ], xb[XD][SW][TB][NS][3];
+#pragma unroll
+    for (int v = 0; v < WD; ++v) request_w(s_lo + v, wr[v]);
+#pragma unroll
+    for (int v = 0; v < XD - 1; ++v) request_x(s_lo + v, xb[v]);
+    int buf = 0;
+    for (int st = s_lo; st < s_hi; st += UNR) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (st + u >= s_hi) break;
+            park(buf, wr[u % WD]);
+            lds_barrier();                                    // the step is in LDS; everybody is done with the other buffer's last use
+            request_w(st + u + WD, wr[u % WD]);
+            request_x(st + u + XD - 1, xb[(u + XD - 1) % XD]);
+            multiply(buf, xb[u % XD]);
+            buf ^= 1;
+        }
+    }
+
+    // epilogue: this lane holds output columns n0 + 16 ct + 4 g + r of token 16 (wave TB + tb) + i16
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int m = (wave * TB + tb) * 16 + i16;
+        if (m >= a.M) continue;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const int tile = grp * CT + ct;
+            if (tile >= n_tiles) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int n = tile * 16 + 4 * g + r;
+                if (n >= n_out) continue;
+                const float val = acc[tb][0][ct][r];
+                if (MODE == G_PART) a.part[ksp * a.part_stride + (size_t)m * n_out + n] = val;
+                else split_store(val / (1.0f + expf(-val)) * acc[tb][NT - 1][ct][r], a.act, a.act_plane, (size_t)m * a.d_ffn + n);
+            }
+        }
+    }
+}
+
 }  // namespace rs

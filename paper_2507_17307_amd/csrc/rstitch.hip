@@ -384,6 +384,74 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
     }
 }
 
+// Launch of k_gemm_tile (33 .. 128 token rows).  CT (column tiles per workgroup) and, for the modes that leave partial
+// sums, the split of K are picked so that the workgroups come as close as possible to a whole number of rounds of the
+// machine with one workgroup per CU (each workgroup streams its share of W at the rate a CU can draw, so a round that
+// fills a fraction of the CUs costs a whole round); ties go to the larger CT (less X traffic) and the smaller split.
+template <int MODE, int TB, int CT>
+rs_status launch_gemm_tile_ct(GemmArgs &a, int blocks, hipStream_t st, const char *name) {
+    constexpr size_t lds = gemm_tile_lds_bytes<MODE, TB, CT>();
+    static_assert(lds <= 128 * 1024, "one workgroup per CU with room to spare");
+    if (lds > 64 * 1024) {
+        static std::atomic<bool> raised{false};           // per instantiation; setting the attribute twice is harmless
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_gemm_tile<MODE, TB, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((k_gemm_tile<MODE, TB, CT>), dim3(blocks), dim3(256), lds, st, a);
+    RS_LAUNCHED(name);
+    return RS_OK;
+}
+
+struct TilePlan { int ct, ks; double eff; };
+
+TilePlan plan_gemm_tile(bool gateup, int n_tiles, int n_win, int n_cu) {
+    static const int ct_gu[] = {5, 4, 3, 2}, ct_part[] = {10, 8, 7, 6, 4};
+    TilePlan best{0, 1, -1.0};
+    const int *cts = gateup ? ct_gu : ct_part;
+    const int n_ct = gateup ? 4 : 5;
+    for (int i = 0; i < n_ct; ++i) {
+        const int ct = cts[i], groups = (n_tiles + ct - 1) / ct;
+        for (int ks = 1; ks <= (gateup ? 1 : GEMM_KSPLIT_MAX); ++ks) {
+            if (ks > 1 && n_win / ks < 6) break;
+            const int units = groups * ks, rounds = (units + n_cu - 1) / n_cu;
+            const double eff = (double)units / ((double)rounds * n_cu) * ((double)n_tiles / ((double)groups * ct));
+            if (eff > best.eff + 1e-9) best = TilePlan{ct, ks, eff};
+        }
+    }
+    return best;
+}
+
+template <int MODE, int TB>
+rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
+    const TilePlan p = plan_gemm_tile(MODE == G_GATEUP, n_tiles, a.K / GEMM_KW, m->n_cu);
+    const int groups = (n_tiles + p.ct - 1) / p.ct;
+    a.yblocks = 1; a.ksplit = p.ks; a.part = nullptr; a.part_stride = 0;
+    if constexpr (MODE == G_PART) {
+        a.part = m->at<float>(m->lay.gemm_part);
+        a.part_stride = (size_t)m->cfg.max_rows * (size_t)a.N;
+    }
+    const int blocks = groups * p.ks;
+    if constexpr (MODE == G_GATEUP) {
+        switch (p.ct) {
+            case 5: return launch_gemm_tile_ct<MODE, TB, 5>(a, blocks, st, name);
+            case 4: return launch_gemm_tile_ct<MODE, TB, 4>(a, blocks, st, name);
+            case 3: return launch_gemm_tile_ct<MODE, TB, 3>(a, blocks, st, name);
+            default: return launch_gemm_tile_ct<MODE, TB, 2>(a, blocks, st, name);
+        }
+    } else {
+        switch (p.ct) {
+            case 10: return launch_gemm_tile_ct<MODE, TB, 10>(a, blocks, st, name);
+            case 8: return launch_gemm_tile_ct<MODE, TB, 8>(a, blocks, st, name);
+            case 7: return launch_gemm_tile_ct<MODE, TB, 7>(a, blocks, st, name);
+            case 6: return launch_gemm_tile_ct<MODE, TB, 6>(a, blocks, st, name);
+            default: return launch_gemm_tile_ct<MODE, TB, 4>(a, blocks, st, name);
+        }
+    }
+}
+
 // n_tiles = number of 16-column output tiles; 16 * NB token rows compiled in (NB = 1, 2 or 4)
 template <int MODE>
 rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
@@ -398,6 +466,15 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
         // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.0 ms, 64 rows 9.1 ms this
         // way; 64-row blocks are no faster (9.7 ms) and 16-row blocks slower.
         if (a.M <= 16) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
+        // more than 32 rows: one workgroup per block of output columns holds all rows (k_gemm_tile).  Measured per call
+        // against 32-row blocks with workgroups of their own: 7B shape 64 rows 9.57 -> 7.4 ms, 128 rows 14.9 -> 12.0; 14B
+        // 64 rows 24.0 -> 19.7, 128 rows 44.7 -> 35.9; 32B 128 rows 78.6 -> 62.6; a 1536-wide model has too few column
+        // blocks for it beyond 48 rows (1.5B shape: 33 rows 3.50 -> 3.06, 48 rows 3.50 -> 3.32, but 128 rows 5.43 -> 5.68)
+        if (a.M > 32 && (m->cfg.d_model >= 2048 || a.M <= 48)) {
+            // partial sums are always left for the next kernel (a split of one is a plain copy of the result)
+            if constexpr (MODE == G_GATEUP) return a.M <= 64 ? launch_gemm_tile<G_GATEUP, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_GATEUP, 2>(m, a, n_tiles, st, name);
+            else return a.M <= 64 ? launch_gemm_tile<G_PART, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_PART, 2>(m, a, n_tiles, st, name);
+        }
         a.yblocks = (a.M + 31) / 32;
         return launch_gemm_nb<MODE, 2>(m, a, n_tiles, st, name);
     }
@@ -655,7 +732,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv"))) return rc;
             toc(RS_PHASE_QKV, l);
             RopeArgs ra{};
-            ra.qkv = g.ksplit > 1 ? g.part : m->at<float>(L.qkv_raw); ra.ksplit = g.ksplit; ra.part_stride = g.part_stride;
+            ra.qkv = g.part ? g.part : m->at<float>(L.qkv_raw); ra.ksplit = g.ksplit; ra.part_stride = g.part_stride;
             ra.qbuf = m->at<float>(L.qbuf); ra.kcache = m->kv_k; ra.vcache = m->kv_v;
             ra.rope_cos = m->at<float>(L.rope_cos); ra.rope_sin = m->at<float>(L.rope_sin);
             ra.row_pos = row_pos; ra.row_slot = row_slot; ra.row_bad = row_bad;
@@ -678,7 +755,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj"))) return rc;
             toc(RS_PHASE_OPROJ, l);
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->mlp_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)(g.ksplit > 1 ? g.part : nullptr),
+                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)g.part,
                                g.ksplit, g.part_stride);
             RS_LAUNCHED("rmsnorm_rows");
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
@@ -691,7 +768,7 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             tic(RS_PHASE_DOWN, l);
             if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down"))) return rc;
             toc(RS_PHASE_DOWN, l);
-            if (g.ksplit > 1) { pend_part = g.part; pend_ks = g.ksplit; pend_stride = g.part_stride; }
+            if (g.part) { pend_part = g.part; pend_ks = g.ksplit; pend_stride = g.part_stride; }
         }
     }
 
