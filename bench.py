@@ -242,7 +242,7 @@ def bench_single_model(args, wl) -> int:
 
     w_s = W.make_weights(wl.slm, wl.seed, 0, device="cuda")
     max_ctx = wl.max_ctx
-    slm = P.Model(w_s, max_ctx=max_ctx, max_rows=64)
+    slm = P.Model(w_s, max_ctx=max_ctx, max_rows=128)
     pair = StitchedPair(slm, None, max_ctx, W.logit_scale(wl, 0, max_ctx + 1))
     prompt = W.make_prompt(wl).tolist()
     marks = {}
@@ -431,8 +431,8 @@ def main() -> int:
     torch.cuda.synchronize()
     log(f"[bench] weights generated on the GPU in {time.time() - t0:.1f}s")
     max_ctx = wl.max_ctx
-    slm = P.Model(w_s, max_ctx=max_ctx, max_rows=64)
-    llm = P.Model(w_l, max_ctx=max_ctx, max_rows=64)
+    slm = P.Model(w_s, max_ctx=max_ctx, max_rows=128)
+    llm = P.Model(w_l, max_ctx=max_ctx, max_rows=128)
     prompt = W.make_prompt(wl).tolist()
     scales = W.logit_scale(wl, 0, max_ctx + 1)
     pair = StitchedPair(slm, llm, max_ctx, scales)

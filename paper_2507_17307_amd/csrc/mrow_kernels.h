@@ -522,23 +522,31 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     };
     auto multiply = [&](int buf, const uint4 (&xb)[SW][TB][NS][3]) {
         const unsigned char *base = smem + (size_t)buf * BUF;
+        // per k step: the A operands of all tiles first, then the planes outermost (smallest first), so that
+        // consecutive matrix-core instructions write different accumulators: a product that has to wait for the
+        // one before it (same accumulator) stalls the pipe for that one's whole latency
 #pragma unroll
         for (int sw = 0; sw < SW; ++sw)
 #pragma unroll
-            for (int s_ = 0; s_ < NS; ++s_)
+            for (int s_ = 0; s_ < NS; ++s_) {
+                bf16x8_t A[NT][CT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(
+                    for (int ct = 0; ct < CT; ++ct)
+                        A[nt][ct] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(
                             base + (size_t)((nt * CT + ct) * 16 + i16) * PITCH + (4 * (NS * sw + s_) + g) * 16));
 #pragma unroll
-                        for (int tb = 0; tb < TB; ++tb)
+                for (int pl = 2; pl >= 0; --pl)
 #pragma unroll
-                            for (int pl = 2; pl >= 0; --pl)           // smallest plane first
+                    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                            for (int ct = 0; ct < CT; ++ct)
                                 acc[tb][nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    A, __builtin_bit_cast(bf16x8_t, xb[sw][tb][s_][pl]), acc[tb][nt][ct], 0, 0, 0);
-                    }
+                                    A[nt][ct], __builtin_bit_cast(bf16x8_t, xb[sw][tb][s_][pl]), acc[tb][nt][ct], 0, 0, 0);
+            }
     };
 
     // register slots: WD for W, XD for X.  When step t is multiplied, the W rows of t + 1 .. t + WD and the X pieces

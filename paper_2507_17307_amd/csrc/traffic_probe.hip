@@ -43,8 +43,8 @@ int main(int argc, char **argv) {
     else { fprintf(stderr, "shape must be s15, m7, m14 or m32\n"); return 2; }
     c.n_layers = layers; c.head_dim = 128; c.vocab = 152064; c.tied_lm_head = 1;
     if (!c.max_ctx) c.max_ctx = 4608;
-    c.max_seqs = 1; c.max_rows = 64; c.rms_eps = 1e-6f; c.rope_theta = 1e6f;
-    if (layers < 1 || layers > 64 || steps < 1 || position < 0 || position >= c.max_ctx || span < 1 || span > 64 || span > position + 1) { fprintf(stderr, "bad arguments\n"); return 2; }
+    c.max_seqs = 1; c.max_rows = 128; c.rms_eps = 1e-6f; c.rope_theta = 1e6f;
+    if (layers < 1 || layers > 64 || steps < 1 || position < 0 || position >= c.max_ctx || span < 1 || span > 128 || span > position + 1) { fprintf(stderr, "bad arguments\n"); return 2; }
     setenv("RSTITCH_GRAPHS", "0", 1);                      // plain launches: one dispatch per kernel for the profiler
 
     const size_t qkv_rows = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, qdim = (size_t)c.n_q_heads * c.head_dim;
