@@ -118,6 +118,51 @@ def test_batched_ragged_calls_match_per_sequence_oracle(spans, decode_path):
         check_invocation(got[i], lg[i], ref, 0.7, router.SLM, where=f"decode seq {i}")
 
 
+TILE_CASES = [("one_span_33", [33]), ("one_span_64", [64]), ("one_span_100", [100]), ("two_spans_128", [59, 69]),
+              ("ragged_20_seqs_90_rows", [1, 9, 2, 7, 3, 8, 4, 6, 5, 5, 1, 9, 2, 7, 3, 8, 4, 2, 3, 1]), ("decode_128", [1] * 128)]
+
+
+@pytest.mark.parametrize("name,spans", TILE_CASES, ids=[c[0] for c in TILE_CASES])
+def test_calls_of_33_to_128_rows_on_a_2048_wide_shape_match_the_oracle(name, spans):
+    """Calls of more than 32 rows on a model at least 2048 wide take the kernel in which one workgroup holds all rows of
+    the call against a block of output columns (one or two blocks of 16 rows per wave, K split over workgroups for
+    QKV / O-proj / down).  The shape has tile counts that leave ragged last column groups (352 gate/up tiles, 192 QKV
+    tiles, 128 model tiles) and 32 / 88 k windows."""
+    import paper_2507_17307_amd as P
+    from workloads.shapes import ModelShape
+    shape = ModelShape("wide_2layers", 2, 2048, 16, 4, 128, 5632, 8192, tied_lm_head=False)
+    w = W.make_weights(shape, 31, 1)
+    n = len(spans)
+    n_slots = next(k for k in (2, 32, 128) if k >= n)
+    max_ctx = 160
+    gpu = P.Model(w.to("cuda"), max_ctx=max_ctx, max_seqs=n_slots, max_rows=128)
+    ref = decoder.OracleModel(w, max_ctx, n_slots=n_slots)
+    slots = [(7 * i + 3) % n_slots for i in range(n)]
+    pre = [5 + (11 * i) % 23 for i in range(n)]
+    toks = [W.rng.randint(31, 400 + i, 0, pre[i] + spans[i] + 1, shape.vocab).tolist() for i in range(n)]
+    for i in range(n):
+        ref.forward(toks[i][:pre[i]], 0, slot=slots[i])
+        gpu.forward_span(toks[i][:pre[i]], 0, 0.5, P.RS_LLM, slot=slots[i])
+    scales = [1.0 + 0.5 * (i % 10) for i in range(n)]
+    if all(sp == 1 for sp in spans):
+        got, lg = gpu.decode_step([toks[i][pre[i]] for i in range(n)], pre, 0.7, P.RS_LLM, scales, slots, want_logits=True)
+    else:
+        got, lg = gpu.catchup_prefill([toks[i][pre[i]:pre[i] + spans[i]] for i in range(n)], pre, 0.7, P.RS_LLM,
+                                      scales, slots, want_logits=True)
+    torch.cuda.synchronize()
+    for i in range(n):
+        want = ref.forward(toks[i][pre[i]:pre[i] + spans[i]], pre[i], slot=slots[i], logit_scale=scales[i])["logits"]
+        check_invocation(got[i], lg[i], want, 0.7, router.LLM, where=f"{name} sequence {i} ({spans[i]} rows at {pre[i]})")
+    # the K/V rows the call wrote, every layer: they are what later calls read
+    kg, vg = gpu.kv_view("k").float().cpu().double(), gpu.kv_view("v").float().cpu().double()
+    for i in range(n):
+        sl, lo, hi = slots[i], pre[i], pre[i] + spans[i]
+        for got_c, want_c, what in ((kg, ref.k_cache, "k"), (vg, ref.v_cache, "v")):
+            g_rows, w_rows = got_c[:, sl, :, lo:hi], want_c[:, sl, :, lo:hi]
+            err = float((g_rows - w_rows).abs().max())
+            assert err <= 2.0 ** -7 * float(w_rows.abs().max()) + 1e-6, f"{name}: {what} rows of sequence {i} differ by {err}"
+
+
 def test_batched_decode_over_large_caches_matches_per_sequence_oracle():
     """Three sequences, one token each, on a model whose caches (three slots of 2 KV heads x 2048 positions x
     128 channels) are large enough that the single-row attention kernel waits for each row's position before it
