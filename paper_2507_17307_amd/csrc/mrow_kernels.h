@@ -421,8 +421,9 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
 // X costs (workgroups) x (rows) x K x 6 bytes of L2 traffic, which is why a workgroup takes as many column
 // tiles as the launch can afford (launch_gemm_tile picks CT and the split of K over workgroups so that the
 // workgroups are close to a whole number of rounds of the machine).
-// Modes: G_GATEUP (whole K, SwiGLU epilogue into the activation planes) and G_PART (K split ksplit >= 1
-// ways over workgroups, raw partial sums part[ks][row][n] for the next kernel to add up in a fixed order).
+// Modes: G_GATEUP (whole K, SwiGLU epilogue into the activation planes), G_PART (K split ksplit >= 1
+// ways over workgroups, raw partial sums part[ks][row][n] for the next kernel to add up in a fixed order) and
+// G_LMHEAD (whole K; scaled logits feed each row's single-pass softmax state, one partial per row and workgroup).
 // ------------------------------------------------------------------------------------------------
 constexpr int G_PART = 5;
 
@@ -442,7 +443,7 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 template <int MODE, int TB, int CT>
 __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
-    static_assert(MODE == G_GATEUP || MODE == G_PART, "gate/up or raw partial sums");
+    static_assert(MODE == G_GATEUP || MODE == G_PART || MODE == G_LMHEAD, "gate/up, raw partial sums or the LM head");
     constexpr int NT = (MODE == G_GATEUP) ? 2 : 1;
     constexpr int NS = GEMM_KW / 32;
     constexpr int SW = tile_sw<TB>();                         // windows per step
@@ -577,6 +578,32 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         const int m = (wave * TB + tb) * 16 + i16;
+        if (MODE == G_LMHEAD) {
+            // the row's softmax state over this workgroup's columns: every lane pushes its logits, the four lanes of a
+            // token (g = 0..3) merge, one partial per (row, workgroup).  Uniform control flow: the merge shuffles
+            const bool ok = m < a.M;
+            SoftState st; st.init();
+            const float lm_scale = ok ? a.seq_scale[m] : 1.f;
+            unsigned long long noise_base = 0;
+            if (a.sample_on && ok) noise_base = (unsigned long long)(a.row_pos[a.out_row[m]] + 1) * (unsigned long long)a.N;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int n = (grp * CT + ct) * 16 + 4 * g + r;
+                    if (!ok || n >= n_out) continue;
+                    const float lg = acc[tb][0][ct][r] * lm_scale;
+                    st.push(lg, n);
+                    if (a.sample_on) st.push_noisy(lg, n, a.sample_key, noise_base);
+                    if (a.logits) a.logits[(size_t)m * a.N + n] = lg;
+                }
+            for (int o = 32; o >= 16; o >>= 1) {
+                SoftState b = shfl_xor_state(st, o);
+                if ((lane & o) == 0) st.merge(b); else { b.merge(st); st = b; }
+            }
+            if (g == 0 && ok) a.parts[(size_t)m * a.n_parts + grp] = to_partial(st);
+            continue;
+        }
         if (m >= a.M) continue;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {

@@ -407,14 +407,14 @@ rs_status launch_gemm_tile_ct(GemmArgs &a, int blocks, hipStream_t st, const cha
 
 struct TilePlan { int ct, ks; double eff; };
 
-TilePlan plan_gemm_tile(bool gateup, int n_tiles, int n_win, int n_cu) {
+TilePlan plan_gemm_tile(bool gateup, bool split, int n_tiles, int n_win, int n_cu) {
     static const int ct_gu[] = {5, 4, 3, 2}, ct_part[] = {10, 8, 7, 6, 4};
     TilePlan best{0, 1, -1.0};
     const int *cts = gateup ? ct_gu : ct_part;
     const int n_ct = gateup ? 4 : 5;
     for (int i = 0; i < n_ct; ++i) {
         const int ct = cts[i], groups = (n_tiles + ct - 1) / ct;
-        for (int ks = 1; ks <= (gateup ? 1 : GEMM_KSPLIT_MAX); ++ks) {
+        for (int ks = 1; ks <= (split ? GEMM_KSPLIT_MAX : 1); ++ks) {
             if (ks > 1 && n_win / ks < 6) break;
             const int units = groups * ks, rounds = (units + n_cu - 1) / n_cu;
             const double eff = (double)units / ((double)rounds * n_cu) * ((double)n_tiles / ((double)groups * ct));
@@ -426,7 +426,7 @@ TilePlan plan_gemm_tile(bool gateup, int n_tiles, int n_win, int n_cu) {
 
 template <int MODE, int TB>
 rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
-    const TilePlan p = plan_gemm_tile(MODE == G_GATEUP, n_tiles, a.K / GEMM_KW, m->n_cu);
+    const TilePlan p = plan_gemm_tile(MODE == G_GATEUP, MODE == G_PART, n_tiles, a.K / GEMM_KW, m->n_cu);
     const int groups = (n_tiles + p.ct - 1) / p.ct;
     a.yblocks = 1; a.ksplit = p.ks; a.part = nullptr; a.part_stride = 0;
     if constexpr (MODE == G_PART) {
@@ -434,6 +434,7 @@ rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStrea
         a.part_stride = (size_t)m->cfg.max_rows * (size_t)a.N;
     }
     const int blocks = groups * p.ks;
+    if constexpr (MODE == G_LMHEAD) a.n_parts = groups;             // one partial per row and workgroup
     if constexpr (MODE == G_GATEUP) {
         switch (p.ct) {
             case 5: return launch_gemm_tile_ct<MODE, TB, 5>(a, blocks, st, name);
@@ -458,7 +459,11 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
     if (a.K % GEMM_KW) return fail(RS_EINVAL, "internal: K = %d is not a multiple of %d", a.K, GEMM_KW);
     a.yblocks = 1;
     if constexpr (MODE == G_LMHEAD) {
-        // more than 16 sequences: 16-row blocks, each with workgroups of its own (a lane's softmax state follows one row)
+        // more than 16 sequences: one workgroup per block of vocabulary columns holds all rows, so the matrix is read once
+        // (16-row blocks with workgroups of their own cost 230 us per block on the 7B shape: 1.85 ms at 128 sequences
+        // against 0.57 ms; 1.5B shape 0.86 -> 0.30 ms)
+        if (a.M > 16 && (n_tiles + 3) / 4 <= LM_PARTS_CAP)       // (at least four column tiles per workgroup)
+            return a.M <= 64 ? launch_gemm_tile<G_LMHEAD, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_LMHEAD, 2>(m, a, n_tiles, st, name);
         a.yblocks = (a.M + 15) / 16;
         return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
     } else {

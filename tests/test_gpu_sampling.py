@@ -72,6 +72,39 @@ def test_sampled_tokens_of_every_lm_head_path_match_the_oracle(shape_name):
     check_invocation(got[0], lg[0], ref.forward([toks[0][15]], 15, slot=0, logit_scale=2.0)["logits"], tau, router.LLM, where="greedy again")
 
 
+def test_sampled_tokens_of_a_step_over_more_than_sixteen_sequences_match_the_oracle():
+    """24 and 70 sequences in one decode step: the LM head in which one workgroup holds all rows (one and two blocks of 16
+    rows per wave)."""
+    import paper_2507_17307_amd as P
+    shape = W.TINY_L
+    w = W.make_weights(shape, 13, 1)
+    key = W.stream_key(13, 4242)
+    for n in (24, 70):
+        gpu = P.Model(w.to("cuda"), max_ctx=32, max_seqs=128, max_rows=128)
+        P.rs_set_sampling(gpu.handle, True, key)
+        ref = decoder.OracleModel(w, 32, n_slots=128)
+        slots = [(5 * i + 2) % 128 for i in range(n)]
+        toks = W.rng.randint(13, 70 + n, 0, n, shape.vocab).tolist()
+        pos = [i % 7 for i in range(n)]
+        for i in range(n):                                     # earlier positions of every sequence, one call per sequence
+            if pos[i]:
+                pre = W.rng.randint(13, 500 + i, 0, pos[i], shape.vocab).tolist()
+                ref.forward(pre, 0, slot=slots[i])
+                gpu.forward_span(pre, 0, 0.5, P.RS_LLM, slot=slots[i])
+        scales = [1.0 + 0.25 * (i % 16) for i in range(n)]
+        got, lg = gpu.decode_step(toks, pos, 0.6, P.RS_SLM, scales, slots, want_logits=True)
+        torch.cuda.synchronize()
+        compared = 0
+        for i in range(n):
+            want = ref.forward([toks[i]], pos[i], slot=slots[i], logit_scale=scales[i])["logits"]
+            check_invocation(dataclasses.replace(got[i], token=router.greedy_token(want)), lg[i], want, 0.6, router.SLM, where=f"{n} sequences, sequence {i}")
+            tok, gap = expected_token(want, key, pos[i] + 1)
+            if gap >= GAP:
+                compared += 1
+                assert got[i].token == tok, f"{n} sequences, sequence {i}: sampled {got[i].token}, oracle {tok} (gap {gap})"
+        assert compared >= n - 3
+
+
 def test_sampled_draws_follow_the_distribution_on_the_gpu():
     """The same step run under 4000 different keys: the frequencies of the drawn tokens follow the step's softmax
     probabilities (a property check that does not involve the oracle's generator)."""
