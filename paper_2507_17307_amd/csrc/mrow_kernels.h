@@ -45,7 +45,7 @@ __device__ __forceinline__ float4 sum_splits4(const float *base, size_t i, int k
 __global__ void __launch_bounds__(ROWK_THREADS)
 k_rmsnorm_rows(float *__restrict__ h, const uint16_t *__restrict__ gain, float eps, int d,
                const int *__restrict__ gather, uint16_t *__restrict__ out, size_t plane,
-               const float *__restrict__ part, int ksplit, size_t part_stride) {
+               const float *__restrict__ part, int ksplit, size_t part_stride, float *__restrict__ out32) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int src = gather ? gather[blockIdx.x] : blockIdx.x;
     float *hr = h + (size_t)src * d;
@@ -95,6 +95,7 @@ k_rmsnorm_rows(float *__restrict__ h, const uint16_t *__restrict__ gain, float e
             w2[q] = pack_bf16x2(ra - bf16_lo(w1[q]), rb - bf16_hi(w1[q]));
         }
         const size_t o = (size_t)blockIdx.x * d + 4 * i4;
+        if (out32) { *reinterpret_cast<float4 *>(out32 + o) = make_float4(x[0], x[1], x[2], x[3]); continue; }   // the consumer splits
         *reinterpret_cast<uint2 *>(out + o) = make_uint2(w0[0], w0[1]);
         *reinterpret_cast<uint2 *>(out + plane + o) = make_uint2(w1[0], w1[1]);
         *reinterpret_cast<uint2 *>(out + 2 * plane + o) = make_uint2(w2[0], w2[1]);
@@ -171,6 +172,8 @@ __global__ void __launch_bounds__(ROWK_THREADS) k_rope_kv_rows(RopeArgs a) {
 struct GemmArgs {
     const uint16_t *W; int N, K, M;       // M = valid token rows
     const uint16_t *X; size_t x_plane;    // three [.., K] bf16 planes, x_plane elements apart
+    const float *X32;                     // k_gemm_tile: the same activations as plain fp32 rows [.., K] (split into planes by the consumer)
+    float *act32;                         // k_gemm_tile, gate/up: SwiGLU output rows [.., d_ffn] fp32
     float *out_f32; int ld_out;           // raw fp32 output [M, ld_out] (QKV)
     int yblocks;                          // > 1: the token rows are cut into yblocks blocks of 16*NB rows, each taken by its own
                                           //      workgroups (same weights; ids arranged so that they meet in one XCD's L2)
@@ -412,13 +415,13 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
 // up tiles) and ALL token rows: wave w holds the rows 16 TB w .. 16 TB (w + 1) - 1 (TB = 1 or 2 blocks of
 // 16) against every column of the workgroup, so nothing has to be summed across waves and W is read from
 // HBM once per call, whatever the row count.  Per 64-element k window the four waves fetch the window's W
-// rows together (whole 128-byte row pieces, into registers, three windows ahead), park them in one of two
-// LDS buffers and every wave reads all of them back in A-operand layout; its X pieces (three planes,
-// B-operand layout, XD - 1 windows ahead) come straight from global memory because no other wave needs
-// them.  One barrier per window, and it is the bare instruction behind a wait for the LDS writes only:
+// rows together (whole 128-byte row pieces, into registers, up to six windows ahead), park them in one of two
+// LDS buffers and every wave reads all of them back in A-operand layout; its X pieces (fp32 rows, split
+// into the three planes in registers, XD - 1 windows ahead) come straight from global memory because no
+// other wave needs them.  One barrier per window, and it is the bare instruction behind a wait for the LDS writes only:
 // __syncthreads() carries a fence that waits for every outstanding load, i.e. for the windows requested
 // ahead, and a window would cost a full memory round trip.
-// X costs (workgroups) x (rows) x K x 6 bytes of L2 traffic, which is why a workgroup takes as many column
+// X costs (workgroups) x (rows) x K x 4 bytes of L2 traffic, which is why a workgroup takes as many column
 // tiles as the launch can afford (launch_gemm_tile picks CT and the split of K over workgroups so that the
 // workgroups are close to a whole number of rounds of the machine).
 // Modes: G_GATEUP (whole K, SwiGLU epilogue into the activation planes), G_PART (K split ksplit >= 1
@@ -483,11 +486,11 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     }
     // token rows of this wave; a row past the call's rows repeats row 0: its products fill matrix-core columns that
     // belong to no row and are never stored
-    const uint16_t *xp[TB];
+    const float *xp[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         const int m = (wave * TB + tb) * 16 + i16;
-        xp[tb] = a.X + (size_t)(m < a.M ? m : 0) * K + g * 8;
+        xp[tb] = a.X32 + (size_t)(m < a.M ? m : 0) * K + g * 8;
     }
     f32x4_t acc[TB][NT][CT];
 #pragma unroll
@@ -503,17 +506,20 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
 #pragma unroll
         for (int q = 0; q < WQ; ++q) wr[q] = load_stream(reinterpret_cast<const uint4 *>(wp[q] + k0));
     };
-    auto request_x = [&](int st, uint4 (&xb)[SW][TB][NS][3]) {
+    // X arrives as fp32 (8 consecutive k per lane and k step: two 16-byte loads, a whole 128-byte line per row and
+    // step over the four lanes of a token) and is split into the three bf16 planes here: 4 bytes per element through
+    // the CU's load path instead of 6
+    auto request_x = [&](int st, float4 (&xb)[SW][TB][NS][2]) {
         const int k0 = min(st, s_hi - 1) * KSTEP;
 #pragma unroll
         for (int sw = 0; sw < SW; ++sw)
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-                for (int s_ = 0; s_ < NS; ++s_)
-#pragma unroll
-                    for (int pl = 0; pl < 3; ++pl)
-                        xb[sw][tb][s_][pl] = *reinterpret_cast<const uint4 *>(xp[tb] + pl * a.x_plane + k0 + GEMM_KW * sw + 32 * s_);
+                for (int s_ = 0; s_ < NS; ++s_) {
+                    const float4 *q = reinterpret_cast<const float4 *>(xp[tb] + k0 + GEMM_KW * sw + 32 * s_);
+                    xb[sw][tb][s_][0] = q[0]; xb[sw][tb][s_][1] = q[1];
+                }
     };
     auto park = [&](int buf, const uint4 (&wr)[WQ]) {
         unsigned char *base = smem + (size_t)buf * BUF;
@@ -521,7 +527,7 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
         for (int q = 0; q < WQ; ++q)
             if (wok[q]) *reinterpret_cast<uint4 *>(base + (size_t)(RPR * q + lrow) * PITCH + lchunk * 16) = wr[q];
     };
-    auto multiply = [&](int buf, const uint4 (&xb)[SW][TB][NS][3]) {
+    auto multiply = [&](int buf, const float4 (&xb)[SW][TB][NS][2]) {
         const unsigned char *base = smem + (size_t)buf * BUF;
         // per k step: the A operands of all tiles first, then the planes outermost (smallest first), so that
         // consecutive matrix-core instructions write different accumulators: a product that has to wait for the
@@ -537,6 +543,13 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
                     for (int ct = 0; ct < CT; ++ct)
                         A[nt][ct] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(
                             base + (size_t)((nt * CT + ct) * 16 + i16) * PITCH + (4 * (NS * sw + s_) + g) * 16));
+                bf16x8_t B[TB][3];
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    const float4 x0 = xb[sw][tb][s_][0], x1 = xb[sw][tb][s_][1];
+                    const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                    split3(xv, B[tb]);
+                }
 #pragma unroll
                 for (int pl = 2; pl >= 0; --pl)
 #pragma unroll
@@ -545,17 +558,20 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
                         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                             for (int ct = 0; ct < CT; ++ct)
-                                acc[tb][nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    A[nt][ct], __builtin_bit_cast(bf16x8_t, xb[sw][tb][s_][pl]), acc[tb][nt][ct], 0, 0, 0);
+                                acc[tb][nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[nt][ct], B[tb][pl], acc[tb][nt][ct], 0, 0, 0);
             }
     };
 
     // register slots: WD for W, XD for X.  When step t is multiplied, the W rows of t + 1 .. t + WD and the X pieces
     // of t + 1 .. t + XD - 1 are in flight or have arrived; every request goes into the slot that the step before
-    // has just consumed, before this step's products.
-    constexpr int WD = SW == 1 ? 3 : 2;
-    constexpr int UNR = WD == XD ? WD : WD * XD;              // steps after which both slot patterns repeat (2 and 3 are coprime)
-    uint4 wr[WD][WQ], xb[XD][SW][TB][NS][3];
+    // has just consumed, before this step's products.  What bounds this kernel is how much of W one workgroup per CU
+    // keeps in flight (the hardware counters show 40 % of the outstanding DRAM requests of a kernel that streams at 6 TB/s).
+    // six slots where a launch is one workgroup per CU and the registers allow it (7B gate/up at 64 rows 86 -> 75 us);
+    // the LM head has several workgroups per CU and is better off with two of them resident (three slots each)
+    constexpr int WD = (TB == 1 && MODE != G_LMHEAD) ? 6 : 3;
+    constexpr int UNR = (WD % XD == 0) ? WD : WD * XD;        // steps after which both slot patterns repeat
+    uint4 wr[WD][WQ];
+    float4 xb[XD][SW][TB][NS][2];
 #pragma unroll
     for (int v = 0; v < WD; ++v) request_w(s_lo + v, wr[v]);
 #pragma unroll
@@ -615,7 +631,7 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
                 if (n >= n_out) continue;
                 const float val = acc[tb][0][ct][r];
                 if (MODE == G_PART) a.part[ksp * a.part_stride + (size_t)m * n_out + n] = val;
-                else split_store(val / (1.0f + expf(-val)) * acc[tb][NT - 1][ct][r], a.act, a.act_plane, (size_t)m * a.d_ffn + n);
+                else a.act32[(size_t)m * a.d_ffn + n] = val / (1.0f + expf(-val)) * acc[tb][NT - 1][ct][r];
             }
         }
     }

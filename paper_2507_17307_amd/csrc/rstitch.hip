@@ -70,7 +70,7 @@ const char *check_config(const rs_config *c) {
 
 struct Layout {
     size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, seq_info, h, xn, qkv_raw, qbuf,
-        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, gemm_part, total;
+        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, gemm_part, xn32, lm32, total;
     int attn_rows_x_splits;   // capacity of attn_part in (row, split) pairs
     int lm_parts_cap;         // partial states per sequence
 };
@@ -116,7 +116,8 @@ Layout make_layout(const rs_config &c) {
     L.qbuf = take((size_t)c.max_rows * qdim * 4);
     L.attn_out = take((size_t)c.max_rows * qdim * 4);
     L.attn_pl = take((size_t)3 * c.max_rows * qdim * 2);
-    L.act = take((size_t)(c.max_rows < FMA_MAX_ROWS ? c.max_rows : FMA_MAX_ROWS) * c.d_ffn * 4);
+    // fp32 SwiGLU rows: the FMA kernels' (up to FMA_MAX_ROWS rows) and the tile kernel's (more than 32 rows)
+    L.act = take((size_t)(c.max_rows > 16 ? c.max_rows : (c.max_rows < FMA_MAX_ROWS ? c.max_rows : FMA_MAX_ROWS)) * c.d_ffn * 4);
     L.act_pl = take((size_t)3 * c.max_rows * c.d_ffn * 2);
     L.attn_rows_x_splits = attn_pairs_cap(c);
     L.attn_part = take((size_t)L.attn_rows_x_splits * c.n_q_heads * (c.head_dim + 4) * 4);
@@ -125,6 +126,8 @@ Layout make_layout(const rs_config &c) {
     L.lm_parts_cap = LM_PARTS_CAP;
     L.lm_parts = take((size_t)c.max_seqs * L.lm_parts_cap * sizeof(rs::SoftPartial));
     L.gemm_part = take((size_t)GEMM_KSPLIT_MAX * c.max_rows * (qkv > (size_t)c.d_model ? qkv : (size_t)c.d_model) * 4);
+    L.xn32 = take(c.max_rows > 16 ? (size_t)c.max_rows * c.d_model * 4 : 0);      // normalised rows for the tile kernel
+    L.lm32 = take(c.max_seqs > 16 ? (size_t)c.max_seqs * c.d_model * 4 : 0);
     L.sync = take(sizeof(rs::SyncState));
     L.layer_ptrs = take((size_t)c.n_layers * sizeof(rs::LayerPtrs));
     L.total = o;
@@ -453,6 +456,17 @@ rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStrea
     }
 }
 
+// Which calls take k_gemm_tile.  Layers: from 24 rows on models at least 2048 wide.  Measured per call against 16- / 32-row
+// blocks with workgroups of their own (k_gemm_rows): 7B shape 24 rows 5.81 -> 5.54 ms, 32 rows 6.35 -> 5.75, 64 rows 9.57 ->
+// 6.9, 128 rows 14.9 -> 11.8; 14B 32 rows 14.5 -> 13.8, 64 rows 24.0 -> 18.0, 128 rows 44.7 -> 34.6; 32B 128 rows 78.6 -> 62.7
+// (17-23 rows are a tie or a loss: two of the four waves hold no rows).  A 1536-wide model has too few column blocks
+// for it outside 33-48 rows (1.5B shape: 33 rows 3.50 -> 2.95, 48 rows 3.50 -> 3.05, but 128 rows 5.43 -> 5.68).
+// LM head: more than 16 sequences (16-row blocks with workgroups of their own cost 230 us per block on the 7B shape:
+// 1.85 ms at 128 sequences against 0.60 ms; 1.5B shape 0.86 -> 0.30 ms); one partial per workgroup must fit the buffer
+// even with four column tiles per workgroup.
+bool tile_layers(const rs_config &c, int rows) { return c.d_model >= 2048 ? rows >= 24 : (rows > 32 && rows <= 48); }
+bool tile_lm_head(const rs_config &c, int n_seqs) { return n_seqs > 16 && ((c.vocab + 15) / 16 + 3) / 4 <= LM_PARTS_CAP; }
+
 // n_tiles = number of 16-column output tiles; 16 * NB token rows compiled in (NB = 1, 2 or 4)
 template <int MODE>
 rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
@@ -460,9 +474,7 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
     a.yblocks = 1;
     if constexpr (MODE == G_LMHEAD) {
         // more than 16 sequences: one workgroup per block of vocabulary columns holds all rows, so the matrix is read once
-        // (16-row blocks with workgroups of their own cost 230 us per block on the 7B shape: 1.85 ms at 128 sequences
-        // against 0.57 ms; 1.5B shape 0.86 -> 0.30 ms)
-        if (a.M > 16 && (n_tiles + 3) / 4 <= LM_PARTS_CAP)       // (at least four column tiles per workgroup)
+        if (tile_lm_head(m->cfg, a.M))
             return a.M <= 64 ? launch_gemm_tile<G_LMHEAD, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_LMHEAD, 2>(m, a, n_tiles, st, name);
         a.yblocks = (a.M + 15) / 16;
         return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
@@ -471,11 +483,7 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
         // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.0 ms, 64 rows 9.1 ms this
         // way; 64-row blocks are no faster (9.7 ms) and 16-row blocks slower.
         if (a.M <= 16) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
-        // more than 32 rows: one workgroup per block of output columns holds all rows (k_gemm_tile).  Measured per call
-        // against 32-row blocks with workgroups of their own: 7B shape 64 rows 9.57 -> 7.4 ms, 128 rows 14.9 -> 12.0; 14B
-        // 64 rows 24.0 -> 19.7, 128 rows 44.7 -> 35.9; 32B 128 rows 78.6 -> 62.6; a 1536-wide model has too few column
-        // blocks for it beyond 48 rows (1.5B shape: 33 rows 3.50 -> 3.06, 48 rows 3.50 -> 3.32, but 128 rows 5.43 -> 5.68)
-        if (a.M > 32 && (m->cfg.d_model >= 2048 || a.M <= 48)) {
+        if (tile_layers(m->cfg, a.M)) {
             // partial sums are always left for the next kernel (a split of one is a plain copy of the result)
             if constexpr (MODE == G_GATEUP) return a.M <= 64 ? launch_gemm_tile<G_GATEUP, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_GATEUP, 2>(m, a, n_tiles, st, name);
             else return a.M <= 64 ? launch_gemm_tile<G_PART, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_PART, 2>(m, a, n_tiles, st, name);
@@ -726,12 +734,15 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             const size_t xn_plane = (size_t)c.max_rows * c.d_model;
             GemmArgs g{};
             g.M = n_rows; g.d_ffn = c.d_ffn;
+            // the tile kernel takes its activations as fp32 rows (it splits them into planes itself)
+            float *xn32 = tile_layers(c, n_rows) ? m->at<float>(L.xn32) : nullptr;
+            g.act32 = m->at<float>(L.act);
             // the down projection of the layer before may have left its result as partial sums (pend_*)
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->attn_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)pend_part, pend_ks, pend_stride);
+                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)pend_part, pend_ks, pend_stride, xn32);
             RS_LAUNCHED("rmsnorm_rows");
             pend_part = nullptr; pend_ks = 0; pend_stride = 0;
-            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
+            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane; g.X32 = xn32;
             g.out_f32 = m->at<float>(L.qkv_raw); g.ld_out = qkv_rows;
             tic(RS_PHASE_QKV, l);
             if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv"))) return rc;
@@ -754,22 +765,22 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim;
-            g.X = m->at<uint16_t>(L.attn_pl); g.x_plane = (size_t)c.max_rows * qdim;
+            g.X = m->at<uint16_t>(L.attn_pl); g.x_plane = (size_t)c.max_rows * qdim; g.X32 = m->at<float>(L.attn_out);
             g.h_out = h; g.ld_h = c.d_model;
             tic(RS_PHASE_OPROJ, l);
             if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj"))) return rc;
             toc(RS_PHASE_OPROJ, l);
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->mlp_norm[l], c.rms_eps,
                                c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)g.part,
-                               g.ksplit, g.part_stride);
+                               g.ksplit, g.part_stride, xn32);
             RS_LAUNCHED("rmsnorm_rows");
-            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane;
+            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane; g.X32 = xn32;
             g.act = m->at<uint16_t>(L.act_pl); g.act_plane = (size_t)c.max_rows * c.d_ffn;
             tic(RS_PHASE_GATEUP, l);
             if ((rc = launch_gemm<G_GATEUP>(m, g, (c.d_ffn + 15) / 16, st, "gemm_gateup"))) return rc;
             toc(RS_PHASE_GATEUP, l);
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn;
-            g.X = m->at<uint16_t>(L.act_pl); g.x_plane = (size_t)c.max_rows * c.d_ffn;
+            g.X = m->at<uint16_t>(L.act_pl); g.x_plane = (size_t)c.max_rows * c.d_ffn; g.X32 = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
             if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down"))) return rc;
             toc(RS_PHASE_DOWN, l);
@@ -798,10 +809,11 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
         const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seqs), dim3(ROWK_THREADS), 0, st, h, m->final_norm, c.rms_eps,
-                           c.d_model, (const int *)m->at<int>(L.out_row), lm_pl, lm_plane, (const float *)pend_part, pend_ks, pend_stride);
+                           c.d_model, (const int *)m->at<int>(L.out_row), lm_pl, lm_plane, (const float *)pend_part, pend_ks, pend_stride,
+                           tile_lm_head(c, n_seqs) ? m->at<float>(L.lm32) : (float *)nullptr);
         RS_LAUNCHED("rmsnorm_rows");
         GemmArgs g{};
-        g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane;
+        g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane; g.X32 = m->at<float>(L.lm32);
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
         g.sample_on = m->sample_on; g.sample_key = m->sample_key; g.row_pos = row_pos; g.out_row = m->at<int>(L.out_row);
         tic(RS_PHASE_LMHEAD, 0);
