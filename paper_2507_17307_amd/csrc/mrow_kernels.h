@@ -567,8 +567,9 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     // has just consumed, before this step's products.  What bounds this kernel is how much of W one workgroup per CU
     // keeps in flight (the hardware counters show 40 % of the outstanding DRAM requests of a kernel that streams at 6 TB/s).
     // six slots where a launch is one workgroup per CU and the registers allow it (7B gate/up at 64 rows 86 -> 75 us);
-    // the LM head has several workgroups per CU and is better off with two of them resident (three slots each)
-    constexpr int WD = (TB == 1 && MODE != G_LMHEAD) ? 6 : 3;
+    // the LM head has several workgroups per CU and is better off with two of them resident (three slots each); with 32
+    // rows per wave four slots fit for the modes without the second (up) set of accumulators (7B down at 128 rows 91 -> 85 us)
+    constexpr int WD = (TB == 1 && MODE != G_LMHEAD) ? 6 : ((TB == 2 && MODE == G_PART) ? 4 : 3);
     constexpr int UNR = (WD % XD == 0) ? WD : WD * XD;        // steps after which both slot patterns repeat
     uint4 wr[WD][WQ];
     float4 xb[XD][SW][TB][NS][2];
