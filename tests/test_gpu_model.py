@@ -163,6 +163,29 @@ def test_calls_of_24_to_128_rows_on_a_2048_wide_shape_match_the_oracle(name, spa
             assert err <= 2.0 ** -7 * float(w_rows.abs().max()) + 1e-6, f"{name}: {what} rows of sequence {i} differ by {err}"
 
 
+def test_many_sequences_with_a_vocabulary_that_is_not_a_multiple_of_the_tile_width():
+    """40 sequences in one decode step on a model with 1003 vocabulary entries: the last block of vocabulary columns of
+    the LM head is ragged (62 full tiles of 16 and one of 11), and so is the last group of column tiles."""
+    import paper_2507_17307_amd as P
+    from workloads.shapes import ModelShape
+    shape = ModelShape("ragged_vocab", 2, 256, 4, 2, 64, 512, 1003, tied_lm_head=True)
+    w = W.make_weights(shape, 17, 0)
+    n = 40
+    gpu = P.Model(w.to("cuda"), max_ctx=16, max_seqs=64, max_rows=64)
+    ref = decoder.OracleModel(w, 16, n_slots=64)
+    slots = [(3 * i + 1) % 64 for i in range(n)]
+    toks = W.rng.randint(17, 5, 0, 2 * n, shape.vocab).tolist()
+    for i in range(n):
+        ref.forward([toks[2 * i]], 0, slot=slots[i])
+        gpu.forward_span([toks[2 * i]], 0, 0.5, P.RS_SLM, slot=slots[i])
+    scales = [1.0 + i % 9 for i in range(n)]
+    got, lg = gpu.decode_step([toks[2 * i + 1] for i in range(n)], [1] * n, 0.5, P.RS_SLM, scales, slots, want_logits=True)
+    torch.cuda.synchronize()
+    for i in range(n):
+        want = ref.forward([toks[2 * i + 1]], 1, slot=slots[i], logit_scale=scales[i])["logits"]
+        check_invocation(got[i], lg[i], want, 0.5, router.SLM, where=f"sequence {i}")
+
+
 def test_batched_decode_over_large_caches_matches_per_sequence_oracle():
     """Three sequences, one token each, on a model whose caches (three slots of 2 KV heads x 2048 positions x
     128 channels) are large enough that the single-row attention kernel waits for each row's position before it
