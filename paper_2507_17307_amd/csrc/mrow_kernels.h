@@ -412,8 +412,9 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
 // ------------------------------------------------------------------------------------------------
 // k_gemm_tile: the same products for 33 .. 128 token rows, one workgroup per block of output columns.
 // A workgroup of four waves owns CT tiles of 16 output columns (gate/up: CT gate tiles and the CT matching
-// up tiles) and ALL token rows: wave w holds the rows 16 TB w .. 16 TB (w + 1) - 1 (TB = 1 or 2 blocks of
-// 16) against every column of the workgroup, so nothing has to be summed across waves and W is read from
+// up tiles) and ALL token rows: wave w of NW (four up to 64 rows, eight up to 128) holds the rows 16 TB w ..
+// 16 TB (w + 1) - 1 (TB = 1 block of 16 in every launch; two blocks per wave on four waves measured slower: 7B gate/up at
+// 128 rows 142 us against 110) against every column of the workgroup, so nothing has to be summed across waves and W is read from
 // HBM once per call, whatever the row count.  Per 64-element k window the four waves fetch the window's W
 // rows together (whole 128-byte row pieces, into registers, up to six windows ahead), park them in one of two
 // LDS buffers and every wave reads all of them back in A-operand layout; its X pieces (fp32 rows, split
@@ -444,8 +445,8 @@ __host__ __device__ constexpr size_t gemm_tile_lds_bytes() {
 // (lgkmcnt(0); expcnt and vmcnt are left alone), then the barrier; the compiler moves no memory access across it
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int MODE, int TB, int CT>
-__global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
+template <int MODE, int TB, int CT, int NW = 4, int CS = 1>
+__global__ void __launch_bounds__(NW * 64) k_gemm_tile(GemmArgs a) {
     static_assert(MODE == G_GATEUP || MODE == G_PART || MODE == G_LMHEAD, "gate/up, raw partial sums or the LM head");
     constexpr int NT = (MODE == G_GATEUP) ? 2 : 1;
     constexpr int NS = GEMM_KW / 32;
@@ -453,13 +454,17 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     constexpr int KSTEP = GEMM_KW * SW;                       // k elements per step: K must be a multiple
     constexpr int PITCH = 128 * SW + 16;                      // bytes per parked row (padded against LDS bank conflicts)
     constexpr int WROWS = NT * CT * 16;                       // W rows of a step
-    constexpr int RPR = 32 / SW;                              // rows per round of 256 16-byte loads
+    constexpr int RPR = 8 * NW / SW;                          // rows per round of 16-byte loads of the whole workgroup
     constexpr int WQ = (WROWS + RPR - 1) / RPR;               // loads per thread and step
     constexpr size_t BUF = (size_t)WROWS * PITCH;
     constexpr int XD = TB == 1 ? 3 : 2;                       // register slots of X (each holds a step's pieces)
+    constexpr int RB = NW / CS;                               // waves that differ in their rows; CS waves share a row block and
+    constexpr int CTH = (CT + CS - 1) / CS;                   // split the workgroup's column tiles, CTH each (the last may get fewer)
+    static_assert(NW % CS == 0, "whole column splits");
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i16 = lane & 15, g = lane >> 4;
+    const int rb = wave % RB, ct0 = (wave / RB) * CTH;          // this wave's row block and first column tile
     const int lrow = tid / (8 * SW), lchunk = tid % (8 * SW); // W load role: row RPR q + lrow of the step, bytes 16 lchunk ..
     const int K = a.K;
     const int n_out = (MODE == G_GATEUP) ? a.d_ffn : a.N;
@@ -489,16 +494,16 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     const float *xp[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
-        const int m = (wave * TB + tb) * 16 + i16;
+        const int m = (rb * TB + tb) * 16 + i16;
         xp[tb] = a.X32 + (size_t)(m < a.M ? m : 0) * K + g * 8;
     }
-    f32x4_t acc[TB][NT][CT];
+    f32x4_t acc[TB][NT][CTH];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) acc[tb][nt][ct] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            for (int ct = 0; ct < CTH; ++ct) acc[tb][nt][ct] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
     // a step past the last is replaced by the last (fetched again, never used): requests are unconditional
     auto request_w = [&](int st, uint4 (&wr)[WQ]) {
@@ -536,13 +541,13 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
         for (int sw = 0; sw < SW; ++sw)
 #pragma unroll
             for (int s_ = 0; s_ < NS; ++s_) {
-                bf16x8_t A[NT][CT];
+                bf16x8_t A[NT][CTH];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int ct = 0; ct < CT; ++ct)
+                    for (int ct = 0; ct < CTH; ++ct)       // (a tile past the workgroup's last repeats it; its products are dropped)
                         A[nt][ct] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(
-                            base + (size_t)((nt * CT + ct) * 16 + i16) * PITCH + (4 * (NS * sw + s_) + g) * 16));
+                            base + (size_t)((nt * CT + min(ct0 + ct, CT - 1)) * 16 + i16) * PITCH + (4 * (NS * sw + s_) + g) * 16));
                 bf16x8_t B[TB][3];
 #pragma unroll
                 for (int tb = 0; tb < TB; ++tb) {
@@ -557,7 +562,7 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                            for (int ct = 0; ct < CT; ++ct)
+                            for (int ct = 0; ct < CTH; ++ct)
                                 acc[tb][nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[nt][ct], B[tb][pl], acc[tb][nt][ct], 0, 0, 0);
             }
     };
@@ -570,6 +575,7 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     // the LM head has several workgroups per CU and is better off with two of them resident (three slots each); with 32
     // rows per wave four slots fit for the modes without the second (up) set of accumulators (7B down at 128 rows 91 -> 85 us)
     constexpr int WD = (TB == 1 && MODE != G_LMHEAD) ? 6 : ((TB == 2 && MODE == G_PART) ? 4 : 3);
+    static_assert(NW == 4 || (NW == 8 && TB == 1), "four waves, or eight with one block of 16 rows each");
     constexpr int UNR = (WD % XD == 0) ? WD : WD * XD;        // steps after which both slot patterns repeat
     uint4 wr[WD][WQ];
     float4 xb[XD][SW][TB][NS][2];
@@ -594,7 +600,7 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
     // epilogue: this lane holds output columns n0 + 16 ct + 4 g + r of token 16 (wave TB + tb) + i16
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
-        const int m = (wave * TB + tb) * 16 + i16;
+        const int m = (rb * TB + tb) * 16 + i16;
         if (MODE == G_LMHEAD) {
             // the row's softmax state over this workgroup's columns: every lane pushes its logits, the four lanes of a
             // token (g = 0..3) merge, one partial per (row, workgroup).  Uniform control flow: the merge shuffles
@@ -604,11 +610,11 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
             unsigned long long noise_base = 0;
             if (a.sample_on && ok) noise_base = (unsigned long long)(a.row_pos[a.out_row[m]] + 1) * (unsigned long long)a.N;
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
+            for (int ct = 0; ct < CTH; ++ct)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int n = (grp * CT + ct) * 16 + 4 * g + r;
-                    if (!ok || n >= n_out) continue;
+                    const int n = (grp * CT + ct0 + ct) * 16 + 4 * g + r;
+                    if (!ok || ct0 + ct >= CT || n >= n_out) continue;
                     const float lg = acc[tb][0][ct][r] * lm_scale;
                     st.push(lg, n);
                     if (a.sample_on) st.push_noisy(lg, n, a.sample_key, noise_base);
@@ -618,14 +624,14 @@ __global__ void __launch_bounds__(256) k_gemm_tile(GemmArgs a) {
                 SoftState b = shfl_xor_state(st, o);
                 if ((lane & o) == 0) st.merge(b); else { b.merge(st); st = b; }
             }
-            if (g == 0 && ok) a.parts[(size_t)m * a.n_parts + grp] = to_partial(st);
+            if (g == 0 && ok) a.parts[(size_t)m * a.n_parts + grp * CS + wave / RB] = to_partial(st);
             continue;
         }
         if (m >= a.M) continue;
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const int tile = grp * CT + ct;
-            if (tile >= n_tiles) continue;
+        for (int ct = 0; ct < CTH; ++ct) {
+            const int tile = grp * CT + ct0 + ct;
+            if (ct0 + ct >= CT || tile >= n_tiles) continue;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int n = tile * 16 + 4 * g + r;

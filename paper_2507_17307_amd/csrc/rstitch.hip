@@ -391,19 +391,11 @@ rs_status launch_gemm_nb(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_
 // sums, the split of K are picked so that the workgroups come as close as possible to a whole number of rounds of the
 // machine with one workgroup per CU (each workgroup streams its share of W at the rate a CU can draw, so a round that
 // fills a fraction of the CUs costs a whole round); ties go to the larger CT (less X traffic) and the smaller split.
-template <int MODE, int TB, int CT>
+template <int MODE, int NW, int CS, int CT>
 rs_status launch_gemm_tile_ct(GemmArgs &a, int blocks, hipStream_t st, const char *name) {
-    constexpr size_t lds = gemm_tile_lds_bytes<MODE, TB, CT>();
-    static_assert(lds <= 128 * 1024, "one workgroup per CU with room to spare");
-    if (lds > 64 * 1024) {
-        static std::atomic<bool> raised{false};           // per instantiation; setting the attribute twice is harmless
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_gemm_tile<MODE, TB, CT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return fail(RS_EHIP, "raising the LDS limit of %s: %s", name, hipGetErrorString(e));
-            raised = true;
-        }
-    }
-    hipLaunchKernelGGL((k_gemm_tile<MODE, TB, CT>), dim3(blocks), dim3(256), lds, st, a);
+    constexpr size_t lds = gemm_tile_lds_bytes<MODE, 1, CT>();
+    static_assert(lds <= 64 * 1024, "fits the default LDS limit");
+    hipLaunchKernelGGL((k_gemm_tile<MODE, 1, CT, NW, CS>), dim3(blocks), dim3(NW * 64), lds, st, a);
     RS_LAUNCHED(name);
     return RS_OK;
 }
@@ -427,7 +419,8 @@ TilePlan plan_gemm_tile(bool gateup, bool split, int n_tiles, int n_win, int n_c
     return best;
 }
 
-template <int MODE, int TB>
+// NW waves: NW / CS blocks of 16 rows, CS waves per block that split the workgroup's column tiles
+template <int MODE, int NW, int CS>
 rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     const TilePlan p = plan_gemm_tile(MODE == G_GATEUP, MODE == G_PART, n_tiles, a.K / GEMM_KW, m->n_cu);
     const int groups = (n_tiles + p.ct - 1) / p.ct;
@@ -437,34 +430,43 @@ rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStrea
         a.part_stride = (size_t)m->cfg.max_rows * (size_t)a.N;
     }
     const int blocks = groups * p.ks;
-    if constexpr (MODE == G_LMHEAD) a.n_parts = groups;             // one partial per row and workgroup
+    if constexpr (MODE == G_LMHEAD) a.n_parts = groups * CS;        // one partial per row, workgroup and column split
     if constexpr (MODE == G_GATEUP) {
         switch (p.ct) {
-            case 5: return launch_gemm_tile_ct<MODE, TB, 5>(a, blocks, st, name);
-            case 4: return launch_gemm_tile_ct<MODE, TB, 4>(a, blocks, st, name);
-            case 3: return launch_gemm_tile_ct<MODE, TB, 3>(a, blocks, st, name);
-            default: return launch_gemm_tile_ct<MODE, TB, 2>(a, blocks, st, name);
+            case 5: return launch_gemm_tile_ct<MODE, NW, CS, 5>(a, blocks, st, name);
+            case 4: return launch_gemm_tile_ct<MODE, NW, CS, 4>(a, blocks, st, name);
+            case 3: return launch_gemm_tile_ct<MODE, NW, CS, 3>(a, blocks, st, name);
+            default: return launch_gemm_tile_ct<MODE, NW, CS, 2>(a, blocks, st, name);
         }
     } else {
         switch (p.ct) {
-            case 10: return launch_gemm_tile_ct<MODE, TB, 10>(a, blocks, st, name);
-            case 8: return launch_gemm_tile_ct<MODE, TB, 8>(a, blocks, st, name);
-            case 7: return launch_gemm_tile_ct<MODE, TB, 7>(a, blocks, st, name);
-            case 6: return launch_gemm_tile_ct<MODE, TB, 6>(a, blocks, st, name);
-            default: return launch_gemm_tile_ct<MODE, TB, 4>(a, blocks, st, name);
+            case 10: return launch_gemm_tile_ct<MODE, NW, CS, 10>(a, blocks, st, name);
+            case 8: return launch_gemm_tile_ct<MODE, NW, CS, 8>(a, blocks, st, name);
+            case 7: return launch_gemm_tile_ct<MODE, NW, CS, 7>(a, blocks, st, name);
+            case 6: return launch_gemm_tile_ct<MODE, NW, CS, 6>(a, blocks, st, name);
+            default: return launch_gemm_tile_ct<MODE, NW, CS, 4>(a, blocks, st, name);
         }
     }
 }
 
-// Which calls take k_gemm_tile.  Layers: from 24 rows on models at least 2048 wide.  Measured per call against 16- / 32-row
-// blocks with workgroups of their own (k_gemm_rows): 7B shape 24 rows 5.81 -> 5.54 ms, 32 rows 6.35 -> 5.75, 64 rows 9.57 ->
-// 6.9, 128 rows 14.9 -> 11.8; 14B 32 rows 14.5 -> 13.8, 64 rows 24.0 -> 18.0, 128 rows 44.7 -> 34.6; 32B 128 rows 78.6 -> 62.7
-// (17-23 rows are a tie or a loss: two of the four waves hold no rows).  A 1536-wide model has too few column blocks
-// for it outside 33-48 rows (1.5B shape: 33 rows 3.50 -> 2.95, 48 rows 3.50 -> 3.05, but 128 rows 5.43 -> 5.68).
+// wave arrangement by row count: four waves of 16 rows up to 64 rows, eight up to 128.  Eight waves that share row
+// blocks and split the column tiles (k_gemm_tile's CS > 1) measured slower at 24-64 rows (7B shape, 64 rows: 7.8 ms
+// per call against 7.0; every wave of a row block fetches that block's X pieces again)
+template <int MODE>
+rs_status launch_gemm_tile_rows(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
+    if (a.M > 64) return launch_gemm_tile<MODE, 8, 1>(m, a, n_tiles, st, name);
+    return launch_gemm_tile<MODE, 4, 1>(m, a, n_tiles, st, name);
+}
+
+// Which calls take k_gemm_tile.  Layers: from 24 rows on models at least 2048 wide, from 33 rows on narrower ones.
+// Measured per call against 16- / 32-row blocks with workgroups of their own (k_gemm_rows): 7B shape 24 rows 5.81 -> 5.54
+// ms, 32 rows 6.35 -> 5.75, 64 rows 9.57 -> 6.9, 128 rows 14.9 -> 10.1; 14B 32 rows 14.5 -> 13.8, 64 rows 24.0 -> 18.0, 128
+// rows 44.7 -> 31.3; 32B 128 rows 78.6 -> 55.3; 1.5B shape 33 rows 3.50 -> 2.95, 64 rows 3.68 -> 3.32, 128 rows 5.44 -> 4.82
+// (17-23 rows, 17-32 on the 1.5B shape, are a tie or a loss: two of the four waves hold no rows).
 // LM head: more than 16 sequences (16-row blocks with workgroups of their own cost 230 us per block on the 7B shape:
-// 1.85 ms at 128 sequences against 0.60 ms; 1.5B shape 0.86 -> 0.30 ms); one partial per workgroup must fit the buffer
+// 1.85 ms at 128 sequences against 0.47 ms; 1.5B shape 0.86 -> 0.24 ms); one partial per workgroup must fit the buffer
 // even with four column tiles per workgroup.
-bool tile_layers(const rs_config &c, int rows) { return c.d_model >= 2048 ? rows >= 24 : (rows > 32 && rows <= 48); }
+bool tile_layers(const rs_config &c, int rows) { return rows >= (c.d_model >= 2048 ? 24 : 33); }
 bool tile_lm_head(const rs_config &c, int n_seqs) { return n_seqs > 16 && ((c.vocab + 15) / 16 + 3) / 4 <= LM_PARTS_CAP; }
 
 // n_tiles = number of 16-column output tiles; 16 * NB token rows compiled in (NB = 1, 2 or 4)
@@ -475,7 +477,7 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
     if constexpr (MODE == G_LMHEAD) {
         // more than 16 sequences: one workgroup per block of vocabulary columns holds all rows, so the matrix is read once
         if (tile_lm_head(m->cfg, a.M))
-            return a.M <= 64 ? launch_gemm_tile<G_LMHEAD, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_LMHEAD, 2>(m, a, n_tiles, st, name);
+            return launch_gemm_tile_rows<G_LMHEAD>(m, a, n_tiles, st, name);
         a.yblocks = (a.M + 15) / 16;
         return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
     } else {
@@ -485,8 +487,8 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
         if (a.M <= 16) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
         if (tile_layers(m->cfg, a.M)) {
             // partial sums are always left for the next kernel (a split of one is a plain copy of the result)
-            if constexpr (MODE == G_GATEUP) return a.M <= 64 ? launch_gemm_tile<G_GATEUP, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_GATEUP, 2>(m, a, n_tiles, st, name);
-            else return a.M <= 64 ? launch_gemm_tile<G_PART, 1>(m, a, n_tiles, st, name) : launch_gemm_tile<G_PART, 2>(m, a, n_tiles, st, name);
+            if constexpr (MODE == G_GATEUP) return launch_gemm_tile_rows<G_GATEUP>(m, a, n_tiles, st, name);
+            else return launch_gemm_tile_rows<G_PART>(m, a, n_tiles, st, name);
         }
         a.yblocks = (a.M + 31) / 32;
         return launch_gemm_nb<MODE, 2>(m, a, n_tiles, st, name);
