@@ -163,6 +163,27 @@ def test_calls_of_24_to_128_rows_on_a_2048_wide_shape_match_the_oracle(name, spa
             assert err <= 2.0 ** -7 * float(w_rows.abs().max()) + 1e-6, f"{name}: {what} rows of sequence {i} differ by {err}"
 
 
+@pytest.mark.parametrize("rows", [40, 100])
+def test_long_spans_on_the_narrowest_shape(rows):
+    """The tiny small-model shape (d_model 128: two 64-element k windows, fewer than the kernel keeps in flight; d_ffn 384)
+    with spans that take the all-rows-per-workgroup kernel: every request past the last window is a clamped duplicate."""
+    import paper_2507_17307_amd as P
+    shape = W.TINY_S
+    w = W.make_weights(shape, 23, 0)
+    gpu = P.Model(w.to("cuda"), max_ctx=128, max_seqs=1, max_rows=128)
+    ref = decoder.OracleModel(w, 128)
+    toks = W.rng.randint(23, 9, 0, rows + 12, shape.vocab).tolist()
+    ref.forward(toks[:11], 0)
+    gpu.forward_span(toks[:11], 0, 0.5, P.RS_SLM)
+    got, lg = gpu.catchup_prefill([toks[11:11 + rows]], [11], 0.6, P.RS_SLM, [3.0], [0], want_logits=True)
+    torch.cuda.synchronize()
+    want = ref.forward(toks[11:11 + rows], 11, logit_scale=3.0)["logits"]
+    check_invocation(got[0], lg[0], want, 0.6, router.SLM, where=f"{rows} rows")
+    kg = gpu.kv_view("k").float().cpu().double()[:, 0, :, 11:11 + rows]
+    kw = ref.k_cache[:, 0, :, 11:11 + rows]
+    assert float((kg - kw).abs().max()) <= 2.0 ** -7 * float(kw.abs().max()) + 1e-6
+
+
 def test_many_sequences_with_a_vocabulary_that_is_not_a_multiple_of_the_tile_width():
     """40 sequences in one decode step on a model with 1003 vocabulary entries: the last block of vocabulary columns of
     the LM head is ragged (62 full tiles of 16 and one of 11), and so is the last group of column tiles."""
