@@ -467,11 +467,17 @@ rs_status launch_gemm_tile_rows(const rs_model *m, GemmArgs &a, int n_tiles, hip
 // 1.85 ms at 128 sequences against 0.47 ms; 1.5B shape 0.86 -> 0.24 ms); one partial per workgroup must fit the buffer
 // even with four column tiles per workgroup.
 bool tile_layers(const rs_config &c, int rows) { return rows >= (c.d_model >= 2048 ? 24 : 33); }
+// ... and only the matrices whose workgroups fill at least 70 % of their rounds of the machine (the 1.5B shape's QKV and
+// O projection have 128 and 96 of them at best: 15.6 and 14.7 us per layer at 128 rows against 12.7 and 11.0 on k_gemm_rows)
+bool tile_fills(const rs_model *m, bool gateup, int n_out, int K) {
+    return plan_gemm_tile(gateup, !gateup, (n_out + 15) / 16, K / GEMM_KW, m->n_cu).eff >= 0.7;
+}
 bool tile_lm_head(const rs_config &c, int n_seqs) { return n_seqs > 16 && ((c.vocab + 15) / 16 + 3) / 4 <= LM_PARTS_CAP; }
 
 // n_tiles = number of 16-column output tiles; 16 * NB token rows compiled in (NB = 1, 2 or 4)
+// tile: the caller's choice of k_gemm_tile for this matrix (it has prepared the activations in that kernel's format)
 template <int MODE>
-rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
+rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name, bool tile = false) {
     if (a.K % GEMM_KW) return fail(RS_EINVAL, "internal: K = %d is not a multiple of %d", a.K, GEMM_KW);
     a.yblocks = 1;
     if constexpr (MODE == G_LMHEAD) {
@@ -485,7 +491,7 @@ rs_status launch_gemm(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t s
         // block with workgroups of its own.  Measured on the 7B shape: 32 rows 6.0 ms, 64 rows 9.1 ms this
         // way; 64-row blocks are no faster (9.7 ms) and 16-row blocks slower.
         if (a.M <= 16) return launch_gemm_nb<MODE, 1>(m, a, n_tiles, st, name);
-        if (tile_layers(m->cfg, a.M)) {
+        if (tile) {
             // partial sums are always left for the next kernel (a split of one is a plain copy of the result)
             if constexpr (MODE == G_GATEUP) return launch_gemm_tile_rows<G_GATEUP>(m, a, n_tiles, st, name);
             else return launch_gemm_tile_rows<G_PART>(m, a, n_tiles, st, name);
@@ -737,17 +743,21 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             GemmArgs g{};
             g.M = n_rows; g.d_ffn = c.d_ffn;
             // the tile kernel takes its activations as fp32 rows (it splits them into planes itself)
-            float *xn32 = tile_layers(c, n_rows) ? m->at<float>(L.xn32) : nullptr;
+            const bool t_all = tile_layers(c, n_rows);
+            const bool t_qkv = t_all && tile_fills(m, false, qkv_rows, c.d_model), t_o = t_all && tile_fills(m, false, c.d_model, qdim);
+            // gate/up hands its output to the down projection in one format: both or neither
+            const bool t_mlp = t_all && tile_fills(m, true, c.d_ffn, c.d_model) && tile_fills(m, false, c.d_model, c.d_ffn);
+            float *xn32 = m->at<float>(L.xn32);
             g.act32 = m->at<float>(L.act);
             // the down projection of the layer before may have left its result as partial sums (pend_*)
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->attn_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)pend_part, pend_ks, pend_stride, xn32);
+                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)pend_part, pend_ks, pend_stride, t_qkv ? xn32 : nullptr);
             RS_LAUNCHED("rmsnorm_rows");
             pend_part = nullptr; pend_ks = 0; pend_stride = 0;
             g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane; g.X32 = xn32;
             g.out_f32 = m->at<float>(L.qkv_raw); g.ld_out = qkv_rows;
             tic(RS_PHASE_QKV, l);
-            if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv"))) return rc;
+            if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv", t_qkv))) return rc;
             toc(RS_PHASE_QKV, l);
             RopeArgs ra{};
             ra.qkv = g.part ? g.part : m->at<float>(L.qkv_raw); ra.ksplit = g.ksplit; ra.part_stride = g.part_stride;
@@ -770,21 +780,21 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.X = m->at<uint16_t>(L.attn_pl); g.x_plane = (size_t)c.max_rows * qdim; g.X32 = m->at<float>(L.attn_out);
             g.h_out = h; g.ld_h = c.d_model;
             tic(RS_PHASE_OPROJ, l);
-            if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj"))) return rc;
+            if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj", t_o))) return rc;
             toc(RS_PHASE_OPROJ, l);
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->mlp_norm[l], c.rms_eps,
                                c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)g.part,
-                               g.ksplit, g.part_stride, xn32);
+                               g.ksplit, g.part_stride, t_mlp ? xn32 : nullptr);
             RS_LAUNCHED("rmsnorm_rows");
             g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane; g.X32 = xn32;
             g.act = m->at<uint16_t>(L.act_pl); g.act_plane = (size_t)c.max_rows * c.d_ffn;
             tic(RS_PHASE_GATEUP, l);
-            if ((rc = launch_gemm<G_GATEUP>(m, g, (c.d_ffn + 15) / 16, st, "gemm_gateup"))) return rc;
+            if ((rc = launch_gemm<G_GATEUP>(m, g, (c.d_ffn + 15) / 16, st, "gemm_gateup", t_mlp))) return rc;
             toc(RS_PHASE_GATEUP, l);
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn;
             g.X = m->at<uint16_t>(L.act_pl); g.x_plane = (size_t)c.max_rows * c.d_ffn; g.X32 = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
-            if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down"))) return rc;
+            if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down", t_mlp))) return rc;
             toc(RS_PHASE_DOWN, l);
             if (g.part) { pend_part = g.part; pend_ks = g.ksplit; pend_stride = g.part_stride; }
         }

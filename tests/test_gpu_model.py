@@ -126,11 +126,12 @@ TILE_CASES = [("one_span_24", [24]), ("two_spans_31", [11, 20]), ("one_span_33",
 def test_calls_of_24_to_128_rows_on_a_2048_wide_shape_match_the_oracle(name, spans):
     """Calls of 24 rows and more on a model at least 2048 wide take the kernel in which one workgroup holds all rows of
     the call against a block of output columns (one or two blocks of 16 rows per wave, K split over workgroups for
-    QKV / O-proj / down).  The shape has tile counts that leave ragged last column groups (352 gate/up tiles, 192 QKV
-    tiles, 128 model tiles) and 32 / 88 k windows."""
+    QKV / O-proj / down) for every matrix whose workgroups fill the machine: here QKV (192 tiles), gate/up (640 tiles in
+    groups of three: a ragged last group) and down (128 tiles, 160 k windows split over eight workgroups); the O projection
+    (128 tiles, 32 windows) stays on the 32-row-block kernel, so both activation formats are in play in one call."""
     import paper_2507_17307_amd as P
     from workloads.shapes import ModelShape
-    shape = ModelShape("wide_2layers", 2, 2048, 16, 4, 128, 5632, 8192, tied_lm_head=False)
+    shape = ModelShape("wide_2layers", 2, 2048, 16, 4, 128, 10240, 8192, tied_lm_head=False)
     w = W.make_weights(shape, 31, 1)
     n = len(spans)
     n_slots = next(k for k in (2, 32, 128) if k >= n)
