@@ -17,6 +17,7 @@ Prints ONE JSON line.  Extra objects:
                 8 TB/s HBM peak, plus the whole-step fraction of each model
   per_model     decode ms/token of each model alone and its roofline fraction
   stitched      invocation mix of the timed region and its roofline fraction
+  device_loop   Algorithm 1 as one kernel (rs_stitch_generate) on a few tokens beside the host-driven loop
   latency_fit   Eq. 5-6 of the paper re-fitted to this machine's timings
   cpu_baseline  the CPU oracle timed on this machine's cores on a bounded sample
 """
@@ -396,6 +397,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3_s15_m7")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency-fit", action="store_true")
+    ap.add_argument("--no-device-loop", action="store_true")
     ap.add_argument("--tau-steps", type=int, default=None, help="small-model-only tokens used to place tau")
     ap.add_argument("--seqs", type=int, default=None, help="run a two-model workload over this many sequences (1..128) with per-sequence routing, through the batched driver")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -589,6 +591,26 @@ def main() -> int:
         router[f"{tag}_lm_head_gbps"] = round(lm_bytes / (lm_ms * 1e-3) / 1e9, 1)
     router["paper_separate_entropy_us"] = 28.0
 
+    # ---- Algorithm 1 with the loop itself on the device (rs_stitch_generate: one kernel, nothing read by the host
+    # until the end) on a bounded number of tokens, beside the host-driven loop over the same tokens; both start
+    # with all but the last prompt token in both caches
+    device_loop = None
+    if not args.no_device_loop:
+        n_dl = min(48, args.steps)
+        pair.on_invocation = None
+        for mid in (SLM, LLM):
+            pair.prefill_prompt(mid, prompt, tau)
+        pair.generate(prompt, tau, 4, llm_prefilled=True, slm_prefilled=True)          # graphs of this start
+        t0 = time.perf_counter()
+        host_run = pair.generate(prompt, tau, n_dl, llm_prefilled=True, slm_prefilled=True)
+        host_s = time.perf_counter() - t0
+        dev_run = pair.generate_on_device(prompt, tau, n_dl, prompt_prefilled=True)
+        device_loop = {"tokens": n_dl, "status": dev_run.status, "invocations": len(dev_run.trace),
+                       "tokens_per_s": round(n_dl / (dev_run.loop_ms * 1e-3), 2),
+                       "ms_per_token": round(dev_run.loop_ms / n_dl, 4),
+                       "host_loop_tokens_per_s": round(n_dl / host_s, 2),
+                       "same_tokens_as_host_loop": dev_run.output == host_run.output}
+
     # ---- latency model of the paper (Eq. 5-6) re-fitted to this machine: GPU time of calls with N_inf token rows
     # on a cache of N_kv positions, each model; coefficients in ms beside the paper's A100 ones
     latency_fit = None
@@ -634,6 +656,7 @@ def main() -> int:
                      "roofline_ms_per_token": round(ideal_s / args.steps * 1e3, 4),
                      "roofline_frac": round(ideal_s / elapsed, 4)},
         "router": router,
+        "device_loop": device_loop,
         "latency_fit": latency_fit,
         "cpu_baseline": cpu,
     }

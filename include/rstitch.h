@@ -266,6 +266,69 @@ rs_status rs_route_plus(rs_model *model, const float *d_hidden, int32_t n_seqs,
                         const rs_router_weights *w, int32_t active,
                         rs_route_out *d_out, float *d_router_logits, void *stream);
 
+/* Algorithm 1 ("Inference procedure") with the loop itself on the device: one
+ * cooperative kernel runs invocation after invocation, applies the routing flags
+ * of Eq. 2 to a loop state in device memory (a rejected small-model token is
+ * dropped and the large model redoes the position; the large model hands back
+ * at or below tau) and appends the accepted tokens to d_seq.  The host reads
+ * nothing between invocations.  The active model's unseen suffix (Section "KV
+ * Cache management") is fed one token row at a time inside the kernel; a caller
+ * that wants a long prompt prefilled on the matrix cores does that first with
+ * rs_catchup_prefill and passes how many rows each model already holds.
+ * Greedy decoding with the entropy rule only (no sampling, no R-Stitch+ router).
+ * On this machine a software barrier across all compute units costs more than a
+ * kernel boundary, so this call is SLOWER than a host loop over rs_decode_step /
+ * rs_catchup_prefill; it is here for callers that cannot put the host in the loop. */
+#define RS_STITCH_RUNNING     0  /* only seen while the kernel runs                        */
+#define RS_STITCH_DONE        1  /* n_new tokens accepted, or the eos token accepted       */
+#define RS_STITCH_TRACE_FULL  2  /* max_records invocations made before that               */
+#define RS_STITCH_FLAGGED     3  /* a record carried BADARG / NONFINITE (it is the last
+                                    record), or the loop state was inconsistent            */
+#define RS_STITCH_ABORTED     4  /* a bounded wait inside the kernel ran out               */
+
+typedef struct rs_stitch_record {    /* one invocation (40 bytes) */
+    int32_t model;       /* RS_SLM / RS_LLM                                               */
+    int32_t pos0;        /* position of the first token row it was fed                    */
+    int32_t n_rows;      /* rows fed: the suffix it had not seen                          */
+    int32_t reserved;
+    rs_route_out out;    /* record of its last row; RS_FLAG_ACCEPT says the token was kept */
+} rs_stitch_record;
+
+typedef struct rs_stitch_result {    /* 32 bytes */
+    int32_t status;      /* RS_STITCH_*                                                   */
+    int32_t n_tokens;    /* tokens in d_seq: prompt + accepted                            */
+    int32_t n_records;   /* invocations made = records written                            */
+    int32_t seen_slm;    /* rows of d_seq the small model's cache holds                   */
+    int32_t seen_llm;    /* same for the large model                                      */
+    int32_t active;      /* the model that would run next                                 */
+    int32_t n_target;    /* n_prompt + n_new                                              */
+    int32_t reserved;
+} rs_stitch_result;
+
+/*   slm, llm      two models on the same device with the same head_dim; both use
+ *                 KV slot seq_slot; neither may have sampling enabled
+ *   d_seq         DEVICE int32[n_prompt + n_new]: the prompt on entry, prompt +
+ *                 accepted tokens on return (read and written by the kernel)
+ *   n_prompt      >= 1;  n_new >= 1;  n_prompt + n_new - 1 <= max_ctx of both
+ *   seen_slm/llm  rows of the prompt already in each model's cache, 0 .. n_prompt - 1
+ *   d_logit_scale DEVICE fp32[n_prompt + n_new] or NULL (= 1): entry p scales
+ *                 the logits that predict position p
+ *   eos           token that ends the run when accepted, or -1
+ *   d_trace       DEVICE rs_stitch_record[max_records], 1 <= max_records <= 2^20;
+ *                 2 * n_new records always suffice
+ *   d_result      DEVICE rs_stitch_result, written when the kernel ends
+ * Asynchronous on `stream`; synchronise it before reading d_seq, d_trace, d_result.
+ * Calls on one pair must not overlap.
+ * Errors: RS_EINVAL (null pointer, counts out of range, different devices or
+ * head_dim), RS_ECAPACITY (the sequence does not fit a cache), RS_ENOTIMPL
+ * (sampling enabled, or the device cannot launch cooperative kernels), RS_EHIP. */
+rs_status rs_stitch_generate(rs_model *slm, rs_model *llm, int32_t seq_slot,
+                             int32_t *d_seq, int32_t n_prompt, int32_t n_new,
+                             int32_t seen_slm, int32_t seen_llm,
+                             const float *d_logit_scale, float tau, int32_t eos,
+                             rs_stitch_record *d_trace, int32_t max_records,
+                             rs_stitch_result *d_result, void *stream);
+
 /* rs_route for callers that cannot allocate device memory or hand over a
  * scratch buffer (code under HIP graph capture, tight serving loops, harnesses
  * that forbid allocation).  Same arguments, kernels and results as rs_route, but

@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     RsError, RsConfig, RouteOut, lib, library_path,
     rs_abi_version, rs_last_error, rs_workspace_bytes, rs_kv_bytes, rs_create_model, rs_destroy_model,
     rs_decode_step, rs_catchup_prefill, rs_route, rs_route_plus, RouterPlus, rs_route_static, rs_route_scratch_bytes, rs_set_phase_timer, rs_set_spin_limit, rs_set_sampling,
+    rs_stitch_generate, STITCH_RUNNING, STITCH_DONE, STITCH_TRACE_FULL, STITCH_FLAGGED, STITCH_ABORTED,
     Model,
 )

@@ -82,6 +82,8 @@ def _load() -> C.CDLL:
     lib.rs_route_plus.argtypes = [vp, vp, i32, C.POINTER(_RsRouterWeights), i32, vp, vp, vp]
     lib.rs_route_static.restype = i32
     lib.rs_route_static.argtypes = [vp, i32, i32, vp, f32, i32, vp, vp]
+    lib.rs_stitch_generate.restype = i32
+    lib.rs_stitch_generate.argtypes = [vp, vp, i32, vp, i32, i32, i32, i32, vp, f32, i32, vp, i32, vp, vp]
     lib.rs_set_spin_limit.restype = i32
     lib.rs_set_spin_limit.argtypes = [vp, C.c_uint32]
     lib.rs_set_phase_timer.restype = i32
@@ -191,6 +193,20 @@ def rs_route_plus(handle: Optional[int], d_hidden, n_seqs: int, router: RouterPl
     out = d_out if isinstance(d_out, int) else _ptr(d_out)
     _check(lib.rs_route_plus(handle, _ptr(d_hidden), n_seqs, C.byref(router.struct), active, out,
                              _ptr(d_router_logits), _stream(stream)))
+
+
+STITCH_RUNNING, STITCH_DONE, STITCH_TRACE_FULL, STITCH_FLAGGED, STITCH_ABORTED = range(5)
+STITCH_RECORD_INTS = 10     # rs_stitch_record: model, pos0, n_rows, reserved, then the 6 words of rs_route_out
+STITCH_RESULT_INTS = 8      # rs_stitch_result: status, n_tokens, n_records, seen_slm, seen_llm, active, n_target, reserved
+
+
+def rs_stitch_generate(slm: int, llm: int, seq_slot: int, d_seq, n_prompt: int, n_new: int, seen_slm: int,
+                       seen_llm: int, d_logit_scale, tau: float, eos: int, d_trace, max_records: int, d_result,
+                       stream=None) -> None:
+    """d_seq: int32 tensor [n_prompt + n_new]; d_trace: int32 tensor [max_records, 10]; d_result: int32 tensor [8]."""
+    _check(lib.rs_stitch_generate(slm, llm, seq_slot, _ptr(d_seq), n_prompt, n_new, seen_slm, seen_llm,
+                                  _ptr(d_logit_scale), tau, eos, _ptr(d_trace), max_records, _ptr(d_result),
+                                  _stream(stream)))
 
 
 def rs_set_sampling(handle: int, enabled: bool, key: int = 0) -> None:

@@ -128,7 +128,7 @@ Layout make_layout(const rs_config &c) {
     L.gemm_part = take((size_t)GEMM_KSPLIT_MAX * c.max_rows * (qkv > (size_t)c.d_model ? qkv : (size_t)c.d_model) * 4);
     L.xn32 = take(c.max_rows > 16 ? (size_t)c.max_rows * c.d_model * 4 : 0);      // normalised rows for the tile kernel
     L.lm32 = take(c.max_seqs > 16 ? (size_t)c.max_seqs * c.d_model * 4 : 0);
-    L.sync = take(sizeof(rs::SyncState));
+    L.sync = take(2 * sizeof(rs::SyncState));          // [0] single-kernel step, [1] device-resident loop
     L.layer_ptrs = take((size_t)c.n_layers * sizeof(rs::LayerPtrs));
     L.total = o;
     return L;
@@ -140,6 +140,7 @@ struct rs_model {
     rs_config cfg;
     Layout lay;
     int n_cu;
+    int device = 0;                               // ordinal the model was created on
     const uint16_t *embed, *lm_head, *final_norm;
     std::vector<const uint16_t *> attn_norm, w_qkv, w_o, mlp_norm, w_gate_up, w_down;
     uint16_t *kv_k, *kv_v;
@@ -166,7 +167,7 @@ struct rs_model {
     bool use_persistent = false;
     int persist_blocks = 0;
     size_t persist_lds = 0;
-    unsigned long long arrivals_expected = 0;     // barrier arrivals of all launches so far
+    unsigned long long barriers_done = 0;         // grid barriers of all single-kernel steps so far
     unsigned int spin_limit = 1u << 22;
 
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
@@ -509,6 +510,14 @@ const void *persistent_kernel(int hd) {
     }
 }
 
+const void *stitch_loop_kernel(int hd) {
+    switch (hd) {
+        case 32: return (const void *)k_stitch_loop<32>;
+        case 64: return (const void *)k_stitch_loop<64>;
+        default: return (const void *)k_stitch_loop<128>;
+    }
+}
+
 size_t persistent_lds(const rs_config &c) {
     size_t need = gemv_lds_bytes<1>(c.d_model);
     const size_t cand[] = {gemv_lds_bytes<1>(c.n_q_heads * c.head_dim), gemv_lds_bytes<1>(c.d_ffn),
@@ -526,13 +535,12 @@ int attn_splits(const rs_config &c, const Layout &L, int n_rows) {
     return n_splits < 1 ? 1 : n_splits;
 }
 
-// The whole single-row decode step as one cooperative kernel.
-rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_token, const int *d_pos, const float *d_scale,
-                             float tau, int active, rs_route_out *d_out, float *d_logits, hipStream_t st) {
+// Arguments of the single-kernel phases for one token row of model m.
+void fill_persist_args(rs_model *m, PersistArgs &p, const int *d_seq_slot, const int *d_token, const int *d_pos,
+                       const float *d_scale, float tau, int active, rs_route_out *d_out, float *d_logits) {
     const rs_config &c = m->cfg;
     const Layout &L = m->lay;
     const int hd = c.head_dim;
-    PersistArgs p{};
     p.prep.n_seqs = 1; p.prep.n_rows = 1; p.prep.d_model = c.d_model; p.prep.vocab = c.vocab;
     p.prep.max_ctx = c.max_ctx; p.prep.max_seqs = c.max_seqs;
     p.prep.seq_slot = d_seq_slot; p.prep.tokens = d_token; p.prep.span_off = nullptr; p.prep.pos0 = d_pos; p.prep.scale = d_scale;
@@ -566,13 +574,20 @@ rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_to
     p.n_splits = attn_splits(c, L, 1); aa.n_slices = p.n_splits;
     p.vocab = c.vocab; p.tau = tau; p.active = active;
     p.seq_bad = p.prep.seq_bad; p.out = d_out;
-    p.sync = m->at<SyncState>(L.sync); p.bar_base = m->arrivals_expected; p.spin_limit = m->spin_limit;
+    p.sync = m->at<SyncState>(L.sync); p.bar_base = m->barriers_done; p.spin_limit = m->spin_limit;
+}
 
+// The whole single-row decode step as one cooperative kernel.
+rs_status forward_persistent(rs_model *m, const int *d_seq_slot, const int *d_token, const int *d_pos, const float *d_scale,
+                             float tau, int active, rs_route_out *d_out, float *d_logits, hipStream_t st) {
+    const rs_config &c = m->cfg;
+    PersistArgs p{};
+    fill_persist_args(m, p, d_seq_slot, d_token, d_pos, d_scale, tau, active, d_out, d_logits);
     void *args[] = {&p};
-    hipError_t e = hipLaunchCooperativeKernel(persistent_kernel(hd), dim3(m->persist_blocks), dim3(256), args,
+    hipError_t e = hipLaunchCooperativeKernel(persistent_kernel(c.head_dim), dim3(m->persist_blocks), dim3(256), args,
                                               (unsigned int)m->persist_lds, st);
     if (e != hipSuccess) return fail(RS_EHIP, "cooperative launch of the decode step: %s", hipGetErrorString(e));
-    m->arrivals_expected += (unsigned long long)(6 * c.n_layers + 2) * (unsigned long long)m->persist_blocks;
+    m->barriers_done += (unsigned long long)(6 * c.n_layers + 2);
     return RS_OK;
 }
 
@@ -969,6 +984,7 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *w, void *kv_k,
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) { delete m; return fail(RS_EHIP, "device query: %s", hipGetErrorString(e)); }
     m->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    m->device = dev;
     m->plan = make_plan(*cfg, m->n_cu);
 
     // rotary table: angle(pos, i) = pos * theta^(-2 i / head_dim), evaluated in double
@@ -985,7 +1001,7 @@ rs_status rs_create_model(const rs_config *cfg, const rs_weights *w, void *kv_k,
     e = hipMemcpy(m->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(m->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(m->ws + L.attn_cnt, 0, (size_t)cfg->max_rows * cfg->n_kv_heads * 4);
-    if (e == hipSuccess) e = hipMemset(m->ws + L.sync, 0, sizeof(SyncState));
+    if (e == hipSuccess) e = hipMemset(m->ws + L.sync, 0, 2 * sizeof(SyncState));
     if (e == hipSuccess) {
         std::vector<LayerPtrs> lp(cfg->n_layers);
         for (int l = 0; l < cfg->n_layers; ++l)
@@ -1066,6 +1082,57 @@ rs_status rs_set_sampling(rs_model *m, int32_t enabled, uint64_t key) {
     }
     m->seen_once.clear(); m->seen_next = 0;
     m->sample_on = on; m->sample_key = key;
+    return RS_OK;
+}
+
+rs_status rs_stitch_generate(rs_model *slm, rs_model *llm, int32_t seq_slot, int32_t *d_seq, int32_t n_prompt,
+                             int32_t n_new, int32_t seen_slm, int32_t seen_llm, const float *d_logit_scale, float tau,
+                             int32_t eos, rs_stitch_record *d_trace, int32_t max_records, rs_stitch_result *d_result,
+                             void *stream) {
+    if (!slm || !llm) return fail(RS_EINVAL, "null model");
+    if (slm == llm) return fail(RS_EINVAL, "the two models must be different handles");
+    if (!d_seq || !d_trace || !d_result) return fail(RS_EINVAL, "null argument");
+    if (n_prompt < 1 || n_new < 1) return fail(RS_EINVAL, "need n_prompt >= 1 and n_new >= 1");
+    if (max_records < 1 || max_records > (1 << 20)) return fail(RS_EINVAL, "max_records must be in 1..2^20");
+    if (seen_slm < 0 || seen_slm > n_prompt - 1 || seen_llm < 0 || seen_llm > n_prompt - 1)
+        return fail(RS_EINVAL, "seen_slm / seen_llm must be in 0 .. n_prompt - 1");
+    rs_model *pair[2] = {slm, llm};
+    for (rs_model *m : pair) {
+        if (seq_slot < 0 || seq_slot >= m->cfg.max_seqs) return fail(RS_EINVAL, "seq_slot %d out of range", seq_slot);
+        if ((long long)n_prompt + n_new - 1 > m->cfg.max_ctx)
+            return fail(RS_ECAPACITY, "%d + %d tokens do not fit max_ctx %d", n_prompt, n_new, m->cfg.max_ctx);
+        if (m->sample_on) return fail(RS_ENOTIMPL, "the device-resident loop decodes greedily: disable sampling");
+    }
+    if (slm->cfg.head_dim != llm->cfg.head_dim) return fail(RS_EINVAL, "the two models must have the same head_dim");
+    if (slm->device != llm->device) return fail(RS_EINVAL, "the two models live on different devices");
+    const int hd = slm->cfg.head_dim;
+    const void *kern = stitch_loop_kernel(hd);
+    const size_t lds = slm->persist_lds > llm->persist_lds ? slm->persist_lds : llm->persist_lds;
+    int coop = 0, per_cu = 0;
+    RS_HIP(hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, slm->device));
+    if (!coop) return fail(RS_ENOTIMPL, "the device cannot launch cooperative kernels");
+    if (lds > 64 * 1024) RS_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    RS_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));
+    int blocks = per_cu * slm->n_cu;
+    if (blocks > 1024) blocks = 1024;
+    if (blocks * 4 > LM_PARTS_CAP) blocks = LM_PARTS_CAP / 4;
+    if (blocks < 1) return fail(RS_ENOTIMPL, "the loop kernel does not fit a compute unit");
+
+    hipStream_t st = (hipStream_t)stream;
+    SyncState *sync = slm->at<SyncState>(slm->lay.sync) + 1;
+    hipLaunchKernelGGL(k_stitch_init, dim3(1), dim3(64), 0, st, d_result, sync, n_prompt, n_prompt + n_new, seen_slm, seen_llm);
+    RS_LAUNCHED("stitch_init");
+    LoopArgs a{};
+    for (int i = 0; i < 2; ++i) {
+        fill_persist_args(pair[i], a.m[i], nullptr, nullptr, nullptr, nullptr, tau, i, nullptr, nullptr);
+        a.m[i].sync = sync; a.m[i].bar_base = 0; a.m[i].spin_limit = slm->spin_limit;
+    }
+    a.seq = d_seq; a.scale = d_logit_scale; a.tau = tau; a.eos = eos; a.slot = seq_slot;
+    a.trace = d_trace; a.max_records = max_records; a.state = d_result;
+    a.sync = sync; a.spin_limit = slm->spin_limit;
+    void *args[] = {&a};
+    hipError_t e = hipLaunchCooperativeKernel(kern, dim3(blocks), dim3(256), args, (unsigned int)lds, st);
+    if (e != hipSuccess) return fail(RS_EHIP, "cooperative launch of the stitched loop: %s", hipGetErrorString(e));
     return RS_OK;
 }
 

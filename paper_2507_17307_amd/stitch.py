@@ -48,6 +48,8 @@ class Invocation:
 class StitchRun:
     output: List[int] = field(default_factory=list)
     trace: List[Invocation] = field(default_factory=list)
+    status: int = B.STITCH_DONE          # generate_on_device: how the kernel's loop ended
+    loop_ms: float = 0.0                 # generate_on_device: GPU time of the call (events on its stream)
 
 
 class StitchedPair:
@@ -137,11 +139,11 @@ class StitchedPair:
     def generate(self, prompt: Sequence[int], tau: float, n_tokens: int, single_model: Optional[int] = None,
                  keep_trace: bool = True, stop_after: Optional[Callable[[int], bool]] = None,
                  llm_prefilled: bool = False, router_plus: Optional[B.RouterPlus] = None,
-                 sampling_key: Optional[int] = None) -> StitchRun:
+                 sampling_key: Optional[int] = None, slm_prefilled: bool = False) -> StitchRun:
         """Algorithm 1 until n_tokens tokens are accepted.  single_model = SLM or LLM runs that model
         alone (every token accepted) while still reporting its entropies.  llm_prefilled: the large model's
         cache already holds the prompt (prefill_prompt), so its first participation only catches up with the
-        tokens accepted since.  router_plus: the R-Stitch+ branch of Algorithm 1: after every small-model call the
+        tokens accepted since (slm_prefilled: the same for the small model).  router_plus: the R-Stitch+ branch of Algorithm 1: after every small-model call the
         learned router (rs_route_plus, enqueued behind the call) may turn a hand-over into "keep the token and stay".
         sampling_key: tokens are sampled from each step's distribution (rs_set_sampling with this 64-bit key on both
         models) instead of taken greedily."""
@@ -155,7 +157,7 @@ class StitchedPair:
         length = n0
         # a prefilled large model still has to produce a distribution the first time it is asked, which may be before
         # any token was accepted: it re-runs the last prompt token then (the same K/V row is written again)
-        n_kv = [0, n0 - 1 if llm_prefilled else 0]
+        n_kv = [n0 - 1 if slm_prefilled else 0, n0 - 1 if llm_prefilled else 0]
         active = SLM if single_model is None else single_model
         run = StitchRun()
         sync = self.stream.synchronize
@@ -184,6 +186,50 @@ class StitchedPair:
             run.output.append(token)
             if stop_after is not None and stop_after(len(run.output)):
                 break
+        return run
+
+
+    def generate_on_device(self, prompt: Sequence[int], tau: float, n_tokens: int, prompt_prefilled: bool = False,
+                           eos: int = -1, max_records: Optional[int] = None) -> StitchRun:
+        """Algorithm 1 with the loop on the device (rs_stitch_generate): one kernel runs every invocation and
+        applies the routing flags itself; the host reads the sequence, the trace and the result once, at the end.
+        prompt_prefilled: both models first take all but the last prompt token through rs_catchup_prefill (the
+        matrix-core path), so the kernel starts each of them at the last prompt token.  The run's `status` is one
+        of binding.STITCH_*."""
+        n0 = len(prompt)
+        if n0 + n_tokens > self.max_ctx + 1:
+            raise ValueError("prompt + tokens exceed max_ctx")
+        dev = self.models[SLM].device
+        seen = 0
+        if prompt_prefilled and n0 > 1:
+            self.seq_np[:n0] = np.asarray(prompt, dtype=np.int32)
+            for model in (SLM, LLM):
+                self._forward(model, 0, n0 - 1, tau)
+                self.stream.synchronize()
+            seen = n0 - 1
+        cap = 2 * n_tokens if max_records is None else max_records
+        d_seq = torch.zeros(n0 + n_tokens, dtype=torch.int32, device=dev)
+        d_seq[:n0] = torch.as_tensor(np.asarray(prompt, dtype=np.int32), device=dev)
+        d_scale = torch.as_tensor(self.scale_np[:n0 + n_tokens], device=dev)
+        d_trace = torch.zeros(cap, B.STITCH_RECORD_INTS, dtype=torch.int32, device=dev)
+        d_result = torch.zeros(B.STITCH_RESULT_INTS, dtype=torch.int32, device=dev)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(self.stream)
+        B.rs_stitch_generate(self.models[SLM].handle, self.models[LLM].handle, 0, d_seq, n0, n_tokens, seen, seen,
+                             d_scale, tau, eos, d_trace, cap, d_result, self.stream)
+        e1.record(self.stream)
+        self.stream.synchronize()
+        result = d_result.cpu().numpy()
+        trace_i = d_trace.cpu().numpy()
+        trace_f = trace_i.view(np.float32)
+        run = StitchRun()
+        run.status = int(result[0])
+        run.loop_ms = e0.elapsed_time(e1)
+        run.output = d_seq.cpu().numpy()[n0:int(result[1])].tolist()
+        for r in range(int(result[2])):
+            run.trace.append(Invocation(int(trace_i[r, 0]), int(trace_i[r, 1]), int(trace_i[r, 2]), int(trace_i[r, 4]),
+                                        float(trace_f[r, 7]), int(trace_i[r, 5]) & 0xFFFFFFFF))
         return run
 
 

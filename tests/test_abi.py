@@ -57,6 +57,7 @@ def test_null_and_range_arguments_are_rejected_before_any_launch():
     assert lib.rs_catchup_prefill(None, 1, 1, None, None, None, None, None, 0.5, 0, None, None, None) == -1
     assert lib.rs_route(None, 1, 100, None, 0.5, 0, None, None, 0, None) == -1
     assert "null" in P.rs_last_error()
+    assert lib.rs_stitch_generate(None, None, 0, None, 1, 1, 0, 0, None, 0.5, -1, None, 1, None, None) == -1
     assert lib.rs_route(16, 0, 100, None, 0.5, 0, 16, 16, 1 << 20, None) == -1
     assert lib.rs_route(16, 1, 1, None, 0.5, 0, 16, 16, 1 << 20, None) == -1
     assert lib.rs_route(16, 1, 100, None, 0.5, 7, 16, 16, 1 << 20, None) == -1

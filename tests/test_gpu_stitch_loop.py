@@ -1,0 +1,113 @@
+"""GPU parity of rs_stitch_generate (Algorithm 1 with the loop on the device) against the oracle's run.
+
+The oracle's `generate` is the loop written out; the kernel's trace must show the same invocations
+(model, first position, rows fed, token kept or not) and the same accepted tokens.
+"""
+import math
+
+import pytest
+import torch
+
+import workloads as W
+from test_gpu_model import pair_run
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedPair
+    wl = W.WORKLOADS["cfg1_tiny_pair"]
+    weights, _, res, _, tau, scales = pair_run(wl)
+    gpu = [P.Model(w.to("cuda"), max_ctx=wl.max_ctx + 1, max_rows=64) for w in weights]
+    pair = StitchedPair(gpu[0], gpu[1], wl.max_ctx, scales)
+    return wl, pair, res, tau, W.make_prompt(wl).tolist()
+
+
+def key(trace, spans=True):
+    return [(t.model, t.pos0, (t.n_rows if hasattr(t, "n_rows") else len(t.span)) if spans else 0, t.accept) for t in trace]
+
+
+def test_device_loop_reproduces_the_oracle_run(cfg1):
+    import paper_2507_17307_amd as P
+    wl, pair, res, tau, prompt = cfg1
+    run = pair.generate_on_device(prompt, tau, wl.n_decode)
+    assert run.status == P.STITCH_DONE
+    assert run.output == res.output
+    assert key(run.trace) == key(res.trace)
+    assert max(abs(a.h_norm - b.h_norm) for a, b in zip(run.trace, res.trace)) <= 1e-3 / math.log(1024)
+    assert any(not t.accept for t in run.trace) and any(t.model == P.RS_LLM and t.n_rows > 1 for t in run.trace)
+    # the host-driven loop of the package sees the same run, and a second device run repeats the first bit for bit
+    host = pair.generate(prompt, tau, wl.n_decode)
+    assert host.output == run.output and key(host.trace) == key(run.trace)
+    again = pair.generate_on_device(prompt, tau, wl.n_decode)
+    assert again.output == run.output and [(t.flags, t.h_norm) for t in again.trace] == [(t.flags, t.h_norm) for t in run.trace]
+
+
+def test_device_loop_after_a_prompt_prefill_through_the_matrix_core_path(cfg1):
+    """Both models take all but the last prompt token through rs_catchup_prefill first: the kernel then starts
+    each of them at the last prompt token, so only the first span of each model differs from the oracle's trace."""
+    import paper_2507_17307_amd as P
+    wl, pair, res, tau, prompt = cfg1
+    run = pair.generate_on_device(prompt, tau, wl.n_decode, prompt_prefilled=True)
+    assert run.status == P.STITCH_DONE and run.output == res.output
+    assert [(t.model, t.accept) for t in run.trace] == [(t.model, t.accept) for t in res.trace]
+    first = {}
+    for got, want in zip(run.trace, res.trace):
+        if got.model not in first:
+            first[got.model] = True
+            assert got.pos0 == len(prompt) - 1 and got.pos0 + got.n_rows == want.pos0 + len(want.span)
+        else:
+            assert (got.pos0, got.n_rows) == (want.pos0, len(want.span))
+
+
+def test_trace_capacity_and_eos_end_the_loop(cfg1):
+    import paper_2507_17307_amd as P
+    wl, pair, res, tau, prompt = cfg1
+    short = pair.generate_on_device(prompt, tau, wl.n_decode, max_records=5)
+    assert short.status == P.STITCH_TRACE_FULL and key(short.trace) == key(res.trace)[:5]
+    assert short.output == res.output[:len(short.output)] and len(short.output) == sum(t.accept for t in res.trace[:5])
+    eos = res.output[6]
+    stop = res.output.index(eos)
+    ended = pair.generate_on_device(prompt, tau, wl.n_decode, eos=eos)
+    assert ended.status == P.STITCH_DONE and ended.output == res.output[:stop + 1]
+
+
+def test_bounded_wait_ends_the_loop_instead_of_hanging(cfg1):
+    """A spin limit of one poll makes the first grid-wide wait give up: the kernel must end with status ABORTED
+    (every workgroup leaves through the same exit); the barrier words are cleared per call, so the next run works."""
+    import paper_2507_17307_amd as P
+    wl, pair, res, tau, prompt = cfg1
+    P.rs_set_spin_limit(pair.models[0].handle, 1)
+    try:
+        run = pair.generate_on_device(prompt, tau, 8)
+    finally:
+        P.rs_set_spin_limit(pair.models[0].handle, 0)
+    assert run.status == P.STITCH_ABORTED
+    ok = pair.generate_on_device(prompt, tau, 8)
+    assert ok.status == P.STITCH_DONE and ok.output == res.output[:8]
+
+
+def test_host_side_argument_checks(cfg1):
+    import paper_2507_17307_amd as P
+    wl, pair, res, tau, prompt = cfg1
+    slm, llm = pair.models[0].handle, pair.models[1].handle
+    seq = torch.zeros(64, dtype=torch.int32, device="cuda")
+    trace = torch.zeros(16, 10, dtype=torch.int32, device="cuda")
+    result = torch.zeros(8, dtype=torch.int32, device="cuda")
+    good = dict(slm=slm, llm=llm, seq_slot=0, d_seq=seq, n_prompt=4, n_new=4, seen_slm=0, seen_llm=0, d_logit_scale=None,
+                tau=0.5, eos=-1, d_trace=trace, max_records=16, d_result=result)
+    for change, status in ((dict(n_prompt=0), -1), (dict(n_new=0), -1), (dict(seen_slm=4), -1), (dict(seen_llm=-1), -1),
+                           (dict(llm=slm), -1), (dict(seq_slot=1), -1), (dict(max_records=0), -1), (dict(d_trace=None), -1),
+                           (dict(n_new=wl.max_ctx + 8), -2)):
+        with pytest.raises(P.RsError) as e:
+            P.rs_stitch_generate(**{**good, **change})
+        assert e.value.status == status, change
+    P.rs_set_sampling(slm, True, 7)
+    try:
+        with pytest.raises(P.RsError) as e:
+            P.rs_stitch_generate(**good)
+        assert e.value.status == -4
+    finally:
+        P.rs_set_sampling(slm, False)
