@@ -111,3 +111,30 @@ def test_host_side_argument_checks(cfg1):
         assert e.value.status == -4
     finally:
         P.rs_set_sampling(slm, False)
+
+
+OTHER_PAIRS = [
+    # name, head_dim, (layers, d, n_q, n_kv, ffn) of the small and of the large model, vocabulary
+    ("hd64", 64, (1, 256, 4, 2, 384), (2, 512, 8, 1, 640), 1536),
+    ("hd128", 128, (1, 256, 2, 1, 384), (3, 384, 3, 1, 512), 1280),
+]
+
+
+@pytest.mark.parametrize("name,hd,small,large,vocab", OTHER_PAIRS, ids=[p[0] for p in OTHER_PAIRS])
+def test_device_loop_at_other_head_sizes_and_depths(name, hd, small, large, vocab):
+    """The kernel is compiled per head size and walks two models of different depth and width: pairs with
+    head_dim 64 and 128 (the five configurations' tiny pair has 32), each against the oracle's run."""
+    import paper_2507_17307_amd as P
+    from paper_2507_17307_amd.stitch import StitchedPair
+    from workloads.recipes import Workload
+    from workloads.shapes import ModelShape
+    mk = lambda tag, s, tied: ModelShape(f"{name}_{tag}", s[0], s[1], s[2], s[3], hd, s[4], vocab, tied)  # noqa: E731
+    wl = Workload(f"loop_{name}", 21, mk("s", small, True), mk("l", large, False), 12, 24, 65.0)
+    weights, _, res, _, tau, scales = pair_run(wl)
+    assert 0 < res.n_llm_tokens < wl.n_decode and res.n_rejected > 0
+    gpu = [P.Model(w.to("cuda"), max_ctx=wl.max_ctx + 8, max_rows=16) for w in weights]
+    pair = StitchedPair(gpu[0], gpu[1], wl.max_ctx, scales)
+    run = pair.generate_on_device(W.make_prompt(wl).tolist(), tau, wl.n_decode)
+    assert run.status == P.STITCH_DONE and run.output == res.output
+    assert key(run.trace) == key(res.trace)
+    assert max(abs(a.h_norm - b.h_norm) for a, b in zip(run.trace, res.trace)) <= 1e-3 / math.log(vocab)
