@@ -1,14 +1,18 @@
 // Whole decode step of one token row as ONE kernel: every workgroup walks the
 // same list of phases (row table + embedding, then per layer QKV / attention /
 // O-proj / gate-up / down, then LM head and router merge) and the phases are
-// separated by a grid-wide barrier.  This removes ~140 kernel launches per
-// step, each of which costs several microseconds of launch and ramp-up latency
-// that a 0.4 ms step cannot afford.
+// separated by a grid-wide barrier; on top of it, Algorithm 1's whole loop as one
+// kernel (k_stitch_loop).  On MI355X a software barrier across the eight XCDs
+// (agent-scope release + acquire per workgroup, several dependent round trips to
+// memory-side atomics) costs 12-16 us against the ~2 us of a kernel boundary, so
+// both are slower than one kernel per phase; they exist for callers that cannot
+// put the host between invocations, and as a measured answer to that question.
 //
-// The kernel is launched cooperatively (all workgroups co-resident), and every
-// wait in it is bounded: a workgroup that polls longer than `spin_limit` times
+// The kernels are launched cooperatively (all workgroups co-resident), and every
+// wait in them is bounded: a workgroup that polls longer than `spin_limit` times
 // raises a sticky abort word; every other workgroup leaves at its next poll, the
-// record is flagged RS_FLAG_ABORTED and later launches return at once.
+// record is flagged RS_FLAG_ABORTED (the loop: status RS_STITCH_ABORTED) and, for
+// the single step, later launches return at once.
 #pragma once
 
 #include "model_kernels.h"
