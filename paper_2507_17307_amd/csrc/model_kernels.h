@@ -1451,26 +1451,40 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
     // slices that hold context: same slice length as attn_partial_unit
     int C = (a.max_ctx + S - 1) / S;
     C = ((C + ATT_BT - 1) / ATT_BT) * ATT_BT;
-    const int S_act = a.row_bad[row] ? 0 : min(S, a.row_pos[row] / C + 1);
+    // The records of all S slices are requested together with the row's position (one round trip instead of
+    // two dependent ones); a slice past the context holds whatever an earlier call left there and is
+    // replaced, never scaled, once the position has arrived.
+    const int bad = a.row_bad[row], pos = a.row_pos[row];
+    constexpr int NPL = SMAX / 64;                          // slices per lane (wave 0)
     float4 buf[NLD];
+    float2 mlr[NPL];
 #pragma unroll
     for (int k = 0; k < NLD; ++k) {
         const int s = sg + k * NSG;
         buf[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (s < S_act) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + dq * HDB + 4 * qd);
+        if (s < S) buf[k] = *reinterpret_cast<const float4 *>(pbase + (size_t)s * PS + 4 + dq * HDB + 4 * qd);
     }
     if (wave == 0) {
-        constexpr int NPL = SMAX / 64;                      // slices per lane
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+            const int s = lane + 64 * k;
+            mlr[k] = make_float2(0.f, 0.f);
+            if (s < S) mlr[k] = *reinterpret_cast<const float2 *>(pbase + (size_t)s * PS);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);                      // every request is in flight before anything waits
+    const int S_act = bad ? 0 : min(S, pos / C + 1);
+#pragma unroll
+    for (int k = 0; k < NLD; ++k)
+        if (sg + k * NSG >= S_act) buf[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (wave == 0) {
         float ms[NPL], ls[NPL], w[NPL];
         float mx = -INFINITY;
 #pragma unroll
         for (int k = 0; k < NPL; ++k) {
             const int s = lane + 64 * k;
             ms[k] = -INFINITY; ls[k] = 0.f;
-            if (s < S_act) {
-                const float2 ml = *reinterpret_cast<const float2 *>(pbase + (size_t)s * PS);
-                ls[k] = ml.y; ms[k] = ls[k] > 0.f ? ml.x : -INFINITY;
-            }
+            if (s < S_act) { ls[k] = mlr[k].y; ms[k] = ls[k] > 0.f ? mlr[k].x : -INFINITY; }
             mx = fmaxf(mx, ms[k]);
         }
         const float M = wave_max(mx);
