@@ -436,9 +436,11 @@ constexpr int G_PART = 5;
 // against 91)
 template <int TB> constexpr int tile_sw() { return 1; }
 
+constexpr int TILE_PAD = 16;                      // bytes added to a parked row of k_gemm_tile against LDS bank conflicts (48 measured the same)
+
 template <int MODE, int TB, int CT>
 __host__ __device__ constexpr size_t gemm_tile_lds_bytes() {
-    return (size_t)2 * ((MODE == G_GATEUP) ? 2 : 1) * CT * 16 * (128 * tile_sw<TB>() + 16);
+    return (size_t)2 * ((MODE == G_GATEUP) ? 2 : 1) * CT * 16 * (128 * tile_sw<TB>() + TILE_PAD);
 }
 
 // workgroup barrier for LDS hand-over that leaves global loads in flight: the LDS accesses issued so far complete
@@ -452,7 +454,7 @@ __global__ void __launch_bounds__(NW * 64) k_gemm_tile(GemmArgs a) {
     constexpr int NS = GEMM_KW / 32;
     constexpr int SW = tile_sw<TB>();                         // windows per step
     constexpr int KSTEP = GEMM_KW * SW;                       // k elements per step: K must be a multiple
-    constexpr int PITCH = 128 * SW + 16;                      // bytes per parked row (padded against LDS bank conflicts)
+    constexpr int PITCH = 128 * SW + TILE_PAD;                // bytes per parked row (padded against LDS bank conflicts)
     constexpr int WROWS = NT * CT * 16;                       // W rows of a step
     constexpr int RPR = 8 * NW / SW;                          // rows per round of 16-byte loads of the whole workgroup
     constexpr int WQ = (WROWS + RPR - 1) / RPR;               // loads per thread and step
