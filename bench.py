@@ -39,6 +39,10 @@ HBM_PEAK = 8.0e12   # bytes/s, MI355X published
 DTYPE = "bf16 weights, f32 activations and accumulation"
 
 
+# (timed accepted tokens, warm-up tokens) of a run without --steps / --warmup
+DEFAULT_STEPS = {"cfg1_tiny_pair": (48, 8), "cfg2_s15_decode": (448, 64), "cfg3_s15_m7": (4032, 64), "cfg4_s15_m14": (256, 32)}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -392,8 +396,11 @@ def bench_batched(args, wl) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=4032, help="accepted tokens in the timed region")
-    ap.add_argument("--warmup", type=int, default=64, help="accepted tokens before the timed region")
+    ap.add_argument("--steps", type=int, default=None,
+                    help="accepted tokens in the timed region (default per workload: 4032 for cfg3, 448 for cfg2, 256 for "
+                         "cfg4, 96 per sequence for a workload of several sequences)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="accepted tokens before the timed region (default 64; 32 for cfg4, 16 for several sequences)")
     ap.add_argument("--workload", default="cfg3_s15_m7")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency-fit", action="store_true")
@@ -414,18 +421,29 @@ def main() -> int:
     import paper_2507_17307_amd as P
     from paper_2507_17307_amd.stitch import StitchedPair, SLM, LLM
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload not in W.WORKLOADS:
+        print(f"bench.py: unknown workload {args.workload!r}; known: {', '.join(W.WORKLOADS)}", file=sys.stderr)
+        return 2
     wl = W.WORKLOADS[args.workload]
+    several = wl.n_seqs > 1 or args.seqs is not None
+    d_steps, d_warmup = DEFAULT_STEPS.get(args.workload, (256, 32))
+    if several:
+        d_steps, d_warmup = 96, 16
+    if args.warmup is None:
+        args.warmup = d_warmup
+    if args.steps is None:
+        args.steps = d_steps if several else min(d_steps, wl.n_decode - args.warmup)
+    if args.steps < 1 or args.warmup < 0 or (not several and args.warmup + args.steps > wl.n_decode):
+        print(f"bench.py: need steps >= 1, warmup >= 0 and warmup + steps <= {wl.n_decode}", file=sys.stderr)
+        return 2
+    if args.seqs is not None and not 1 <= args.seqs <= 128:
+        print("bench.py: --seqs must be in 1..128", file=sys.stderr)
+        return 2
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
     if wl.llm is None:
         return bench_single_model(args, wl)
     if wl.n_seqs > 1 or args.seqs is not None:
-        if args.seqs is not None and not 1 <= args.seqs <= 128:
-            print("bench.py: --seqs must be in 1..128", file=sys.stderr)
-            return 2
         return bench_batched(args, wl)
-    if args.warmup + args.steps > wl.n_decode:
-        print(f"bench.py: warmup + steps must not exceed {wl.n_decode}", file=sys.stderr)
-        return 2
     dev = "cuda"
     t0 = time.time()
     w_s = W.make_weights(wl.slm, wl.seed, 0, device=dev)

@@ -17,4 +17,11 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 def test_unknown_workload_is_refused():
     r = run("--workload", "cfg9_nothing")
-    assert r.returncode != 0 and r.stdout.strip() == ""
+    assert r.returncode == 2 and "unknown workload" in r.stderr and r.stdout.strip() == ""
+
+
+def test_step_counts_beyond_the_workload_are_refused():
+    r = run("--workload", "cfg2_s15_decode", "--steps", "600")
+    assert r.returncode == 2 and "warmup + steps" in r.stderr
+    r = run("--seqs", "129")
+    assert r.returncode == 2 and "--seqs" in r.stderr
