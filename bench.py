@@ -40,7 +40,7 @@ DTYPE = "bf16 weights, f32 activations and accumulation"
 
 
 # (timed accepted tokens, warm-up tokens) of a run without --steps / --warmup
-DEFAULT_STEPS = {"cfg1_tiny_pair": (48, 8), "cfg2_s15_decode": (448, 64), "cfg3_s15_m7": (4032, 64), "cfg4_s15_m14": (256, 32)}
+DEFAULT_STEPS = {"cfg2_s15_decode": (448, 64), "cfg3_s15_m7": (4032, 64), "cfg4_s15_m14": (256, 32)}
 
 
 def log(*a):
@@ -425,6 +425,10 @@ def main() -> int:
         print(f"bench.py: unknown workload {args.workload!r}; known: {', '.join(W.WORKLOADS)}", file=sys.stderr)
         return 2
     wl = W.WORKLOADS[args.workload]
+    if wl.max_ctx < 1024:
+        print(f"bench.py: {args.workload} is a parity-test workload (a context of {wl.max_ctx}): the timed passes here "
+              "assume the real shapes", file=sys.stderr)
+        return 2
     several = wl.n_seqs > 1 or args.seqs is not None
     d_steps, d_warmup = DEFAULT_STEPS.get(args.workload, (256, 32))
     if several:

@@ -20,6 +20,11 @@ def test_unknown_workload_is_refused():
     assert r.returncode == 2 and "unknown workload" in r.stderr and r.stdout.strip() == ""
 
 
+def test_the_tiny_parity_workload_is_not_a_bench_line():
+    r = run("--workload", "cfg1_tiny_pair")
+    assert r.returncode == 2 and "parity-test workload" in r.stderr
+
+
 def test_step_counts_beyond_the_workload_are_refused():
     r = run("--workload", "cfg2_s15_decode", "--steps", "600")
     assert r.returncode == 2 and "warmup + steps" in r.stderr
