@@ -868,7 +868,6 @@ struct AttnArgs {
     const uint16_t *vcache;        // [layer][slot][kv_head][hd][position] bf16
     float *partials;               // [rows, n_q, n_slices, hd+4]
     float *out;                    // [rows, n_q*hd] fp32
-    uint16_t *out_planes; size_t out_plane;   // optional three-plane bf16 split of the same values, or null
     const int *row_pos, *row_slot, *row_bad;
     int n_q, n_kv, max_ctx, max_seqs, layer, n_slices;
     int n_rows;                    // token rows in the call (k_attn_partial_rows)
@@ -1514,13 +1513,6 @@ __device__ __forceinline__ void attn_combine_unit(const AttnArgs &a, unsigned ch
         for (int g = 0; g < NSG; ++g) o += red[g][tid];
         const size_t oi = ((size_t)row * a.n_q + head) * HD + dq * HDB + tid;
         a.out[oi] = o;
-        if (a.out_planes) {
-            const uint16_t p0 = f32_to_bf16(o);
-            const float r1 = o - bf16_to_f32(p0);
-            const uint16_t p1 = f32_to_bf16(r1);
-            a.out_planes[oi] = p0; a.out_planes[a.out_plane + oi] = p1;
-            a.out_planes[2 * a.out_plane + oi] = f32_to_bf16(r1 - bf16_to_f32(p1));
-        }
     }
 }
 

@@ -2,24 +2,18 @@
 // tokens a model has not seen, and batched decode.  The weights are still read
 // once per call, so the phases stay HBM-bound; the contraction over tokens runs
 // on the matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate) so that ALU
-// work never becomes the limiter.  Activations are fp32 values carried as three
-// bf16 planes (p0 = bf16(x), p1 = bf16(x - p0), p2 = x - p0 - p1, which is exact:
-// 3 x 8 significant bits hold the 24 of an fp32); each weight tile is multiplied
-// with all three, smallest first, so the product is that of the fp32 activation.
+// work never becomes the limiter.  Activations stay fp32 in memory; the consumer
+// splits each value in registers into three bf16 planes (p0 = bf16(x), p1 =
+// bf16(x - p0), p2 = x - p0 - p1, which is exact: 3 x 8 significant bits hold the
+// 24 of an fp32) and multiplies each weight tile with all three, smallest first,
+// so the product is that of the fp32 activation (4 bytes per element through the
+// load path instead of the 6 of stored planes).
 #pragma once
 
 #include "device_utils.h"
 #include "model_kernels.h"
 
 namespace rs {
-
-// planes: p[0], p[1], p[2] each [rows, cols]; `plane` = elements per plane
-__device__ __forceinline__ void split_store(float v, uint16_t *p, size_t plane, size_t i) {
-    const uint16_t a = f32_to_bf16(v);
-    const float r1 = v - bf16_to_f32(a);
-    const uint16_t b = f32_to_bf16(r1);
-    p[i] = a; p[plane + i] = b; p[2 * plane + i] = f32_to_bf16(r1 - bf16_to_f32(b));
-}
 
 constexpr int ROWK_THREADS = 1024;     // one workgroup per token row in the two row kernels below
 constexpr int KSPLIT_MAX = 8;
@@ -37,15 +31,16 @@ __device__ __forceinline__ float4 sum_splits4(const float *base, size_t i, int k
     return first;
 }
 
-// RMSNorm of whole rows into three bf16 planes: grid n_out, block ROWK_THREADS; d a multiple of 4, at
-// most 12 * ROWK_THREADS.  src row = gather ? gather[blockIdx.x] : blockIdx.x
+// RMSNorm of whole rows: grid n_out, block ROWK_THREADS; d a multiple of 4, at most 12 * ROWK_THREADS.
+// src row = gather ? gather[blockIdx.x] : blockIdx.x; the normalised row goes to out32[blockIdx.x] as fp32 (the
+// matrix-core kernels split it into bf16 planes themselves).
 // part != null: the projection before this norm left its result as `ksplit` partial sums
 // part[ks][row][d] (split over K across workgroups); they are added to the residual row here, in a
 // fixed order, and the row is written back before it is normalised.
 __global__ void __launch_bounds__(ROWK_THREADS)
 k_rmsnorm_rows(float *__restrict__ h, const uint16_t *__restrict__ gain, float eps, int d,
-               const int *__restrict__ gather, uint16_t *__restrict__ out, size_t plane,
-               const float *__restrict__ part, int ksplit, size_t part_stride, float *__restrict__ out32) {
+               const int *__restrict__ gather, float *__restrict__ out32,
+               const float *__restrict__ part, int ksplit, size_t part_stride) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int src = gather ? gather[blockIdx.x] : blockIdx.x;
     float *hr = h + (size_t)src * d;
@@ -82,23 +77,9 @@ k_rmsnorm_rows(float *__restrict__ h, const uint16_t *__restrict__ gain, float e
     for (int k = 0; k < NV; ++k) {
         const int i4 = tid + k * ROWK_THREADS;
         if (i4 >= n4) continue;
-        const float x[4] = {v[k].x * (inv * bf16_lo(gv[k].x)), v[k].y * (inv * bf16_hi(gv[k].x)),
-                            v[k].z * (inv * bf16_lo(gv[k].y)), v[k].w * (inv * bf16_hi(gv[k].y))};
-        // three planes, four values each: packed 8-byte stores
-        uint32_t w0[2], w1[2], w2[2];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const float a0 = x[2 * q], b0 = x[2 * q + 1];
-            w0[q] = pack_bf16x2(a0, b0);
-            const float ra = a0 - bf16_lo(w0[q]), rb = b0 - bf16_hi(w0[q]);
-            w1[q] = pack_bf16x2(ra, rb);
-            w2[q] = pack_bf16x2(ra - bf16_lo(w1[q]), rb - bf16_hi(w1[q]));
-        }
         const size_t o = (size_t)blockIdx.x * d + 4 * i4;
-        if (out32) { *reinterpret_cast<float4 *>(out32 + o) = make_float4(x[0], x[1], x[2], x[3]); continue; }   // the consumer splits
-        *reinterpret_cast<uint2 *>(out + o) = make_uint2(w0[0], w0[1]);
-        *reinterpret_cast<uint2 *>(out + plane + o) = make_uint2(w1[0], w1[1]);
-        *reinterpret_cast<uint2 *>(out + 2 * plane + o) = make_uint2(w2[0], w2[1]);
+        *reinterpret_cast<float4 *>(out32 + o) = make_float4(v[k].x * (inv * bf16_lo(gv[k].x)), v[k].y * (inv * bf16_hi(gv[k].x)),
+                                                             v[k].z * (inv * bf16_lo(gv[k].y)), v[k].w * (inv * bf16_hi(gv[k].y)));
     }
 }
 
@@ -156,10 +137,11 @@ __global__ void __launch_bounds__(ROWK_THREADS) k_rope_kv_rows(RopeArgs a) {
 // A workgroup of GEMM_NW waves owns R consecutive tiles of 16 output columns (for gate/up a tile is 16
 // gate rows plus the 16 matching up rows of W) and ALL of K; wave w takes the k windows w, w+GEMM_NW,
 // ... of 64 elements (more waves where a matrix has few tiles, so that enough requests are in flight).  Per window a wave requests
-//   * its piece of X once: three bf16 planes, 16 tokens x 64 k per 16-token block, each lane
-//     straight in the B-operand layout of v_mfma_f32_16x16x32_bf16 (lane (i = lane % 16, g = lane / 16)
-//     supplies the 8 consecutive k at 32 s + 8 g of token i); the piece serves all R tiles, so X
-//     costs 3/R of the W bytes in L2 traffic;
+//   * its piece of X once: fp32, 16 tokens x 64 k per 16-token block, each lane the values of its
+//     place in the B-operand layout of v_mfma_f32_16x16x32_bf16 (lane (i = lane % 16, g = lane / 16)
+//     supplies the 8 consecutive k at 32 s + 8 g of token i), split into the three planes in
+//     registers; the piece serves all R tiles, so X costs 2/R of the W bytes in L2 traffic (stored
+//     planes cost 3/R: a 7B-shape call of 16 rows 4.84 -> 4.4 ms);
 //   * the 16 x 64 piece of W of every tile it owns with coalesced 16-byte loads, eight lanes per
 //     128-byte row piece (whole cache lines: on this chip 64-byte pieces, which the operand layout
 //     would give directly, stream at 4.5 TB/s, 128-byte pieces at 6.2), parked in the wave's private
@@ -171,16 +153,15 @@ __global__ void __launch_bounds__(ROWK_THREADS) k_rope_kv_rows(RopeArgs a) {
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
     const uint16_t *W; int N, K, M;       // M = valid token rows
-    const uint16_t *X; size_t x_plane;    // three [.., K] bf16 planes, x_plane elements apart
-    const float *X32;                     // k_gemm_tile: the same activations as plain fp32 rows [.., K] (split into planes by the consumer)
-    float *act32;                         // k_gemm_tile, gate/up: SwiGLU output rows [.., d_ffn] fp32
+    const float *X32;                     // activations: fp32 rows [.., K] (split into three bf16 planes in registers)
+    float *act32;                         // gate/up: SwiGLU output rows [.., d_ffn] fp32
     float *out_f32; int ld_out;           // raw fp32 output [M, ld_out] (QKV)
     int yblocks;                          // > 1: the token rows are cut into yblocks blocks of 16*NB rows, each taken by its own
                                           //      workgroups (same weights; ids arranged so that they meet in one XCD's L2)
     int ksplit; size_t part_stride;       // > 1: K is split over workgroups too; split ks writes its partial sums to
     float *part;                          //      part[ks * part_stride + m * N + n] (QKV, O-proj, down) and the consumer adds them up
     float *h_out; int ld_h;               // residual accumulate
-    uint16_t *act; size_t act_plane; int d_ffn;   // gate/up output planes
+    int d_ffn;
     const float *seq_scale; SoftPartial *parts; float *logits; int n_parts;   // LM head
     int sample_on; unsigned long long sample_key;         // LM head: also track the arg max of logit + Gumbel noise
     const int *row_pos, *out_row;                         // sampling: position of the row that feeds output row m is row_pos[out_row[m]]
@@ -234,13 +215,13 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
     const int m_base = yb * 16 * NB;
 
     // token side: rows past M read row 0 and are cleared after the load
-    const uint16_t *xp[NB];
+    const float *xp[NB];
     bool xok[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int m = m_base + nb * 16 + i16;
         xok[nb] = m < a.M;
-        xp[nb] = a.X + (size_t)(xok[nb] ? m : 0) * K + g * 8;
+        xp[nb] = a.X32 + (size_t)(xok[nb] ? m : 0) * K + g * 8;
     }
     SoftState st; st.init();
     const int lm_row = m_base + i16;                      // LM head (NB = 1): the output row this lane's state follows
@@ -269,15 +250,15 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
         // products of the current one.  Requests are unconditional (the window index is clamped;
         // a duplicate is fetched but never multiplied) so that the compiler can count them and wait
         // for exactly the older set.
-        auto request = [&](int win, uint4 (&xb)[NB][NS][3], uint4 (&wr)[R][NT][NQ]) {
+        auto request = [&](int win, float4 (&xb)[NB][NS][2], uint4 (&wr)[R][NT][NQ]) {
             const int k0 = min(win, w_hi - 1) * GEMM_KW;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int s = 0; s < NS; ++s)
-#pragma unroll
-                    for (int pl = 0; pl < 3; ++pl)
-                        xb[nb][s][pl] = *reinterpret_cast<const uint4 *>(xp[nb] + pl * a.x_plane + k0 + 32 * s);
+                for (int s = 0; s < NS; ++s) {
+                    const float4 *q = reinterpret_cast<const float4 *>(xp[nb] + k0 + 32 * s);
+                    xb[nb][s][0] = q[0]; xb[nb][s][1] = q[1];
+                }
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -286,14 +267,20 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
                     for (int q = 0; q < NQ; ++q)
                         wr[r][nt][q] = load_stream(reinterpret_cast<const uint4 *>(wp[r][nt][q] + k0));
         };
-        auto multiply = [&](uint4 (&xb)[NB][NS][3], const uint4 (&wr)[R][NT][NQ]) {
+        auto multiply = [&](const float4 (&xb)[NB][NS][2], const uint4 (&wr)[R][NT][NQ]) {
+            // this lane's 8 consecutive k of token i16 per k step, as three bf16 planes whose sum is the fp32 value
+            bf16x8_t B[NB][NS][3];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                if (!xok[nb]) {
 #pragma unroll
-                    for (int s = 0; s < NS; ++s)
+                for (int s = 0; s < NS; ++s) {
+                    const float4 x0 = xb[nb][s][0], x1 = xb[nb][s][1];
+                    float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                    if (!xok[nb]) {
 #pragma unroll
-                        for (int pl = 0; pl < 3; ++pl) xb[nb][s][pl] = make_uint4(0, 0, 0, 0);
+                        for (int e = 0; e < 8; ++e) xv[e] = 0.f;
+                    }
+                    split3(xv, B[nb][s]);
                 }
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -316,13 +303,13 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
                         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                             for (int pl = 2; pl >= 0; --pl)           // smallest plane first
-                                acc[r][nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    A, __builtin_bit_cast(bf16x8_t, xb[nb][s][pl]), acc[r][nt][nb], 0, 0, 0);
+                                acc[r][nt][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B[nb][s][pl], acc[r][nt][nb], 0, 0, 0);
                     }
                 }
         };
         if constexpr (TWO_IN_FLIGHT) {
-            uint4 xb0[NB][NS][3], xb1[NB][NS][3], wr0[R][NT][NQ], wr1[R][NT][NQ];
+            float4 xb0[NB][NS][2], xb1[NB][NS][2];
+            uint4 wr0[R][NT][NQ], wr1[R][NT][NQ];
             int win = w_lo + wave;
             if (win < w_hi) {
                 request(win, xb0, wr0);
@@ -338,7 +325,8 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
                 }
             }
         } else {
-            uint4 xb0[NB][NS][3], wr0[R][NT][NQ];
+            float4 xb0[NB][NS][2];
+            uint4 wr0[R][NT][NQ];
             for (int win = w_lo + wave; win < w_hi; win += GEMM_NW) {
                 request(win, xb0, wr0);
                 multiply(xb0, wr0);
@@ -381,7 +369,7 @@ __global__ void __launch_bounds__(GEMM_NW * 64) k_gemm_rows(GemmArgs a) {
                 if ((MODE == G_QKV || MODE == G_OPROJ || MODE == G_DOWN) && KSP > 1) a.part[ksp * a.part_stride + (size_t)m * n_out + n] = val;
                 else if (MODE == G_QKV) a.out_f32[(size_t)m * a.ld_out + n] = val;
                 else if (MODE == G_OPROJ || MODE == G_DOWN) a.h_out[(size_t)m * a.ld_h + n] += val;
-                else if (MODE == G_GATEUP) split_store(val / (1.0f + expf(-val)) * o1[rr], a.act, a.act_plane, (size_t)m * a.d_ffn + n);
+                else if (MODE == G_GATEUP) a.act32[(size_t)m * a.d_ffn + n] = val / (1.0f + expf(-val)) * o1[rr];
                 else {
                     const float lg = val * lm_scale;
                     st.push(lg, n);

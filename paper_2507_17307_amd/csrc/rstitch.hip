@@ -69,8 +69,8 @@ const char *check_config(const rs_config *c) {
 }
 
 struct Layout {
-    size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, seq_info, h, xn, qkv_raw, qbuf,
-        attn_out, attn_pl, act, act_pl, attn_part, attn_cnt, lm_pl, lm_parts, sync, layer_ptrs, gemm_part, xn32, lm32, total;
+    size_t rope_cos, rope_sin, row_slot, row_pos, row_bad, out_row, seq_bad, seq_scale, seq_info, h, qkv_raw, qbuf,
+        attn_out, act, attn_part, attn_cnt, lm_parts, sync, layer_ptrs, gemm_part, xn32, lm32, total;
     int attn_rows_x_splits;   // capacity of attn_part in (row, split) pairs
     int lm_parts_cap;         // partial states per sequence
 };
@@ -111,23 +111,18 @@ Layout make_layout(const rs_config &c) {
     L.seq_scale = take(c.max_seqs * 4);
     L.seq_info = take((size_t)c.max_seqs * 16);
     L.h = take((size_t)c.max_rows * c.d_model * 4);
-    L.xn = take((size_t)3 * c.max_rows * c.d_model * 2);
     L.qkv_raw = take((size_t)c.max_rows * qkv * 4);
     L.qbuf = take((size_t)c.max_rows * qdim * 4);
     L.attn_out = take((size_t)c.max_rows * qdim * 4);
-    L.attn_pl = take((size_t)3 * c.max_rows * qdim * 2);
-    // fp32 SwiGLU rows: the FMA kernels' (up to FMA_MAX_ROWS rows) and the tile kernel's (more than 32 rows)
-    L.act = take((size_t)(c.max_rows > 16 ? c.max_rows : (c.max_rows < FMA_MAX_ROWS ? c.max_rows : FMA_MAX_ROWS)) * c.d_ffn * 4);
-    L.act_pl = take((size_t)3 * c.max_rows * c.d_ffn * 2);
+    L.act = take((size_t)c.max_rows * c.d_ffn * 4);                               // fp32 SwiGLU rows
     L.attn_rows_x_splits = attn_pairs_cap(c);
     L.attn_part = take((size_t)L.attn_rows_x_splits * c.n_q_heads * (c.head_dim + 4) * 4);
     L.attn_cnt = take((size_t)c.max_rows * c.n_kv_heads * 4);
-    L.lm_pl = take((size_t)3 * c.max_seqs * c.d_model * 2);
     L.lm_parts_cap = LM_PARTS_CAP;
     L.lm_parts = take((size_t)c.max_seqs * L.lm_parts_cap * sizeof(rs::SoftPartial));
     L.gemm_part = take((size_t)GEMM_KSPLIT_MAX * c.max_rows * (qkv > (size_t)c.d_model ? qkv : (size_t)c.d_model) * 4);
-    L.xn32 = take(c.max_rows > 16 ? (size_t)c.max_rows * c.d_model * 4 : 0);      // normalised rows for the tile kernel
-    L.lm32 = take(c.max_seqs > 16 ? (size_t)c.max_seqs * c.d_model * 4 : 0);
+    L.xn32 = take((size_t)c.max_rows * c.d_model * 4);                            // normalised rows of a multi-row call (fp32)
+    L.lm32 = take((size_t)c.max_seqs * c.d_model * 4);                            // normalised last rows for the LM head
     L.sync = take(2 * sizeof(rs::SyncState));          // [0] single-kernel step, [1] device-resident loop
     L.layer_ptrs = take((size_t)c.n_layers * sizeof(rs::LayerPtrs));
     L.total = o;
@@ -459,15 +454,18 @@ rs_status launch_gemm_tile_rows(const rs_model *m, GemmArgs &a, int n_tiles, hip
     return launch_gemm_tile<MODE, 4, 1>(m, a, n_tiles, st, name);
 }
 
-// Which calls take k_gemm_tile.  Layers: from 24 rows on models at least 2048 wide, from 33 rows on narrower ones.
+// Which calls take k_gemm_tile.  Layers: every call of more than 16 rows.
 // Measured per call against 16- / 32-row blocks with workgroups of their own (k_gemm_rows): 7B shape 24 rows 5.81 -> 5.54
 // ms, 32 rows 6.35 -> 5.75, 64 rows 9.57 -> 6.9, 128 rows 14.9 -> 10.1; 14B 32 rows 14.5 -> 13.8, 64 rows 24.0 -> 18.0, 128
 // rows 44.7 -> 31.3; 32B 128 rows 78.6 -> 55.3; 1.5B shape 33 rows 3.50 -> 2.95, 64 rows 3.68 -> 3.32, 128 rows 5.44 -> 4.82
-// (17-23 rows, 17-32 on the 1.5B shape, are a tie or a loss: two of the four waves hold no rows).
+// From 17 rows on: the 32-row blocks of k_gemm_rows split two blocks' activations per window in every wave and lose
+// against the tile kernel even where two of its four waves hold no rows (7B shape, 17 / 23 rows: 6.16 / 6.27 ms against
+// 5.35 / 5.50; 32B 22.1 / 23.0 against 21.4 / 22.2; 1.5B 2.69 / 2.79 against 2.64 / 2.75; only the 14B shape is 2 %
+// better off there).
 // LM head: more than 16 sequences (16-row blocks with workgroups of their own cost 230 us per block on the 7B shape:
 // 1.85 ms at 128 sequences against 0.47 ms; 1.5B shape 0.86 -> 0.24 ms); one partial per workgroup must fit the buffer
 // even with four column tiles per workgroup.
-bool tile_layers(const rs_config &c, int rows) { return rows >= (c.d_model >= 2048 ? 24 : 33); }
+bool tile_layers(const rs_config &, int rows) { return rows > 16; }
 // ... and only the matrices whose workgroups fill at least 70 % of their rounds of the machine (the 1.5B shape's QKV and
 // O projection have 128 and 96 of them at best: 15.6 and 14.7 us per layer at 128 rows against 12.7 and 11.0 on k_gemm_rows)
 bool tile_fills(const rs_model *m, bool gateup, int n_out, int K) {
@@ -563,7 +561,7 @@ void fill_persist_args(rs_model *m, PersistArgs &p, const int *d_seq_slot, const
     AttnArgs &aa = p.attn;
     aa.qbuf = g.qbuf; aa.kcache = m->kv_k; aa.vcache = m->kv_v;
     aa.partials = m->at<float>(L.attn_part);
-    aa.out = m->at<float>(L.attn_out); aa.out_planes = nullptr; aa.out_plane = 0;
+    aa.out = m->at<float>(L.attn_out);
     aa.row_pos = p.prep.row_pos; aa.row_slot = p.prep.row_slot; aa.row_bad = p.prep.row_bad;
     aa.n_q = c.n_q_heads; aa.n_kv = c.n_kv_heads; aa.max_ctx = c.max_ctx; aa.max_seqs = c.max_seqs;
 
@@ -732,8 +730,6 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         aa.qbuf = m->at<float>(L.qbuf); aa.kcache = m->kv_k; aa.vcache = m->kv_v;
         aa.partials = m->at<float>(L.attn_part);
         aa.out = m->at<float>(L.attn_out);
-        aa.out_planes = single ? nullptr : m->at<uint16_t>(L.attn_pl);
-        aa.out_plane = (size_t)c.max_rows * qdim;
         aa.row_pos = row_pos; aa.row_slot = row_slot; aa.row_bad = row_bad; aa.seq_info = m->at<int4>(L.seq_info);
         aa.n_q = c.n_q_heads; aa.n_kv = c.n_kv_heads; aa.max_ctx = c.max_ctx; aa.max_seqs = c.max_seqs; aa.layer = l;
 
@@ -753,11 +749,8 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             }
             if (rc) return rc;
         } else {
-            uint16_t *xn = m->at<uint16_t>(L.xn);
-            const size_t xn_plane = (size_t)c.max_rows * c.d_model;
             GemmArgs g{};
             g.M = n_rows; g.d_ffn = c.d_ffn;
-            // the tile kernel takes its activations as fp32 rows (it splits them into planes itself)
             const bool t_all = tile_layers(c, n_rows);
             const bool t_qkv = t_all && tile_fills(m, false, qkv_rows, c.d_model), t_o = t_all && tile_fills(m, false, c.d_model, qdim);
             // gate/up hands its output to the down projection in one format: both or neither
@@ -766,10 +759,10 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             g.act32 = m->at<float>(L.act);
             // the down projection of the layer before may have left its result as partial sums (pend_*)
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->attn_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)pend_part, pend_ks, pend_stride, t_qkv ? xn32 : nullptr);
+                               c.d_model, (const int *)nullptr, xn32, (const float *)pend_part, pend_ks, pend_stride);
             RS_LAUNCHED("rmsnorm_rows");
             pend_part = nullptr; pend_ks = 0; pend_stride = 0;
-            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane; g.X32 = xn32;
+            g.W = m->w_qkv[l]; g.N = qkv_rows; g.K = c.d_model; g.X32 = xn32;
             g.out_f32 = m->at<float>(L.qkv_raw); g.ld_out = qkv_rows;
             tic(RS_PHASE_QKV, l);
             if ((rc = launch_gemm<G_QKV>(m, g, (qkv_rows + 15) / 16, st, "gemm_qkv", t_qkv))) return rc;
@@ -792,22 +785,20 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
             toc(RS_PHASE_ATTN, l);
             if (rc) return rc;
             g.W = m->w_o[l]; g.N = c.d_model; g.K = qdim;
-            g.X = m->at<uint16_t>(L.attn_pl); g.x_plane = (size_t)c.max_rows * qdim; g.X32 = m->at<float>(L.attn_out);
+            g.X32 = m->at<float>(L.attn_out);
             g.h_out = h; g.ld_h = c.d_model;
             tic(RS_PHASE_OPROJ, l);
             if ((rc = launch_gemm<G_OPROJ>(m, g, (c.d_model + 15) / 16, st, "gemm_oproj", t_o))) return rc;
             toc(RS_PHASE_OPROJ, l);
             hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_rows), dim3(ROWK_THREADS), 0, st, h, m->mlp_norm[l], c.rms_eps,
-                               c.d_model, (const int *)nullptr, xn, xn_plane, (const float *)g.part,
-                               g.ksplit, g.part_stride, t_mlp ? xn32 : nullptr);
+                               c.d_model, (const int *)nullptr, xn32, (const float *)g.part, g.ksplit, g.part_stride);
             RS_LAUNCHED("rmsnorm_rows");
-            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X = xn; g.x_plane = xn_plane; g.X32 = xn32;
-            g.act = m->at<uint16_t>(L.act_pl); g.act_plane = (size_t)c.max_rows * c.d_ffn;
+            g.W = m->w_gate_up[l]; g.N = 2 * c.d_ffn; g.K = c.d_model; g.X32 = xn32;
             tic(RS_PHASE_GATEUP, l);
             if ((rc = launch_gemm<G_GATEUP>(m, g, (c.d_ffn + 15) / 16, st, "gemm_gateup", t_mlp))) return rc;
             toc(RS_PHASE_GATEUP, l);
             g.W = m->w_down[l]; g.N = c.d_model; g.K = c.d_ffn;
-            g.X = m->at<uint16_t>(L.act_pl); g.x_plane = (size_t)c.max_rows * c.d_ffn; g.X32 = m->at<float>(L.act);
+            g.X32 = m->at<float>(L.act);
             tic(RS_PHASE_DOWN, l);
             if ((rc = launch_gemm<G_DOWN>(m, g, (c.d_model + 15) / 16, st, "gemm_down", t_mlp))) return rc;
             toc(RS_PHASE_DOWN, l);
@@ -833,14 +824,12 @@ rs_status forward_kernels(rs_model *m, int n_seqs, int n_rows, const int *d_seq_
         toc(RS_PHASE_LMHEAD, 0);
         if (rc) return rc;
     } else {
-        uint16_t *lm_pl = m->at<uint16_t>(L.lm_pl);
-        const size_t lm_plane = (size_t)c.max_seqs * c.d_model;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seqs), dim3(ROWK_THREADS), 0, st, h, m->final_norm, c.rms_eps,
-                           c.d_model, (const int *)m->at<int>(L.out_row), lm_pl, lm_plane, (const float *)pend_part, pend_ks, pend_stride,
-                           tile_lm_head(c, n_seqs) ? m->at<float>(L.lm32) : (float *)nullptr);
+                           c.d_model, (const int *)m->at<int>(L.out_row), m->at<float>(L.lm32), (const float *)pend_part, pend_ks,
+                           pend_stride);
         RS_LAUNCHED("rmsnorm_rows");
         GemmArgs g{};
-        g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X = lm_pl; g.x_plane = lm_plane; g.X32 = m->at<float>(L.lm32);
+        g.M = n_seqs; g.W = m->lm_head; g.N = c.vocab; g.K = c.d_model; g.X32 = m->at<float>(L.lm32);
         g.seq_scale = m->at<float>(L.seq_scale); g.parts = parts; g.logits = d_logits;
         g.sample_on = m->sample_on; g.sample_key = m->sample_key; g.row_pos = row_pos; g.out_row = m->at<int>(L.out_row);
         tic(RS_PHASE_LMHEAD, 0);
