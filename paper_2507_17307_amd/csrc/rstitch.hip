@@ -256,9 +256,10 @@ rs_status launch_attn(AttnArgs &a, int n_splits, int n_kv, int n_rows, int n_seq
         // time and a two-row call on eight KV heads at 5000 positions took 17.5 us instead of ~7
         const int rp = 16 / (a.n_q / n_kv);
         const long base = (long)n_splits * n_kv * n_seqs;
-        if (n_splits * ATT_BT >= a.max_ctx && (n_rows >= 3 || base <= n_cu)) {
+        if (n_splits * ATT_BT >= a.max_ctx && (n_rows >= 5 || base <= n_cu)) {
             // every slice is one 64-position pass: one workgroup per (slice, KV head, sequence), K/V tile through LDS
-            // (two-row calls with more workgroups than CUs stay on the kernel below: 7B shape 7.6 us against 9.6).
+            // (calls of two to four rows with more workgroups than CUs stay on the kernel below: 7B shape, two rows 7.6 us
+            // against 9.6; per call, three rows: 7B 3.588 -> 3.577 ms, 14B 7.57 -> 7.19; from five rows on it loses).
             // Measured per call, 7B shape: 5 rows 3.91 -> 3.84 ms, 16 rows 5.03 -> 4.83, 64 rows 10.26 -> 9.61; 1.5B shape: 8 rows
             // 1.92 -> 1.82, 16 rows 2.43 -> 2.19.
             // A sequence's row slots are dealt to ZS workgroups where that shortens the busiest CU's queue: cost in slot
