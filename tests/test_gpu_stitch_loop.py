@@ -11,7 +11,12 @@ import torch
 import workloads as W
 from test_gpu_model import pair_run
 
-pytestmark = pytest.mark.gpu
+import os
+
+# (a process that launched a cooperative kernel under rocprofv3's kernel trace was seen to crash inside the profiler's
+# exit handler, after its work was done: these tests stay out of profiled runs)
+_profiled = any("rocprofiler" in os.environ.get(k, "") for k in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES", "HSA_TOOLS_LIB"))
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(_profiled, reason="cooperative launches are kept out of rocprofv3 runs")]
 
 
 @pytest.fixture(scope="module")
