@@ -446,12 +446,19 @@ rs_status launch_gemm_tile(const rs_model *m, GemmArgs &a, int n_tiles, hipStrea
     }
 }
 
-// wave arrangement by row count: four waves of 16 rows up to 64 rows, eight up to 128.  Eight waves that share row
-// blocks and split the column tiles (k_gemm_tile's CS > 1) measured slower at 24-64 rows (7B shape, 64 rows: 7.8 ms
-// per call against 7.0; every wave of a row block fetches that block's X pieces again)
+// wave arrangement by row count: four waves of 16 rows up to 64 rows, eight up to 128.  Up to 32 rows two of the four
+// waves would hold no rows: there two waves share each row block and split the workgroup's column tiles (k_gemm_tile's
+// CS = 2; per call at 17 / 24 / 32 rows: 7B shape 5.41 / 5.53 / 5.76 -> 4.98 / 5.15 / 5.46 ms, 14B 12.2 / 12.8 / 13.8 ->
+// 11.0 / 11.8 / 13.0, 1.5B 2.65 / 2.71 / 2.85 -> 2.56 / 2.65 / 2.82); not the LM head, whose partial states are counted
+// per workgroup.  The same split with eight waves measured slower at 64 rows (7B shape: 7.8 ms per call against 7.0;
+// every wave of a row block fetches that block's X pieces again), and four waves on one row block lose against
+// k_gemm_rows (7B shape, 16 rows: 4.83 against 4.26 ms)
 template <int MODE>
 rs_status launch_gemm_tile_rows(const rs_model *m, GemmArgs &a, int n_tiles, hipStream_t st, const char *name) {
     if (a.M > 64) return launch_gemm_tile<MODE, 8, 1>(m, a, n_tiles, st, name);
+    if constexpr (MODE != G_LMHEAD) {
+        if (a.M <= 32) return launch_gemm_tile<MODE, 4, 2>(m, a, n_tiles, st, name);
+    }
     return launch_gemm_tile<MODE, 4, 1>(m, a, n_tiles, st, name);
 }
 

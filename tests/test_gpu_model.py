@@ -118,15 +118,15 @@ def test_batched_ragged_calls_match_per_sequence_oracle(spans, decode_path):
         check_invocation(got[i], lg[i], ref, 0.7, router.SLM, where=f"decode seq {i}")
 
 
-TILE_CASES = [("one_span_24", [24]), ("two_spans_31", [11, 20]), ("one_span_33", [33]), ("one_span_64", [64]), ("one_span_100", [100]), ("two_spans_128", [59, 69]),
+TILE_CASES = [("one_span_17", [17]), ("one_span_24", [24]), ("two_spans_31", [11, 20]), ("decode_32", [1] * 32), ("one_span_33", [33]), ("one_span_64", [64]), ("one_span_100", [100]), ("two_spans_128", [59, 69]),
               ("ragged_20_seqs_90_rows", [1, 9, 2, 7, 3, 8, 4, 6, 5, 5, 1, 9, 2, 7, 3, 8, 4, 2, 3, 1]), ("decode_128", [1] * 128)]
 
 
 @pytest.mark.parametrize("name,spans", TILE_CASES, ids=[c[0] for c in TILE_CASES])
-def test_calls_of_24_to_128_rows_on_a_2048_wide_shape_match_the_oracle(name, spans):
-    """Calls of 24 rows and more on a model at least 2048 wide take the kernel in which one workgroup holds all rows of
-    the call against a block of output columns (one or two blocks of 16 rows per wave, K split over workgroups for
-    QKV / O-proj / down) for every matrix whose workgroups fill the machine: here QKV (192 tiles), gate/up (640 tiles in
+def test_calls_of_17_to_128_rows_on_a_2048_wide_shape_match_the_oracle(name, spans):
+    """Calls of more than 16 rows take the kernel in which one workgroup holds all rows of the call against a block of
+    output columns (up to 32 rows: two waves per 16-row block, each with half of the column tiles; up to 64: four waves of 16
+    rows; above: eight; K split over workgroups for QKV / O-proj / down) for every matrix whose workgroups fill the machine: here QKV (192 tiles), gate/up (640 tiles in
     groups of three: a ragged last group) and down (128 tiles, 160 k windows split over eight workgroups); the O projection
     (128 tiles, 32 windows) stays on the 32-row-block kernel, so both activation formats are in play in one call."""
     import paper_2507_17307_amd as P
