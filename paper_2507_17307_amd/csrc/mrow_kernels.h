@@ -571,19 +571,34 @@ __global__ void __launch_bounds__(NW * 64) k_gemm_tile(GemmArgs a) {
     float4 xb[XD][SW][TB][NS][2];
 #pragma unroll
     for (int v = 0; v < WD; ++v) request_w(s_lo + v, wr[v]);
-#pragma unroll
-    for (int v = 0; v < XD - 1; ++v) request_x(s_lo + v, xb[v]);
     int buf = 0;
-    for (int st = s_lo; st < s_hi; st += UNR) {
+    if (rb * TB * 16 < a.M) {
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            if (st + u >= s_hi) break;
-            park(buf, wr[u % WD]);
-            lds_barrier();                                    // the step is in LDS; everybody is done with the other buffer's last use
-            request_w(st + u + WD, wr[u % WD]);
-            request_x(st + u + XD - 1, xb[(u + XD - 1) % XD]);
-            multiply(buf, xb[u % XD]);
-            buf ^= 1;
+        for (int v = 0; v < XD - 1; ++v) request_x(s_lo + v, xb[v]);
+        for (int st = s_lo; st < s_hi; st += UNR) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                if (st + u >= s_hi) break;
+                park(buf, wr[u % WD]);
+                lds_barrier();                                // the step is in LDS; everybody is done with the other buffer's last use
+                request_w(st + u + WD, wr[u % WD]);
+                request_x(st + u + XD - 1, xb[(u + XD - 1) % XD]);
+                multiply(buf, xb[u % XD]);
+                buf ^= 1;
+            }
+        }
+    } else {
+        // a wave whose 16-row block lies past the call's rows only helps to fetch and park W: same steps, same barriers,
+        // no activation requests and no products (they would take load-path and matrix-core time from the waves with rows)
+        for (int st = s_lo; st < s_hi; st += WD) {
+#pragma unroll
+            for (int u = 0; u < WD; ++u) {
+                if (st + u >= s_hi) break;
+                park(buf, wr[u]);
+                lds_barrier();
+                request_w(st + u + WD, wr[u]);
+                buf ^= 1;
+            }
         }
     }
 
